@@ -1,0 +1,175 @@
+/*
+ * ee_decode.h -- C ABI of the early-exit decode step for MI355X (gfx950).
+ *
+ * One call of ee_decode_iteration is one iteration of the paper's Algorithm 1
+ * ("Iteration-level Batch Inference for Early-exit LLMs"): one new token for every
+ * sequence of a batch, with the per-sequence sticky exit status of Section 3.1, the
+ * whole-batch break at output_layer, and the KV-cache filling of Section 3.2.  The
+ * other entry points expose the steps of that iteration one by one.
+ *
+ * Conventions
+ *   - "dev" pointers are DEVICE pointers owned by the caller; the library borrows
+ *     them for the duration of the enqueued work and never frees them.  "host"
+ *     pointers are read before the call returns.
+ *   - Every call only ENQUEUES work on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and returns without synchronising.  Outputs are
+ *     valid once the caller has synchronised the stream.  No call allocates or
+ *     frees device memory; scratch space comes in through `workspace`.
+ *   - Layers are 1-based in every argument and output, as in Algorithm 1.
+ *   - Return value: EE_OK, or a negative error code.  Arguments are validated on
+ *     the host before anything is launched; on error nothing has been enqueued.
+ *     ee_last_error() returns a thread-local message for the last failing call.
+ *     Data errors that only the device can see (a block id >= num_blocks, a token
+ *     id >= vocab) are the caller's contract.
+ *   - dtype EE_FP32: weights, activations and KV cache are float; matrices are plain
+ *     row-major [out_features][in_features].
+ *     dtype EE_BF16: weights, embedding, gains and KV cache are bfloat16; matrices
+ *     are in the MFMA tile order written by ee_pack_weight.  The residual stream,
+ *     q, softmax statistics, logits and confidences are float in both cases.
+ */
+#ifndef EE_DECODE_H
+#define EE_DECODE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define EE_OK 0
+#define EE_ERR_INVALID_ARG (-1)  /* null pointer, non-positive size, bad enum          */
+#define EE_ERR_SHAPE (-2)        /* sizes inconsistent with each other                 */
+#define EE_ERR_UNSUPPORTED (-3)  /* a shape or mode this build has no kernel for       */
+#define EE_ERR_WORKSPACE (-4)    /* workspace too small or misaligned                  */
+#define EE_ERR_HIP (-5)          /* a HIP call failed (message in ee_last_error)       */
+
+#define EE_FP32 0
+#define EE_BF16 1
+
+/* Row orders understood by ee_pack_weight. */
+#define EE_PACK_PLAIN 0    /* w_o, w_down, w_lm                                           */
+#define EE_PACK_QKV 1      /* w_qkv : rotary partners (j, j + head_dim/2) share a tile    */
+#define EE_PACK_GATE_UP 2  /* w_gate_up : gate row f and up row f share a tile            */
+
+#define EE_MAX_LAYERS 64
+
+typedef struct ee_model_desc {
+  int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab; /* d_model == n_heads * head_dim */
+  int32_t dtype;       /* EE_FP32 | EE_BF16                                                        */
+  float rms_eps;       /* RMSNorm epsilon                                                          */
+  float rope_theta;    /* rotary base; <= 0 disables the rotary embedding                         */
+  int32_t exit_every;  /* exit head after layers i with i % exit_every == 0 and i < n_layers       */
+  float logit_scale;   /* s: exit-head logits at layer i are multiplied by s * i                   */
+  int32_t conf_mode;   /* 0: largest softmax probability; 1: top-1 minus top-2 probability, the
+                          softmax-response measure of the paper's Section 2.1                      */
+} ee_model_desc;
+
+/* Weights of one decoder layer (all dev).  Plain shapes: g_attn,g_ffn [d]; w_qkv [3d][d] (q rows, then
+ * k rows, then v rows); w_o [d][d]; w_gate_up [2f][d] (gate rows, then up rows); w_down [d][f].
+ * For EE_BF16 the matrices are the ee_pack_weight images of those plain matrices. */
+typedef struct ee_layer_weights {
+  const void *g_attn, *w_qkv, *w_o, *g_ffn, *w_gate_up, *w_down;
+} ee_layer_weights;
+
+typedef struct ee_model {
+  ee_model_desc desc;
+  const void* embed;              /* dev [vocab][d], plain row-major in the model dtype            */
+  const void* g_final;            /* dev [d]; final RMSNorm gain, shared by every exit head        */
+  const void* w_lm;               /* dev [vocab][d]; LM head (packed PLAIN for EE_BF16), shared by
+                                     every exit head and by the final token selection              */
+  const ee_layer_weights* layers; /* host array [n_layers]                                         */
+} ee_model;
+
+/* Paged KV cache (the block-virtualised cache the paper inherits, Section 2.2 / 3.2).
+ * k_pool and v_pool: dev [n_layers][num_blocks][n_heads][block_size][head_dim] in the model dtype.
+ * block_size must be 16.  Position p of sequence b lives in block block_tables[b][p / 16] at offset p % 16. */
+typedef struct ee_kv_cache {
+  void* k_pool;
+  void* v_pool;
+  int32_t num_blocks, block_size;
+} ee_kv_cache;
+
+/* One batch of sequences, one token each.  The block allocator is the caller's: the library only
+ * dereferences block_tables, and writes position context_lens[b] of sequence b (whose block must exist). */
+typedef struct ee_batch {
+  int32_t batch;               /* B >= 0; B == 0 is a no-op that still returns EE_OK                     */
+  const int32_t* tokens;       /* dev [B]: token each sequence consumes this iteration                   */
+  const int32_t* context_lens; /* dev [B]: p_b = positions already cached; the new K/V go to position p_b */
+  const int32_t* block_tables; /* dev [B][max_blocks]: physical block of each logical block              */
+  int32_t max_blocks;          /* row pitch of block_tables                                              */
+  int32_t max_context;         /* host-side upper bound of context_lens[b] + 1 (sizes the attention grid) */
+} ee_batch;
+
+const char* ee_last_error(void);
+
+/* Number of bytes ee_pack_weight writes for an [n_out][n_in] matrix (EE_BF16 only). */
+size_t ee_packed_weight_bytes(int32_t n_out, int32_t n_in);
+
+/* Reorders a plain bf16 matrix w [n_out][n_in] (dev) into the tile order the MFMA kernels stream:
+ * tiles of 32 output rows x 16 input columns, stored [row_tile][col_tile][lane 0..63][8 values], so that a
+ * wavefront fetches one operand tile as 1 KiB of consecutive bytes.  `order` (EE_PACK_*) says which output
+ * rows share a tile; pair_stride is head_dim/2 for EE_PACK_QKV, d_ffn for EE_PACK_GATE_UP, ignored for PLAIN.
+ * n_out must be a multiple of 32, n_in of 16, pair_stride of 16.  A set-up step, not part of the decode step. */
+int ee_pack_weight(const void* w /*dev*/, int32_t n_out, int32_t n_in, int32_t order, int32_t pair_stride,
+                   void* packed /*dev*/, void* stream);
+
+/* Scratch bytes the calls below need for batches up to max_batch and contexts up to max_context.
+ * The workspace must be 256-byte aligned.  Its contents need no initialisation and are dead between calls. */
+size_t ee_workspace_bytes(const ee_model_desc* desc, int32_t max_batch, int32_t max_context);
+
+/* One decode iteration: Algorithm 1 of the paper.
+ *   embed the batch's tokens; for layer i = 1..n run the layer over the whole batch (caching this position's
+ *   K/V of layer i), evaluate the exit head on every sequence whose status is still false, OR the result into
+ *   the status (sticky), and stop at the first layer where every status is true (output_layer); fill K/V of
+ *   this position for layers output_layer+1..n from the hidden state at output_layer (Section 3.2); pick the
+ *   greedy token of every sequence from that hidden state.
+ * The layer loop is enqueued once: a device-side flag makes the kernels of the layers after output_layer
+ * return at once, so there is no host round trip inside the iteration.
+ *   thresholds        host [n_layers]: lambda_i; accepted means confidence > lambda_i (strict).
+ *   forced_exit_layer dev [B] or NULL: synthetic confidence injection; the decision of sequence b at layer i
+ *                     becomes (i >= forced_exit_layer[b]) while the exit-head arithmetic still runs.
+ *   use_exit_heads    0 = full-layer baseline: no exit head is evaluated, output_layer = n.
+ *   out_tokens        dev [B] int32: greedy token (lowest index on ties).
+ *   out_exit_layer    dev [B] int32: first layer whose check accepted the sequence, n_layers if none.
+ *   out_batch_exit_layer dev [1] int32: output_layer.
+ *   out_conf          dev [n_layers][B] float or NULL: confidence evaluated at each layer; NaN where no check
+ *                     was made (no head, sequence already accepted, layer not run).
+ *   out_hidden        dev [B][d] float or NULL: hidden state at output_layer (what the tokens come from). */
+int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const ee_batch* batch,
+                        const float* thresholds, const int32_t* forced_exit_layer, int32_t use_exit_heads,
+                        int32_t* out_tokens, int32_t* out_exit_layer, int32_t* out_batch_exit_layer,
+                        float* out_conf, float* out_hidden, void* workspace, size_t workspace_bytes, void* stream);
+
+/* The exit check of one layer (Section 3.1 status rule with the softmax-response confidence of Section 2.1):
+ * z = (logit_scale * layer) * (RMSNorm(hidden; g_final) . W_lm^T); confidence per conf_mode; a sequence whose
+ * status is 0 and whose confidence exceeds `threshold` gets status 1 and exit_layer = layer; statuses never
+ * revert.  n_exited counts the sequences with status 1; done_flag is set to 1 (and batch_exit_layer to `layer`)
+ * when it reaches `batch`, and is left alone otherwise.
+ *   hidden dev [B][d] float.  status, exit_layer dev [B] int32 in/out.  n_exited, done_flag, batch_exit_layer
+ *   dev [1] int32 in/out.  argmax dev [B] int32 or NULL (arg max of the logits, every row).  conf dev [B] float
+ *   or NULL (NaN for rows whose status was already 1).  forced_exit_layer as above. */
+int ee_exit_check(const ee_model* model, int32_t layer, const float* hidden, int32_t batch, float threshold,
+                  const int32_t* forced_exit_layer, int32_t* status, int32_t* exit_layer, int32_t* n_exited,
+                  int32_t* done_flag, int32_t* batch_exit_layer, int32_t* argmax, float* conf, void* workspace,
+                  size_t workspace_bytes, void* stream);
+
+/* KV-cache filling (Algorithm 1's second loop, Section 3.2): for every sequence b and every layer
+ * i > fill_from_layer[b], K = RoPE(RMSNorm(hidden_b; g_attn_i) . Wk_i^T, p_b), V = RMSNorm(..) . Wv_i^T, written to
+ * position p_b = context_lens[b] of layer i.  The paper's rule passes the same output_layer for every b.
+ *   hidden dev [B][d] float; fill_from_layer dev [B] int32.  batch->tokens is not read. */
+int ee_kv_fill(const ee_model* model, const ee_kv_cache* cache, const ee_batch* batch, const float* hidden,
+               const int32_t* fill_from_layer, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Single-query attention over the paged cache of one layer (the attention inside Algorithm 1's M(i, ...)):
+ * out[b][h] = softmax_j(q[b][h] . K[b][j][h] / sqrt(head_dim)) . V[b][j][h], j = 0..context_lens[b] INCLUSIVE: the new
+ * token's K/V must already be in the cache.   q dev [B][H][dh] float, rotary embedding applied.
+ * out dev [B][H][dh] float.  batch->tokens is not read. */
+int ee_paged_attention_decode(const ee_model_desc* desc, const ee_kv_cache* cache, int32_t layer, const float* q,
+                              const ee_batch* batch, float* out, void* workspace, size_t workspace_bytes,
+                              void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* EE_DECODE_H */

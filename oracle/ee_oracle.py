@@ -264,19 +264,24 @@ def decode_iteration(m: OracleModel, cache: DenseKV, tokens: torch.Tensor, pos: 
     return out, torch.tensor(exit_layer, dtype=torch.int32), output_layer
 
 
-def prefill(m: OracleModel, cache: DenseKV, prompts: torch.Tensor, lens: torch.Tensor) -> torch.Tensor:
+def prefill(m: OracleModel, cache: DenseKV, prompts: torch.Tensor, lens: torch.Tensor,
+            last_hidden: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Teacher-forced prompt pass through the decode step with no exit heads (full layers): position t
     of every sequence that is at least t+1 long.  Returns the first generated token of each sequence
-    (the prediction after its last prompt token).  Sequences shorter than the longest simply stop early."""
+    (the prediction after its last prompt token).  Sequences shorter than the longest simply stop early.
+    last_hidden [B][d] float64, if given, receives the final hidden state each first token came from."""
     B, P = prompts.shape
     first = torch.zeros(B, dtype=torch.int32)
     for t in range(int(lens.max()) if B else 0):
         rows = [b for b in range(B) if int(lens[b]) > t]
         sub = _RowView(cache, rows)
-        tok, _, _ = decode_iteration(m, sub, prompts[rows, t], torch.full((len(rows),), t), 2.0, heads=False)
+        tr = {}
+        tok, _, _ = decode_iteration(m, sub, prompts[rows, t], torch.full((len(rows),), t), 2.0, heads=False, trace=tr)
         for r, b in enumerate(rows):
             if int(lens[b]) == t + 1:
                 first[b] = tok[r]
+                if last_hidden is not None:
+                    last_hidden[b] = tr["h_exit"][r]
     return first
 
 

@@ -1,0 +1,460 @@
+// C ABI of the early-exit decode step: argument validation, workspace carving, kernel sequencing.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "ee_common.h"
+
+namespace ee {
+
+static thread_local char g_error[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_error, sizeof(g_error), fmt, ap);
+  va_end(ap);
+}
+
+namespace {
+
+struct Carver {
+  char* base;
+  size_t off;
+  template <class T>
+  T* take(size_t count) {
+    off = (off + 255) & ~(size_t)255;
+    T* p = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += count * sizeof(T);
+    return p;
+  }
+};
+
+struct Workspace {
+  // shared
+  int32_t *status, *n_exited, *done, *scratch_exit_layer, *scratch_L;
+  float* q;           // [B][d]
+  float4* partials;   // bf16: [Mpad][vocab/32]; fp32: [B]
+  // bf16 path
+  float* hT;          // [d][Mpad]
+  bf16_t* xT;         // [Mpad][d]
+  bf16_t* aoT;        // [Mpad][d]
+  bf16_t* actT;       // [Mpad][f]
+  float* rowsq;       // [2n + 2][Mpad]: sum of squares of the residual rows after the embedding / each update
+  bf16_t* fill_x;     // [n][Mpad][d]
+  // fp32 path
+  float *h, *x, *ao, *act, *logits;
+  size_t bytes;
+};
+
+Workspace carve(const ee_model_desc& D, int B, void* base) {
+  Workspace w{};
+  Carver c{reinterpret_cast<char*>(base), 0};
+  const int Bp = B < 1 ? 1 : B;
+  const int Mpad = round_up(Bp, 32);
+  const size_t d = D.d_model, f = D.d_ffn, V = D.vocab, n = D.n_layers;
+  w.status = c.take<int32_t>(Bp);
+  w.n_exited = c.take<int32_t>(1);
+  w.done = c.take<int32_t>(1);
+  w.scratch_exit_layer = c.take<int32_t>(Bp);
+  w.scratch_L = c.take<int32_t>(1);
+  w.q = c.take<float>(Bp * d);
+  if (D.dtype == EE_BF16) {
+    w.partials = c.take<float4>((size_t)Mpad * (V / 32));
+    w.hT = c.take<float>(d * Mpad);
+    w.xT = c.take<bf16_t>(d * Mpad);
+    w.aoT = c.take<bf16_t>(d * Mpad);
+    w.actT = c.take<bf16_t>(f * Mpad);
+    w.rowsq = c.take<float>((2 * n + 2) * Mpad);
+    w.fill_x = c.take<bf16_t>(n * Mpad * d);
+  } else {
+    w.partials = c.take<float4>(Bp);
+    w.h = c.take<float>(Bp * d);
+    w.x = c.take<float>(Bp * d);
+    w.ao = c.take<float>(Bp * d);
+    w.act = c.take<float>(Bp * f);
+    w.logits = c.take<float>(Bp * V);
+  }
+  w.bytes = (c.off + 255) & ~(size_t)255;
+  return w;
+}
+
+int check_desc(const ee_model_desc* D) {
+  if (!D) EE_FAIL(EE_ERR_INVALID_ARG, "model description is NULL");
+  if (D->n_layers < 1 || D->d_model < 1 || D->n_heads < 1 || D->head_dim < 1 || D->d_ffn < 1 || D->vocab < 1)
+    EE_FAIL(EE_ERR_INVALID_ARG, "model sizes must be positive");
+  if (D->n_layers > EE_MAX_LAYERS) EE_FAIL(EE_ERR_UNSUPPORTED, "n_layers %d exceeds %d", D->n_layers, EE_MAX_LAYERS);
+  if (D->dtype != EE_FP32 && D->dtype != EE_BF16) EE_FAIL(EE_ERR_INVALID_ARG, "dtype must be EE_FP32 or EE_BF16");
+  if (D->d_model != D->n_heads * D->head_dim)
+    EE_FAIL(EE_ERR_SHAPE, "d_model %d != n_heads %d * head_dim %d", D->d_model, D->n_heads, D->head_dim);
+  if (D->head_dim != 64 && D->head_dim != 128) EE_FAIL(EE_ERR_UNSUPPORTED, "head_dim %d: only 64 and 128", D->head_dim);
+  if (D->exit_every < 1) EE_FAIL(EE_ERR_INVALID_ARG, "exit_every must be >= 1");
+  if (D->conf_mode != 0 && D->conf_mode != 1) EE_FAIL(EE_ERR_INVALID_ARG, "conf_mode must be 0 or 1");
+  if (!(D->logit_scale >= 0.0f)) EE_FAIL(EE_ERR_INVALID_ARG, "logit_scale must be >= 0");
+  if (!(D->rms_eps >= 0.0f)) EE_FAIL(EE_ERR_INVALID_ARG, "rms_eps must be >= 0");
+  if (D->vocab % 2) EE_FAIL(EE_ERR_UNSUPPORTED, "vocab must be even");
+  if (D->dtype == EE_BF16) {
+    if (D->d_model % 64 || D->d_ffn % 16 || D->vocab % 32)
+      EE_FAIL(EE_ERR_UNSUPPORTED, "bf16 path needs d_model %% 64 == 0, d_ffn %% 16 == 0, vocab %% 32 == 0");
+  }
+  return EE_OK;
+}
+
+int check_model(const ee_model* M) {
+  if (!M) EE_FAIL(EE_ERR_INVALID_ARG, "model is NULL");
+  int rc = check_desc(&M->desc);
+  if (rc) return rc;
+  if (!M->embed || !M->g_final || !M->w_lm || !M->layers) EE_FAIL(EE_ERR_INVALID_ARG, "model has a NULL weight pointer");
+  for (int i = 0; i < M->desc.n_layers; ++i) {
+    const ee_layer_weights& L = M->layers[i];
+    if (!L.g_attn || !L.w_qkv || !L.w_o || !L.g_ffn || !L.w_gate_up || !L.w_down)
+      EE_FAIL(EE_ERR_INVALID_ARG, "layer %d has a NULL weight pointer", i + 1);
+  }
+  return EE_OK;
+}
+
+int check_cache(const ee_kv_cache* C) {
+  if (!C || !C->k_pool || !C->v_pool) EE_FAIL(EE_ERR_INVALID_ARG, "KV cache or one of its pools is NULL");
+  if (C->block_size != 16) EE_FAIL(EE_ERR_UNSUPPORTED, "block_size %d: only 16", C->block_size);
+  if (C->num_blocks < 1) EE_FAIL(EE_ERR_INVALID_ARG, "num_blocks must be positive");
+  return EE_OK;
+}
+
+int check_batch(const ee_batch* Bt, bool need_tokens) {
+  if (!Bt) EE_FAIL(EE_ERR_INVALID_ARG, "batch is NULL");
+  if (Bt->batch < 0) EE_FAIL(EE_ERR_INVALID_ARG, "batch size %d is negative", Bt->batch);
+  if (Bt->batch == 0) return EE_OK;
+  if ((need_tokens && !Bt->tokens) || !Bt->context_lens || !Bt->block_tables)
+    EE_FAIL(EE_ERR_INVALID_ARG, "batch has a NULL pointer");
+  if (Bt->max_blocks < 1) EE_FAIL(EE_ERR_INVALID_ARG, "max_blocks must be positive");
+  if (Bt->max_context < 1 || Bt->max_context > Bt->max_blocks * 16)
+    EE_FAIL(EE_ERR_SHAPE, "max_context %d does not fit max_blocks %d * 16", Bt->max_context, Bt->max_blocks);
+  return EE_OK;
+}
+
+int check_workspace(const ee_model_desc& D, int B, void* ws, size_t ws_bytes) {
+  if (!ws) EE_FAIL(EE_ERR_WORKSPACE, "workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(ws) & 255) EE_FAIL(EE_ERR_WORKSPACE, "workspace is not 256-byte aligned");
+  const size_t need = carve(D, B, nullptr).bytes;
+  if (ws_bytes < need) EE_FAIL(EE_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", ws_bytes, need);
+  return EE_OK;
+}
+
+bool has_head(const ee_model_desc& D, int i) { return i < D.n_layers && i % D.exit_every == 0; }
+
+int acc_ksplit(int n_tiles, int K) {
+  const int k_steps = K / 16;
+  int s = 1024 / n_tiles;
+  if (s > k_steps / 64) s = k_steps / 64;
+  return s < 1 ? 1 : s;
+}
+
+size_t pool_layer_elems(const ee_model_desc& D, const ee_kv_cache& C) {
+  return (size_t)C.num_blocks * D.n_heads * 16 * D.head_dim;
+}
+size_t elem_bytes(const ee_model_desc& D) { return D.dtype == EE_BF16 ? 2 : 4; }
+
+QkvEpi make_qkv_epi(const ee_model_desc& D, const ee_kv_cache& C, const ee_batch& Bt, int layer, float* q,
+                    const float* rowsq) {
+  QkvEpi e{};
+  e.q = q;
+  const size_t lb = pool_layer_elems(D, C) * elem_bytes(D) * (size_t)(layer - 1);
+  e.k_pool = reinterpret_cast<char*>(C.k_pool) + lb;
+  e.v_pool = reinterpret_cast<char*>(C.v_pool) + lb;
+  e.context_lens = Bt.context_lens;
+  e.block_tables = Bt.block_tables;
+  e.fill_from = nullptr;
+  e.fill_from_stride = 0;
+  e.layer = layer;
+  e.max_blocks = Bt.max_blocks;
+  e.n_heads = D.n_heads;
+  e.head_dim = D.head_dim;
+  e.d_model = D.d_model;
+  e.rope_theta = D.rope_theta;
+  e.rowsq = rowsq;
+  e.eps = D.rms_eps;
+  return e;
+}
+
+// --- exit head: statistics of (scale * logits) for every row of the hidden state ------------------------
+void enqueue_head_bf16(const ee_model& M, const Workspace& w, int B, int Mpad, float scale, const float* rowsq_slot,
+                       Pred pred, hipStream_t st) {
+  const ee_model_desc& D = M.desc;
+  launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(M.g_final), w.xT, rowsq_slot, D.rms_eps, Mpad, D.d_model, pred, st);
+  GemmShape g{M.w_lm, w.xT, D.d_model, B, 0, D.vocab / 32, 16, 1};
+  LmEpi e{w.partials, nullptr, D.vocab / 32, D.vocab, scale, nullptr, D.rms_eps, D.d_model};
+  launch_gemm_lm_bf16(g, e, pred, st);
+}
+void enqueue_head_f32(const ee_model& M, const Workspace& w, const float* h, int B, float scale, Pred pred, hipStream_t st) {
+  const ee_model_desc& D = M.desc;
+  launch_rmsnorm_f32(h, reinterpret_cast<const float*>(M.g_final), w.x, B, D.d_model, D.rms_eps, pred, st);
+  SimpleShape g{reinterpret_cast<const float*>(M.w_lm), w.x, D.d_model, B, 0, D.vocab, 1};
+  LmEpi e{w.partials, w.logits, 1, D.vocab, scale, nullptr, D.rms_eps, D.d_model};
+  launch_simple_lm(g, e, pred, st);
+  launch_head_stats_f32(w.logits, w.partials, B, D.vocab, scale, pred, st);
+}
+
+// --- KV filling for layers above fill_from ----------------------------------------------------------------
+void enqueue_fill_bf16(const ee_model& M, const ee_kv_cache& C, const ee_batch& Bt, const Workspace& w, int Mpad,
+                       const int32_t* fill_from, int stride, float* rowsq_slot, Pred pred, hipStream_t st) {
+  const ee_model_desc& D = M.desc;
+  GainTable gt{};
+  FillLayers fl{};
+  for (int i = 0; i < D.n_layers; ++i) {
+    gt.g[i] = M.layers[i].g_attn;
+    fl.w_qkv[i] = M.layers[i].w_qkv;
+  }
+  launch_rowsq(w.hT, rowsq_slot, Mpad, D.d_model, pred, st);
+  launch_prep_x_layers(w.hT, gt, D.n_layers, w.fill_x, rowsq_slot, D.rms_eps, fill_from, stride, Bt.batch, Mpad, D.d_model,
+                       pred, st);
+  GemmShape g{nullptr, nullptr, D.d_model, Bt.batch, D.d_model / 32, 2 * D.d_model / 32, D.head_dim / 2, 1};
+  QkvEpi e = make_qkv_epi(D, C, Bt, 1, nullptr, nullptr);
+  e.fill_from = fill_from;
+  e.fill_from_stride = stride;
+  launch_gemm_kvfill_bf16(fl, D.n_layers, w.fill_x, (size_t)Mpad * D.d_model, pool_layer_elems(D, C), g, e, pred, st);
+}
+void enqueue_fill_f32(const ee_model& M, const ee_kv_cache& C, const ee_batch& Bt, const Workspace& w, const float* h,
+                      const int32_t* fill_from, int stride, Pred pred, hipStream_t st) {
+  const ee_model_desc& D = M.desc;
+  for (int i = 1; i <= D.n_layers; ++i) {
+    const ee_layer_weights& L = M.layers[i - 1];
+    launch_rmsnorm_f32(h, reinterpret_cast<const float*>(L.g_attn), w.x, Bt.batch, D.d_model, D.rms_eps, pred, st);
+    SimpleShape g{reinterpret_cast<const float*>(L.w_qkv), w.x, D.d_model, Bt.batch, D.d_model, 2 * D.d_model,
+                  D.head_dim / 2};
+    QkvEpi e = make_qkv_epi(D, C, Bt, i, nullptr, nullptr);
+    e.fill_from = fill_from;
+    e.fill_from_stride = stride;
+    launch_simple_qkv(g, e, pred, st);
+  }
+}
+
+}  // namespace
+}  // namespace ee
+
+using namespace ee;
+
+extern "C" {
+
+const char* ee_last_error(void) { return g_error; }
+
+size_t ee_packed_weight_bytes(int32_t n_out, int32_t n_in) {
+  if (n_out <= 0 || n_in <= 0) return 0;
+  return (size_t)n_out * (size_t)n_in * sizeof(bf16_t);
+}
+
+int ee_pack_weight(const void* w, int32_t n_out, int32_t n_in, int32_t order, int32_t pair_stride, void* packed,
+                   void* stream) {
+  if (!w || !packed) EE_FAIL(EE_ERR_INVALID_ARG, "ee_pack_weight: NULL pointer");
+  if (n_out <= 0 || n_in <= 0 || n_out % 32 || n_in % 16)
+    EE_FAIL(EE_ERR_SHAPE, "ee_pack_weight: n_out %d must be a positive multiple of 32, n_in %d of 16", n_out, n_in);
+  int s = 16;
+  if (order == EE_PACK_QKV || order == EE_PACK_GATE_UP) {
+    s = pair_stride;
+    if (s < 16 || s % 16 || n_out % (2 * s))
+      EE_FAIL(EE_ERR_SHAPE, "ee_pack_weight: pair_stride %d must be a multiple of 16 and 2*pair_stride divide n_out %d", s,
+              n_out);
+  } else if (order != EE_PACK_PLAIN) {
+    EE_FAIL(EE_ERR_INVALID_ARG, "ee_pack_weight: unknown order %d", order);
+  }
+  launch_pack_weight(reinterpret_cast<const bf16_t*>(w), n_out, n_in, s, reinterpret_cast<bf16_t*>(packed),
+                     reinterpret_cast<hipStream_t>(stream));
+  EE_HIP(hipGetLastError());
+  return EE_OK;
+}
+
+size_t ee_workspace_bytes(const ee_model_desc* desc, int32_t max_batch, int32_t max_context) {
+  (void)max_context;
+  if (check_desc(desc) != EE_OK || max_batch < 0) return 0;
+  return carve(*desc, max_batch, nullptr).bytes;
+}
+
+int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const ee_batch* batch, const float* thresholds,
+                        const int32_t* forced_exit_layer, int32_t use_exit_heads, int32_t* out_tokens,
+                        int32_t* out_exit_layer, int32_t* out_batch_exit_layer, float* out_conf, float* out_hidden,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  int rc;
+  if ((rc = check_model(model)) || (rc = check_cache(cache)) || (rc = check_batch(batch, true))) return rc;
+  const ee_model_desc& D = model->desc;
+  const int B = batch->batch;
+  if (B == 0) return EE_OK;
+  if (use_exit_heads && !thresholds) EE_FAIL(EE_ERR_INVALID_ARG, "thresholds is NULL");
+  if (!out_tokens || !out_exit_layer || !out_batch_exit_layer) EE_FAIL(EE_ERR_INVALID_ARG, "an output pointer is NULL");
+  if ((rc = check_workspace(D, B, workspace, workspace_bytes))) return rc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const Workspace w = carve(D, B, workspace);
+  const int Mpad = round_up(B, 32);
+  const int n = D.n_layers, d = D.d_model, f = D.d_ffn;
+  const bool bf = D.dtype == EE_BF16;
+  IterState s{w.status, out_exit_layer, w.n_exited, w.done, out_batch_exit_layer};
+  const Pred run_layers{w.done, 0};  // kernels of the layer loop: only while the batch has not left
+  const Pred run_fill{w.done, 1};    // KV filling: only after it has
+  const Pred always{nullptr, 0};
+
+  // Algorithm 1, initialisation
+  launch_iter_init(s, B, n, out_conf, bf ? w.rowsq : nullptr, bf ? (size_t)(2 * n + 2) * Mpad : 0, st);
+  if (bf)
+    launch_embed_bf16(reinterpret_cast<const bf16_t*>(model->embed), batch->tokens, w.hT, B, Mpad, d, st);
+  else
+    launch_embed_f32(reinterpret_cast<const float*>(model->embed), batch->tokens, w.h, B, d, st);
+  // rowsq slot 0: after the embedding; slot 2i-1: after layer i's attention update; slot 2i: after layer i
+  auto rs = [&](int slot) { return w.rowsq + (size_t)slot * Mpad; };
+  if (bf) launch_rowsq(w.hT, rs(0), Mpad, d, always, st);
+
+  // Algorithm 1, batch inference loop.  Everything is enqueued; the done flag turns later layers into no-ops.
+  for (int i = 1; i <= n; ++i) {
+    const ee_layer_weights& L = model->layers[i - 1];
+    const size_t pool_off = pool_layer_elems(D, *cache) * elem_bytes(D) * (size_t)(i - 1);
+    AttnArgs at{w.q, reinterpret_cast<char*>(cache->k_pool) + pool_off, reinterpret_cast<char*>(cache->v_pool) + pool_off,
+                batch->context_lens, batch->block_tables, batch->max_blocks, B, D.n_heads, D.head_dim, nullptr, 0};
+    if (bf) {
+      launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_attn), w.xT, rs(2 * i - 2), D.rms_eps, Mpad, d, run_layers, st);
+      GemmShape gq{L.w_qkv, w.xT, d, B, 0, 3 * d / 32, D.head_dim / 2, 1};
+      launch_gemm_qkv_bf16(gq, make_qkv_epi(D, *cache, *batch, i, w.q, nullptr), run_layers, st);
+      at.out = w.aoT;
+      at.out_xt = 1;
+      if ((rc = launch_attention(at, D.dtype, run_layers, st))) return rc;
+      GemmShape go{L.w_o, w.aoT, d, B, 0, d / 32, 16, acc_ksplit(d / 32, d)};
+      launch_gemm_acc_bf16(go, AccEpi{w.hT, Mpad, d}, run_layers, st);
+      launch_rowsq(w.hT, rs(2 * i - 1), Mpad, d, run_layers, st);
+      launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_ffn), w.xT, rs(2 * i - 1), D.rms_eps, Mpad, d, run_layers, st);
+      GemmShape gg{L.w_gate_up, w.xT, d, B, 0, 2 * f / 32, f, 1};
+      launch_gemm_gateup_bf16(gg, GateUpEpi{w.actT, f, nullptr, D.rms_eps, d}, run_layers, st);
+      GemmShape gd{L.w_down, w.actT, f, B, 0, d / 32, 16, acc_ksplit(d / 32, f)};
+      launch_gemm_acc_bf16(gd, AccEpi{w.hT, Mpad, d}, run_layers, st);
+      launch_rowsq(w.hT, rs(2 * i), Mpad, d, run_layers, st);
+    } else {
+      launch_rmsnorm_f32(w.h, reinterpret_cast<const float*>(L.g_attn), w.x, B, d, D.rms_eps, run_layers, st);
+      SimpleShape gq{reinterpret_cast<const float*>(L.w_qkv), w.x, d, B, 0, 3 * d, D.head_dim / 2};
+      launch_simple_qkv(gq, make_qkv_epi(D, *cache, *batch, i, w.q, nullptr), run_layers, st);
+      at.out = w.ao;
+      at.out_xt = 0;
+      if ((rc = launch_attention(at, D.dtype, run_layers, st))) return rc;
+      SimpleShape go{reinterpret_cast<const float*>(L.w_o), w.ao, d, B, 0, d, 1};
+      launch_simple_acc(go, AccEpi{w.h, 0, d}, run_layers, st);
+      launch_rmsnorm_f32(w.h, reinterpret_cast<const float*>(L.g_ffn), w.x, B, d, D.rms_eps, run_layers, st);
+      SimpleShape gg{reinterpret_cast<const float*>(L.w_gate_up), w.x, d, B, 0, 2 * f, f};
+      launch_simple_gateup(gg, GateUpEpi{w.act, f, nullptr, D.rms_eps, d}, run_layers, st);
+      SimpleShape gd{reinterpret_cast<const float*>(L.w_down), w.act, f, B, 0, d, 1};
+      launch_simple_acc(gd, AccEpi{w.h, 0, d}, run_layers, st);
+    }
+    if (use_exit_heads && has_head(D, i)) {
+      const float scale = D.logit_scale * (float)i;
+      if (bf)
+        enqueue_head_bf16(*model, w, B, Mpad, scale, rs(2 * i), run_layers, st);
+      else
+        enqueue_head_f32(*model, w, w.h, B, scale, run_layers, st);
+      CombineArgs ca{w.partials, bf ? D.vocab / 32 : 1, B, i, scale, thresholds[i - 1], D.conf_mode, forced_exit_layer, s,
+                     out_tokens, out_conf ? out_conf + (size_t)(i - 1) * B : nullptr};
+      launch_combine(ca, run_layers, st);
+    }
+  }
+
+  // Algorithm 1, KV cache filling for layers output_layer+1..n (runs only if the batch left early)
+  if (use_exit_heads) {
+    if (bf)
+      enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, out_batch_exit_layer, 0, rs(2 * n + 1), run_fill, st);
+    else
+      enqueue_fill_f32(*model, *cache, *batch, w, w.h, out_batch_exit_layer, 0, run_fill, st);
+  }
+
+  // Algorithm 1, transform_to_tokens.  When the batch left at an exit head, that head's arg max over the same
+  // hidden state already is the token; the LM head is only streamed again when the loop ran to the last layer.
+  {
+    if (bf)
+      enqueue_head_bf16(*model, w, B, Mpad, 0.0f, rs(2 * n), run_layers, st);
+    else
+      enqueue_head_f32(*model, w, w.h, B, 0.0f, run_layers, st);
+    CombineArgs ca{w.partials, bf ? D.vocab / 32 : 1, B, 0, 0.0f, 0.0f, 0, nullptr, s, out_tokens, nullptr};
+    launch_combine(ca, run_layers, st);
+  }
+  if (out_hidden) {
+    if (bf)
+      launch_ht_to_hidden(w.hT, out_hidden, B, Mpad, d, st);
+    else
+      launch_copy_f32(w.h, out_hidden, (size_t)B * d, st);
+  }
+  (void)always;
+  EE_HIP(hipGetLastError());
+  return EE_OK;
+}
+
+int ee_exit_check(const ee_model* model, int32_t layer, const float* hidden, int32_t batch, float threshold,
+                  const int32_t* forced_exit_layer, int32_t* status, int32_t* exit_layer, int32_t* n_exited,
+                  int32_t* done_flag, int32_t* batch_exit_layer, int32_t* argmax, float* conf, void* workspace,
+                  size_t workspace_bytes, void* stream) {
+  int rc;
+  if ((rc = check_model(model))) return rc;
+  const ee_model_desc& D = model->desc;
+  if (batch < 0) EE_FAIL(EE_ERR_INVALID_ARG, "batch size %d is negative", batch);
+  if (batch == 0) return EE_OK;
+  if (layer < 1 || layer > D.n_layers) EE_FAIL(EE_ERR_INVALID_ARG, "layer %d outside 1..%d", layer, D.n_layers);
+  if (!hidden || !status || !exit_layer || !n_exited || !done_flag || !batch_exit_layer)
+    EE_FAIL(EE_ERR_INVALID_ARG, "ee_exit_check: NULL pointer");
+  if ((rc = check_workspace(D, batch, workspace, workspace_bytes))) return rc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const Workspace w = carve(D, batch, workspace);
+  const int Mpad = round_up(batch, 32);
+  const Pred always{nullptr, 0};
+  const float scale = D.logit_scale * (float)layer;
+  if (D.dtype == EE_BF16) {
+    launch_iter_init(IterState{w.status, w.scratch_exit_layer, w.n_exited, w.done, w.scratch_L}, 0, D.n_layers, nullptr,
+                     w.rowsq, (size_t)Mpad, st);
+    launch_hidden_to_ht(hidden, w.hT, batch, Mpad, D.d_model, st);
+    launch_rowsq(w.hT, w.rowsq, Mpad, D.d_model, always, st);
+    enqueue_head_bf16(*model, w, batch, Mpad, scale, w.rowsq, always, st);
+  } else {
+    enqueue_head_f32(*model, w, hidden, batch, scale, always, st);
+  }
+  IterState s{status, exit_layer, n_exited, done_flag, batch_exit_layer};
+  CombineArgs ca{w.partials, D.dtype == EE_BF16 ? D.vocab / 32 : 1, batch, layer, scale, threshold, D.conf_mode,
+                 forced_exit_layer, s, argmax, conf};
+  launch_combine(ca, always, st);
+  EE_HIP(hipGetLastError());
+  return EE_OK;
+}
+
+int ee_kv_fill(const ee_model* model, const ee_kv_cache* cache, const ee_batch* batch, const float* hidden,
+               const int32_t* fill_from_layer, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc;
+  if ((rc = check_model(model)) || (rc = check_cache(cache)) || (rc = check_batch(batch, false))) return rc;
+  const ee_model_desc& D = model->desc;
+  const int B = batch->batch;
+  if (B == 0) return EE_OK;
+  if (!hidden || !fill_from_layer) EE_FAIL(EE_ERR_INVALID_ARG, "ee_kv_fill: NULL pointer");
+  if ((rc = check_workspace(D, B, workspace, workspace_bytes))) return rc;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const Workspace w = carve(D, B, workspace);
+  const int Mpad = round_up(B, 32);
+  const Pred always{nullptr, 0};
+  if (D.dtype == EE_BF16) {
+    launch_iter_init(IterState{w.status, w.scratch_exit_layer, w.n_exited, w.done, w.scratch_L}, 0, D.n_layers, nullptr,
+                     w.rowsq, (size_t)Mpad, st);
+    launch_hidden_to_ht(hidden, w.hT, B, Mpad, D.d_model, st);
+    enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, fill_from_layer, 1, w.rowsq, always, st);
+  } else {
+    enqueue_fill_f32(*model, *cache, *batch, w, hidden, fill_from_layer, 1, always, st);
+  }
+  EE_HIP(hipGetLastError());
+  return EE_OK;
+}
+
+int ee_paged_attention_decode(const ee_model_desc* desc, const ee_kv_cache* cache, int32_t layer, const float* q,
+                              const ee_batch* batch, float* out, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  int rc;
+  if ((rc = check_desc(desc)) || (rc = check_cache(cache)) || (rc = check_batch(batch, false))) return rc;
+  if (batch->batch == 0) return EE_OK;
+  if (layer < 1 || layer > desc->n_layers) EE_FAIL(EE_ERR_INVALID_ARG, "layer %d outside 1..%d", layer, desc->n_layers);
+  if (!q || !out) EE_FAIL(EE_ERR_INVALID_ARG, "ee_paged_attention_decode: NULL pointer");
+  const size_t off = pool_layer_elems(*desc, *cache) * elem_bytes(*desc) * (size_t)(layer - 1);
+  AttnArgs at{q, reinterpret_cast<char*>(cache->k_pool) + off, reinterpret_cast<char*>(cache->v_pool) + off,
+              batch->context_lens, batch->block_tables, batch->max_blocks, batch->batch, desc->n_heads, desc->head_dim,
+              out, 0};
+  const Pred always{nullptr, 0};
+  if ((rc = launch_attention(at, desc->dtype, always, reinterpret_cast<hipStream_t>(stream)))) return rc;
+  EE_HIP(hipGetLastError());
+  return EE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,202 @@
+// Shared declarations of the early-exit decode library: types, memory layouts, launch interfaces.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ee_decode.h"
+
+namespace ee {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// ---------------------------------------------------------------------------------------------------
+// Error reporting (host)
+// ---------------------------------------------------------------------------------------------------
+void set_error(const char* fmt, ...);
+#define EE_FAIL(code, ...)      \
+  do {                          \
+    ee::set_error(__VA_ARGS__); \
+    return (code);              \
+  } while (0)
+#define EE_HIP(expr)                                                                        \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) EE_FAIL(EE_ERR_HIP, "%s failed: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+// ---------------------------------------------------------------------------------------------------
+// Layouts of the bf16 path.
+//
+// XT ("operand tiles"): a [rows m][cols k] bf16 activation matrix stored in the order in which the
+//   32x32x16 MFMA wants its second operand: [m/32][k/16][lane][8] with lane = (m%32) + 32*((k%16)/8) and
+//   element k%8, so a wavefront fetches one 32x16 operand tile as 1 KiB of consecutive bytes.
+// HT ("transposed residual"): the fp32 residual stream stored [k][Mpad] (channel-major) so that the
+//   atomic accumulation from an MFMA result tile (lanes = consecutive m) touches consecutive words.
+// ---------------------------------------------------------------------------------------------------
+__host__ __device__ inline size_t xt_index(int m, int k, int K) {
+  return ((size_t)(m >> 5) * (size_t)(K >> 4) + (size_t)(k >> 4)) * 512 + (size_t)((((k >> 3) & 1) << 5) + (m & 31)) * 8 +
+         (size_t)(k & 7);
+}
+__host__ __device__ inline size_t ht_index(int m, int k, int Mpad) { return (size_t)k * Mpad + m; }
+__host__ __device__ inline int round_up(int x, int to) { return (x + to - 1) / to * to; }
+
+// Packed weight row order: packed tile `nt`, row r (0..31) holds plain output row
+//   f_lo(nt, r%16) + (r/16) * pair_stride,   f_lo = (nt / tpb) * 2*pair_stride + 16*(nt % tpb) + r%16,  tpb = pair_stride/16.
+// pair_stride 16 is the identity order.
+__host__ __device__ inline int packed_row_lo(int nt, int r16, int pair_stride) {
+  const int tpb = pair_stride >> 4;
+  return (nt / tpb) * 2 * pair_stride + ((nt % tpb) << 4) + r16;
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Per-iteration device state
+// ---------------------------------------------------------------------------------------------------
+struct IterState {
+  int32_t* status;            // [B] sticky exit status
+  int32_t* exit_layer;        // [B]
+  int32_t* n_exited;          // [1]
+  int32_t* done;              // [1] 1 once every sequence of the batch is accepted
+  int32_t* batch_exit_layer;  // [1] output_layer of Algorithm 1
+};
+
+// Epilogue parameter blocks ---------------------------------------------------------------------------
+struct QkvEpi {                 // rotary embedding + paged cache write (+ q output)
+  float* q;                     // [M][d] fp32 or nullptr (KV filling)
+  void* k_pool;                 // layer base of the pools ([num_blocks][H][16][dh])
+  void* v_pool;
+  const int32_t* context_lens;  // [M]
+  const int32_t* block_tables;  // [M][max_blocks]
+  const int32_t* fill_from;     // nullptr, or [M]: only rows with fill_from[m] < layer are written (KV filling)
+  int fill_from_stride;         // 1 = per row, 0 = one value for the whole batch
+  int layer;
+  int max_blocks, n_heads, head_dim, d_model;
+  float rope_theta;
+  const float* rowsq;           // nullptr, or [M] sum of squares of the hidden row: value *= rsqrt(rowsq/d + eps)
+  float eps;
+};
+struct AccEpi {                 // h += value
+  float* h;
+  int Mpad;                     // HT pitch (bf16 path) or 0: plain [M][n_out]
+  int n_out;
+};
+struct GateUpEpi {              // act = silu(gate) * up
+  void* act;                    // XT bf16 [Mpad][f] (bf16 path) or plain float [M][f]
+  int d_ffn;
+  const float* rowsq;
+  float eps;
+  int d_model;
+};
+struct LmEpi {                  // per-tile softmax statistics of the scaled logits
+  float4* partials;             // [M][n_parts]: {max logit (unscaled), sum exp(scale*(z - max)), 2nd max, arg max as int bits}
+  float* logits;                // fp32 path: [M][vocab] raw logits; bf16 path: nullptr
+  int n_parts;
+  int vocab;
+  float scale;                  // logit_scale * layer
+  const float* rowsq;
+  float eps;
+  int d_model;
+};
+
+// ---------------------------------------------------------------------------------------------------
+// Launchers (each enqueues on `st`; `done` may be nullptr; when *done == want_done_zero ? ... see below)
+// `skip_if_done`: pointer to the done flag; kernels return at once when *skip_if_done != 0.
+// `run_if_done`:  kernels return at once when *run_if_done == 0 (KV filling).
+// ---------------------------------------------------------------------------------------------------
+struct Pred {
+  const int32_t* flag;  // nullptr = always run
+  int run_when;         // run when (*flag != 0) == run_when
+};
+
+// misc.hip
+void launch_iter_init(const IterState& s, int B, int n_layers, float* conf_out, float* zero_buf, size_t zero_count,
+                      hipStream_t st);
+void launch_embed_bf16(const bf16_t* E, const int32_t* tokens, float* hT, int B, int Mpad, int d, hipStream_t st);
+void launch_embed_f32(const float* E, const int32_t* tokens, float* h, int B, int d, hipStream_t st);
+void launch_hidden_to_ht(const float* plain, float* hT, int B, int Mpad, int d, hipStream_t st);
+void launch_ht_to_hidden(const float* hT, float* plain, int B, int Mpad, int d, hipStream_t st);
+void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t st);
+// RMSNorm of the bf16 path: rowsq[m] += sum_k h^2, then x = bf16(h * rsqrt(rowsq/d + eps) * g) in XT order.
+// launch_prep_x_layers writes one slab per layer with that layer's gain (KV filling).
+struct GainTable {
+  const void* g[EE_MAX_LAYERS];
+};
+void launch_rowsq(const float* hT, float* rowsq, int Mpad, int d, Pred pred, hipStream_t st);
+void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, float eps, int Mpad, int d,
+                   Pred pred, hipStream_t st);
+void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
+                          float eps, const int32_t* fill_from, int fill_from_stride, int B, int Mpad, int d, Pred pred,
+                          hipStream_t st);
+void launch_rmsnorm_f32(const float* h, const float* gain, float* x, int B, int d, float eps, Pred pred, hipStream_t st);
+void launch_head_stats_f32(const float* logits, float4* partials, int B, int vocab, float scale, Pred pred,
+                           hipStream_t st);
+struct CombineArgs {
+  const float4* partials;
+  int n_parts;
+  int B;
+  int layer;           // 1-based; 0 = final token selection (no status update)
+  float scale;         // logit_scale * layer
+  float threshold;
+  int conf_mode;
+  const int32_t* forced_exit_layer;
+  IterState s;
+  int32_t* argmax_out;  // [B] or nullptr
+  float* conf_out;      // [B] or nullptr
+};
+void launch_combine(const CombineArgs& a, Pred pred, hipStream_t st);
+
+// pack.hip
+void launch_pack_weight(const bf16_t* w, int n_out, int n_in, int pair_stride, bf16_t* packed, hipStream_t st);
+
+// gemm_mfma.hip (bf16 path).  w: packed; x: XT [Mpad][K].  tiles [tile_begin, tile_begin + n_tiles).
+struct GemmShape {
+  const void* w;
+  const void* x;
+  int K;            // contraction length
+  int M;            // valid rows
+  int tile_begin;   // first packed 32-row tile
+  int n_tiles;      // tiles to compute
+  int pair_stride;  // row order of the packed matrix
+  int ksplit;       // workgroups along K (> 1 only with the accumulate epilogue)
+};
+void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st);
+void launch_gemm_acc_bf16(const GemmShape& g, const AccEpi& e, Pred pred, hipStream_t st);
+void launch_gemm_gateup_bf16(const GemmShape& g, const GateUpEpi& e, Pred pred, hipStream_t st);
+void launch_gemm_lm_bf16(const GemmShape& g, const LmEpi& e, Pred pred, hipStream_t st);
+// KV filling over layers first..n in one launch: per-layer weights / x slabs / pools.
+struct FillLayers {
+  const void* w_qkv[EE_MAX_LAYERS];
+};
+void launch_gemm_kvfill_bf16(const FillLayers& fl, int n_layers, const bf16_t* x_slabs, size_t x_slab_elems,
+                             size_t pool_layer_elems, const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st);
+
+// gemm_simple.hip (fp32 path).  w: plain [n_out][K]; x: plain [M][K].
+struct SimpleShape {
+  const float* w;
+  const float* x;
+  int K, M;
+  int row_begin;    // first output row
+  int n_rows;       // output rows to compute (even)
+  int pair_stride;  // rows (f, f + pair_stride) are computed together
+};
+void launch_simple_qkv(const SimpleShape& g, const QkvEpi& e, Pred pred, hipStream_t st);
+void launch_simple_acc(const SimpleShape& g, const AccEpi& e, Pred pred, hipStream_t st);
+void launch_simple_gateup(const SimpleShape& g, const GateUpEpi& e, Pred pred, hipStream_t st);
+void launch_simple_lm(const SimpleShape& g, const LmEpi& e, Pred pred, hipStream_t st);
+
+// attention.hip
+struct AttnArgs {
+  const float* q;               // [B][H*dh] fp32, rotary applied
+  const void* k_pool;           // layer base
+  const void* v_pool;
+  const int32_t* context_lens;  // attends positions 0..context_lens[b] inclusive
+  const int32_t* block_tables;
+  int max_blocks, B, n_heads, head_dim;
+  void* out;                    // fp32 plain [B][H*dh], or XT bf16 [Mpad][H*dh]
+  int out_xt;                   // 1: XT bf16
+};
+int launch_attention(const AttnArgs& a, int dtype, Pred pred, hipStream_t st);
+
+}  // namespace ee

@@ -1,0 +1,107 @@
+// Device-side epilogues shared by the MFMA (bf16) and the plain (fp32) projection kernels.
+// Each takes one batch row m and one pair of output rows (f_lo, f_hi) with their finished dot products.
+#pragma once
+
+#include "ee_common.h"
+
+namespace ee {
+
+__device__ inline float row_rinv(const float* rowsq, int m, int d, float eps) {
+  return rowsq ? rsqrtf(rowsq[m] / (float)d + eps) : 1.0f;
+}
+
+__device__ inline void store_elem(float* p, float v) { *p = v; }
+__device__ inline void store_elem(bf16_t* p, float v) { *p = (bf16_t)v; }
+
+// Rotary embedding (split-half pairing: channel j with j + dh/2, angle = pos * theta^(-2j/dh)) and the write of
+// this position's K/V into the paged cache; q goes to a dense buffer.  The angle is formed in double so that long
+// contexts do not lose the fraction of the angle to float rounding of the frequency.
+template <class T>
+__device__ inline void epi_qkv(const QkvEpi& e, int m, int f_lo, float lo, float hi) {
+  if (e.fill_from && !(e.fill_from[(size_t)m * e.fill_from_stride] < e.layer)) return;
+  const float r = row_rinv(e.rowsq, m, e.d_model, e.eps);
+  lo *= r;
+  hi *= r;
+  const int d = e.d_model, dh = e.head_dim, half = dh >> 1;
+  const int which = f_lo / d;  // 0 q, 1 k, 2 v
+  const int within = f_lo - which * d;
+  const int head = within / dh;
+  const int j = within - head * dh;  // < dh/2
+  const int p = e.context_lens[m];
+  if (which < 2 && e.rope_theta > 0.0f) {
+    const double ang = (double)p * exp2(-2.0 * (double)j / (double)dh * log2((double)e.rope_theta));
+    double sn, cs;
+    sincos(ang, &sn, &cs);
+    const float c = (float)cs, s = (float)sn;
+    const float a = lo * c - hi * s;
+    const float b = hi * c + lo * s;
+    lo = a;
+    hi = b;
+  }
+  if (which == 0) {
+    if (e.q) {
+      float* q = e.q + (size_t)m * d + head * dh + j;
+      q[0] = lo;
+      q[half] = hi;
+    }
+    return;
+  }
+  const int blk = e.block_tables[(size_t)m * e.max_blocks + (p >> 4)];
+  const size_t at = (((size_t)blk * e.n_heads + head) * 16 + (p & 15)) * dh + j;
+  T* pool = reinterpret_cast<T*>(which == 1 ? e.k_pool : e.v_pool);
+  store_elem(pool + at, lo);
+  store_elem(pool + at + half, hi);
+}
+
+__device__ inline void epi_acc(const AccEpi& e, int m, int f, float v) {
+  float* p = e.Mpad ? e.h + ht_index(m, f, e.Mpad) : e.h + (size_t)m * e.n_out + f;
+  unsafeAtomicAdd(p, v);
+}
+
+// SwiGLU product; f_lo is the gate row f, f_hi the up row f + d_ffn.
+template <class T>
+__device__ inline void epi_gateup(const GateUpEpi& e, int m, int f, float gate, float up) {
+  const float r = row_rinv(e.rowsq, m, e.d_model, e.eps);
+  gate *= r;
+  up *= r;
+  const float a = gate / (1.0f + expf(-gate)) * up;
+  if constexpr (sizeof(T) == 2) {
+    reinterpret_cast<bf16_t*>(e.act)[xt_index(m, f, e.d_ffn)] = (bf16_t)a;
+  } else {
+    reinterpret_cast<float*>(e.act)[(size_t)m * e.d_ffn + f] = a;
+  }
+}
+
+// Running softmax statistics of one row: largest and second largest (unscaled) logit, index of the largest
+// (lowest index on ties) and sum of exp(scale * (z - max)).
+struct HeadStat {
+  float zmax, sum, z2;
+  int idx;
+};
+__device__ inline HeadStat stat_empty() { return {-INFINITY, 0.0f, -INFINITY, 0x7fffffff}; }
+__device__ inline HeadStat stat_merge(const HeadStat& a, const HeadStat& b, float scale) {
+  HeadStat o;
+  if (a.zmax > b.zmax || (a.zmax == b.zmax && a.idx < b.idx)) {
+    o.zmax = a.zmax;
+    o.idx = a.idx;
+    o.z2 = fmaxf(a.z2, b.zmax);
+  } else {
+    o.zmax = b.zmax;
+    o.idx = b.idx;
+    o.z2 = fmaxf(b.z2, a.zmax);
+  }
+  const float wa = a.sum > 0.0f ? a.sum * expf(scale * (a.zmax - o.zmax)) : 0.0f;
+  const float wb = b.sum > 0.0f ? b.sum * expf(scale * (b.zmax - o.zmax)) : 0.0f;
+  o.sum = wa + wb;
+  return o;
+}
+__device__ inline HeadStat stat_push(const HeadStat& a, float z, int idx, float scale) {
+  HeadStat b = {z, 1.0f, -INFINITY, idx};
+  return stat_merge(a, b, scale);
+}
+__device__ inline float4 stat_pack(const HeadStat& s) { return make_float4(s.zmax, s.sum, s.z2, __int_as_float(s.idx)); }
+__device__ inline HeadStat stat_unpack(const float4& v) { return {v.x, v.y, v.z, __float_as_int(v.w)}; }
+
+__device__ inline bool pred_skip(const Pred& p) { return p.flag && ((*p.flag != 0) != (p.run_when != 0)); }
+
+}  // namespace ee

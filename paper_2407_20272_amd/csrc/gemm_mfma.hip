@@ -1,0 +1,248 @@
+// bf16 projections of the decode step on the matrix cores (v_mfma_f32_32x32x16_bf16).
+//
+// The decode step multiplies a handful of activation rows (the batch) by large weight matrices, so the
+// kernel is a weight streamer: every weight byte is fetched from HBM exactly once, straight into registers
+// (1 KiB of consecutive bytes per wavefront load thanks to the packed tile order), and the small activation
+// operand comes out of L2 in its own tile order.  A workgroup of four wavefronts owns one 32-row output tile
+// and splits the contraction four ways; the partial tiles meet in LDS and the epilogue (rotary + paged cache
+// write, residual accumulation, SwiGLU, or exit-head softmax statistics) runs on the finished sums.
+#include <type_traits>
+
+#include "ee_common.h"
+#include "ee_epilogue.h"
+
+namespace ee {
+namespace {
+
+constexpr int NW = 4;  // wavefronts per workgroup
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <int MT, int U>
+struct Frag {
+  u32x4 w[U];
+  u32x4 x[MT][U];
+};
+
+template <int MT, int U>
+__device__ inline void frag_load(Frag<MT, U>& f, const u32x4* __restrict__ wp, const u32x4* __restrict__ xp,
+                                 size_t x_tile_stride, int ks) {
+#pragma unroll
+  for (int u = 0; u < U; ++u) f.w[u] = __builtin_nontemporal_load(wp + (size_t)(ks + u) * 64);
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int u = 0; u < U; ++u) f.x[mt][u] = xp[mt * x_tile_stride + (size_t)(ks + u) * 64];
+}
+
+// Last, partial group: steps past ks1 re-read the last valid weight tile against a zero activation tile.
+template <int MT, int U>
+__device__ inline void frag_load_tail(Frag<MT, U>& f, const u32x4* __restrict__ wp, const u32x4* __restrict__ xp,
+                                      size_t x_tile_stride, int ks, int ks1) {
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const bool ok = ks + u < ks1;
+    const int kk = ok ? ks + u : ks1 - 1;
+    f.w[u] = __builtin_nontemporal_load(wp + (size_t)kk * 64);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      u32x4 v = xp[mt * x_tile_stride + (size_t)kk * 64];
+      f.x[mt][u] = ok ? v : u32x4{0, 0, 0, 0};
+    }
+  }
+}
+
+template <int MT, int U>
+__device__ inline void frag_mma(const Frag<MT, U>& f, f32x16 (&acc)[MT]) {
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+      acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.w[u]),
+                                                        __builtin_bit_cast(bf16x8, f.x[mt][u]), acc[mt], 0, 0, 0);
+}
+
+struct FillCtl {  // KV filling: one grid.z slice per layer
+  int enabled;
+  FillLayers layers;
+  const bf16_t* x_slabs;
+  size_t x_slab_elems;
+  size_t pool_layer_bytes;
+};
+
+template <int MT, int U, class Epi, bool FILL>
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred pred, FillCtl fc) {
+  if (pred_skip(pred)) return;
+  __shared__ float red[NW][16][64];
+  __shared__ float zt[32][33];
+  __shared__ int any_row;
+
+  if constexpr (FILL) {
+    const int layer = blockIdx.z + 1;
+    // rows that need this layer filled: fill_from[m] < layer
+    if (threadIdx.x == 0) any_row = 0;
+    __syncthreads();
+    int need = 0;
+    if (e.fill_from_stride == 0) {
+      need = e.fill_from[0] < layer;
+    } else {
+      for (int m = threadIdx.x; m < g.M; m += blockDim.x) need |= e.fill_from[m] < layer;
+    }
+    if (need) any_row = 1;
+    __syncthreads();
+    if (!any_row) return;
+    g.w = fc.layers.w_qkv[layer - 1];
+    g.x = fc.x_slabs + (size_t)(layer - 1) * fc.x_slab_elems;
+    e.layer = layer;
+    e.k_pool = reinterpret_cast<char*>(e.k_pool) + (size_t)(layer - 1) * fc.pool_layer_bytes;
+    e.v_pool = reinterpret_cast<char*>(e.v_pool) + (size_t)(layer - 1) * fc.pool_layer_bytes;
+  }
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int nt = g.tile_begin + blockIdx.x;
+  const int k_steps = g.K >> 4;
+  const int chunks = gridDim.y * NW;
+  const int c = blockIdx.y * NW + wave;
+  const int ks0 = (int)((long)k_steps * c / chunks);
+  const int ks1 = (int)((long)k_steps * (c + 1) / chunks);
+  const int m_tiles = (g.M + 31) >> 5;
+  const size_t x_tile_stride = (size_t)k_steps * 64;
+
+  const u32x4* wp = reinterpret_cast<const u32x4*>(g.w) + (size_t)nt * k_steps * 64 + lane;
+
+  for (int mt0 = 0; mt0 < m_tiles; mt0 += MT) {
+    const u32x4* xp = reinterpret_cast<const u32x4*>(g.x) + (size_t)mt0 * x_tile_stride + lane;
+    f32x16 acc[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[mt][i] = 0.0f;
+
+    // double-buffered stream over this wavefront's share of the contraction
+    Frag<MT, U> A, B;
+    const int n = (ks1 - ks0) / U;
+    int k = ks0;
+    if (n > 0) frag_load(A, wp, xp, x_tile_stride, k);
+    int i = 0;
+    for (; i + 2 <= n; i += 2) {
+      frag_load(B, wp, xp, x_tile_stride, k + U);
+      frag_mma(A, acc);
+      if (i + 2 < n) frag_load(A, wp, xp, x_tile_stride, k + 2 * U);
+      frag_mma(B, acc);
+      k += 2 * U;
+    }
+    if (i < n) {
+      frag_mma(A, acc);
+      k += U;
+    }
+    if (k < ks1) {
+      frag_load_tail(A, wp, xp, x_tile_stride, k, ks1);
+      frag_mma(A, acc);
+    }
+
+    // meet the four partial tiles in LDS, one batch tile at a time
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      __syncthreads();
+#pragma unroll
+      for (int a = 0; a < 16; ++a) red[wave][a][lane] = acc[mt][a];
+      __syncthreads();
+      const int l2 = threadIdx.x & 63, qq = threadIdx.x >> 6;
+      const int m = (mt0 + mt) * 32 + (l2 & 31);
+      float vlo[2], vhi[2];
+      int r16[2];
+#pragma unroll
+      for (int ai = 0; ai < 2; ++ai) {
+        const int a = 2 * qq + ai;
+        vlo[ai] = red[0][a][l2] + red[1][a][l2] + red[2][a][l2] + red[3][a][l2];
+        vhi[ai] = red[0][a + 8][l2] + red[1][a + 8][l2] + red[2][a + 8][l2] + red[3][a + 8][l2];
+        r16[ai] = (a >> 2) * 8 + (l2 >> 5) * 4 + (a & 3);
+      }
+      if constexpr (std::is_same<Epi, LmEpi>::value) {
+        const float r = m < g.M ? row_rinv(e.rowsq, m, e.d_model, e.eps) : 0.0f;
+#pragma unroll
+        for (int ai = 0; ai < 2; ++ai) {
+          zt[r16[ai]][l2 & 31] = vlo[ai] * r;
+          zt[r16[ai] + 16][l2 & 31] = vhi[ai] * r;
+        }
+        __syncthreads();
+        if (threadIdx.x < 32) {
+          const int mm = (mt0 + mt) * 32 + threadIdx.x;
+          if (mm < g.M) {
+            HeadStat s = stat_empty();
+            for (int rr = 0; rr < 32; ++rr) s = stat_push(s, zt[rr][threadIdx.x], nt * 32 + rr, e.scale);
+            e.partials[(size_t)mm * e.n_parts + (nt - g.tile_begin)] = stat_pack(s);
+          }
+        }
+      } else {
+        if (m < g.M) {
+#pragma unroll
+          for (int ai = 0; ai < 2; ++ai) {
+            const int f_lo = packed_row_lo(nt, r16[ai], g.pair_stride);
+            if constexpr (std::is_same<Epi, QkvEpi>::value) {
+              epi_qkv<bf16_t>(e, m, f_lo, vlo[ai], vhi[ai]);
+            } else if constexpr (std::is_same<Epi, AccEpi>::value) {
+              epi_acc(e, m, f_lo, vlo[ai]);
+              epi_acc(e, m, f_lo + g.pair_stride, vhi[ai]);
+            } else {
+              epi_gateup<bf16_t>(e, m, f_lo, vlo[ai], vhi[ai]);
+            }
+          }
+        }
+      }
+    }
+  }
+}
+
+int pick_mt(int M) {
+  const int m_tiles = (M + 31) / 32;
+  if (m_tiles % 4 == 0) return 4;
+  if (m_tiles % 2 == 0) return 2;
+  return 1;
+}
+
+template <class Epi, bool FILL>
+void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int nz, hipStream_t st) {
+  dim3 grid(g.n_tiles, g.ksplit, nz), block(256);
+  switch (pick_mt(g.M)) {
+    case 4:
+      hipLaunchKernelGGL((gemm_mfma_kernel<4, 2, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
+      break;
+    case 2:
+      hipLaunchKernelGGL((gemm_mfma_kernel<2, 4, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
+      break;
+    default:
+      hipLaunchKernelGGL((gemm_mfma_kernel<1, 8, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
+  }
+}
+
+}  // namespace
+
+void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st) {
+  FillCtl fc{};
+  launch<QkvEpi, false>(g, e, pred, fc, 1, st);
+}
+void launch_gemm_acc_bf16(const GemmShape& g, const AccEpi& e, Pred pred, hipStream_t st) {
+  FillCtl fc{};
+  launch<AccEpi, false>(g, e, pred, fc, 1, st);
+}
+void launch_gemm_gateup_bf16(const GemmShape& g, const GateUpEpi& e, Pred pred, hipStream_t st) {
+  FillCtl fc{};
+  launch<GateUpEpi, false>(g, e, pred, fc, 1, st);
+}
+void launch_gemm_lm_bf16(const GemmShape& g, const LmEpi& e, Pred pred, hipStream_t st) {
+  FillCtl fc{};
+  launch<LmEpi, false>(g, e, pred, fc, 1, st);
+}
+void launch_gemm_kvfill_bf16(const FillLayers& fl, int n_layers, const bf16_t* x_slabs, size_t x_slab_elems,
+                             size_t pool_layer_elems, const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st) {
+  FillCtl fc{};
+  fc.enabled = 1;
+  fc.layers = fl;
+  fc.x_slabs = x_slabs;
+  fc.x_slab_elems = x_slab_elems;
+  fc.pool_layer_bytes = pool_layer_elems * sizeof(bf16_t);
+  launch<QkvEpi, true>(g, e, pred, fc, n_layers, st);
+}
+
+}  // namespace ee

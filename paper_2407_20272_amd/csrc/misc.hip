@@ -1,0 +1,256 @@
+// Small kernels of the decode step: state reset, embedding gather, normalisation, exit-head decision.
+#include "ee_common.h"
+#include "ee_epilogue.h"
+
+namespace ee {
+namespace {
+
+// ---------------------------------------------------------------------------------------------------
+// Status <- False for every sequence (Algorithm 1, initialisation), counters, scratch that must start at 0.
+// ---------------------------------------------------------------------------------------------------
+__global__ void iter_init_kernel(IterState s, int B, int n_layers, float* conf_out, float* zero_buf, size_t zero_count) {
+  const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = t; i < (size_t)B; i += stride) {
+    s.status[i] = 0;
+    s.exit_layer[i] = n_layers;
+  }
+  if (t == 0) {
+    *s.n_exited = 0;
+    *s.done = 0;
+    *s.batch_exit_layer = n_layers;
+  }
+  if (conf_out)
+    for (size_t i = t; i < (size_t)B * n_layers; i += stride) conf_out[i] = __builtin_nanf("");
+  for (size_t i = t; i < zero_count; i += stride) zero_buf[i] = 0.0f;
+}
+
+// hidden_states <- Embed(input_tokens): one row gather per sequence; padding rows of the last tile are zero.
+__global__ void embed_bf16_kernel(const bf16_t* E, const int32_t* tokens, float* hT, int B, int Mpad, int d) {
+  const int k = blockIdx.x * blockDim.y + threadIdx.y;
+  const int m = blockIdx.y * 32 + threadIdx.x;
+  if (k >= d || m >= Mpad) return;
+  float v = 0.0f;
+  if (m < B) v = (float)E[(size_t)tokens[m] * d + k];
+  hT[ht_index(m, k, Mpad)] = v;
+}
+__global__ void embed_f32_kernel(const float* E, const int32_t* tokens, float* h, int B, int d) {
+  const int k = blockIdx.x * blockDim.x + threadIdx.x;
+  const int m = blockIdx.y;
+  if (k < d) h[(size_t)m * d + k] = E[(size_t)tokens[m] * d + k];
+}
+
+__global__ void hidden_to_ht_kernel(const float* plain, float* hT, int B, int Mpad, int d) {
+  const int k = blockIdx.x * blockDim.y + threadIdx.y;
+  const int m = blockIdx.y * 32 + threadIdx.x;
+  if (k >= d || m >= Mpad) return;
+  hT[ht_index(m, k, Mpad)] = m < B ? plain[(size_t)m * d + k] : 0.0f;
+}
+__global__ void ht_to_hidden_kernel(const float* hT, float* plain, int B, int Mpad, int d) {
+  const int k = blockIdx.x * blockDim.y + threadIdx.y;
+  const int m = blockIdx.y * 32 + threadIdx.x;
+  if (k >= d || m >= B) return;
+  plain[(size_t)m * d + k] = hT[ht_index(m, k, Mpad)];
+}
+__global__ void copy_f32_kernel(const float* src, float* dst, size_t n) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
+}
+
+// ---------------------------------------------------------------------------------------------------
+// bf16 path, RMSNorm in two small steps.
+//   rowsq_kernel : rowsq[m] += sum_k h[m][k]^2 over a 256-channel slice (grid = (d/256, Mpad/32)).
+//   prep_x_kernel: x = bf16(h * rsqrt(rowsq/d + eps) * gain) written in operand-tile order.
+//     A workgroup covers one 32-row batch tile x 64 channels: thread (m = t%32, c = t/32) owns 8 channels.
+//     grid = (d/64, Mpad/32, slabs); slab z uses gains.g[z] and writes slab z of xT (KV filling: one per layer).
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rowsq_kernel(const float* hT, float* rowsq, int Mpad, int d, Pred pred) {
+  if (pred_skip(pred)) return;
+  const int ml = threadIdx.x & 31, cl = threadIdx.x >> 5;
+  const int m = blockIdx.y * 32 + ml;
+  const int k0 = blockIdx.x * 256 + cl * 32;
+  float ss = 0.0f;
+#pragma unroll 8
+  for (int i = 0; i < 32; ++i) {
+    const int k = k0 + i;
+    const float h = k < d ? hT[ht_index(m, k, Mpad)] : 0.0f;
+    ss = fmaf(h, h, ss);
+  }
+  __shared__ float part[8][32];
+  part[cl][ml] = ss;
+  __syncthreads();
+  if (cl == 0) {
+    float s = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += part[j][ml];
+    unsafeAtomicAdd(rowsq + m, s);
+  }
+}
+
+__global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable gains, const bf16_t* gain0, bf16_t* xT,
+                                                     size_t slab_elems, const float* rowsq, float eps,
+                                                     const int32_t* fill_from, int fill_from_stride, int B, int Mpad,
+                                                     int d, Pred pred) {
+  if (pred_skip(pred)) return;
+  const int z = blockIdx.z;
+  const int ml = threadIdx.x & 31, cl = threadIdx.x >> 5;
+  const int m = blockIdx.y * 32 + ml;
+  if (fill_from) {
+    // KV filling: slab z is layer z+1; skip slabs no sequence needs
+    const int layer = z + 1;
+    __shared__ int any_row;
+    if (threadIdx.x == 0) any_row = 0;
+    __syncthreads();
+    int need = 0;
+    if (fill_from_stride == 0) need = fill_from[0] < layer;
+    else
+      for (int r = threadIdx.x; r < B; r += blockDim.x) need |= fill_from[r] < layer;
+    if (need) any_row = 1;
+    __syncthreads();
+    if (!any_row) return;
+  }
+  const bf16_t* gain = fill_from ? reinterpret_cast<const bf16_t*>(gains.g[z]) : gain0;
+  const int c = blockIdx.x * 8 + cl;  // 8-channel chunk
+  const int k0 = c * 8;
+  const float r = rsqrtf(rowsq[m] / (float)d + eps);
+  bf16x8 out;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) out[i] = (bf16_t)(hT[ht_index(m, k0 + i, Mpad)] * r * (float)gain[k0 + i]);
+  *reinterpret_cast<bf16x8*>(xT + (size_t)z * slab_elems + xt_index(m, k0, d)) = out;
+}
+
+// fp32 path: plain RMSNorm, one workgroup per row.
+__global__ __launch_bounds__(256) void rmsnorm_f32_kernel(const float* h, const float* gain, float* x, int d, float eps,
+                                                          Pred pred) {
+  if (pred_skip(pred)) return;
+  const int m = blockIdx.x;
+  const float* hp = h + (size_t)m * d;
+  float ss = 0.0f;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) ss = fmaf(hp[k], hp[k], ss);
+  __shared__ float red[256];
+  red[threadIdx.x] = ss;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s) red[threadIdx.x] += red[threadIdx.x + s];
+    __syncthreads();
+  }
+  const float r = 1.0f / sqrtf(red[0] / (float)d + eps);
+  for (int k = threadIdx.x; k < d; k += blockDim.x) x[(size_t)m * d + k] = hp[k] * r * gain[k];
+}
+
+// fp32 path: softmax statistics of one row of materialised logits -> one partial record.
+__global__ __launch_bounds__(256) void head_stats_f32_kernel(const float* logits, float4* partials, int vocab, float scale,
+                                                             Pred pred) {
+  if (pred_skip(pred)) return;
+  const int m = blockIdx.x;
+  HeadStat s = stat_empty();
+  for (int v = threadIdx.x; v < vocab; v += blockDim.x) s = stat_push(s, logits[(size_t)m * vocab + v], v, scale);
+  __shared__ float4 red[256];
+  red[threadIdx.x] = stat_pack(s);
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (threadIdx.x < w)
+      red[threadIdx.x] = stat_pack(stat_merge(stat_unpack(red[threadIdx.x]), stat_unpack(red[threadIdx.x + w]), scale));
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) partials[m] = red[0];
+}
+
+// ---------------------------------------------------------------------------------------------------
+// Exit decision of one layer (Section 3.1): merge the per-tile statistics of every row into the confidence,
+// apply the sticky status rule, count accepted sequences and raise the all-exited flag.  One workgroup per row.
+// layer == 0: final token selection only.
+// ---------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, Pred pred) {
+  if (pred_skip(pred)) return;
+  const int m = blockIdx.x;
+  HeadStat s = stat_empty();
+  for (int i = threadIdx.x; i < a.n_parts; i += blockDim.x)
+    s = stat_merge(s, stat_unpack(a.partials[(size_t)m * a.n_parts + i]), a.scale);
+  __shared__ float4 red[256];
+  red[threadIdx.x] = stat_pack(s);
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (threadIdx.x < w)
+      red[threadIdx.x] = stat_pack(stat_merge(stat_unpack(red[threadIdx.x]), stat_unpack(red[threadIdx.x + w]), a.scale));
+    __syncthreads();
+  }
+  if (threadIdx.x != 0) return;
+  s = stat_unpack(red[0]);
+  if (a.argmax_out) a.argmax_out[m] = s.idx;
+  if (a.layer == 0) return;
+  float conf = 1.0f / s.sum;                                          // largest softmax probability
+  if (a.conf_mode == 1) conf = (1.0f - expf(a.scale * (s.z2 - s.zmax))) / s.sum;  // top-1 minus top-2
+  if (a.s.status[m] != 0) {                                           // already accepted: stays accepted
+    if (a.conf_out) a.conf_out[m] = __builtin_nanf("");
+    return;
+  }
+  if (a.conf_out) a.conf_out[m] = conf;
+  const bool accepted = a.forced_exit_layer ? (a.layer >= a.forced_exit_layer[m]) : (conf > a.threshold);
+  if (!accepted) return;
+  a.s.status[m] = 1;
+  a.s.exit_layer[m] = a.layer;
+  const int before = atomicAdd(a.s.n_exited, 1);
+  if (before + 1 == a.B) {
+    *a.s.batch_exit_layer = a.layer;
+    *a.s.done = 1;
+  }
+}
+
+}  // namespace
+
+void launch_iter_init(const IterState& s, int B, int n_layers, float* conf_out, float* zero_buf, size_t zero_count,
+                      hipStream_t st) {
+  size_t work = (size_t)B * n_layers;
+  if (zero_count > work) work = zero_count;
+  int blocks = (int)((work + 255) / 256);
+  if (blocks < 1) blocks = 1;
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(iter_init_kernel, dim3(blocks), dim3(256), 0, st, s, B, n_layers, conf_out, zero_buf, zero_count);
+}
+void launch_embed_bf16(const bf16_t* E, const int32_t* tokens, float* hT, int B, int Mpad, int d, hipStream_t st) {
+  hipLaunchKernelGGL(embed_bf16_kernel, dim3((d + 7) / 8, Mpad / 32), dim3(32, 8), 0, st, E, tokens, hT, B, Mpad, d);
+}
+void launch_embed_f32(const float* E, const int32_t* tokens, float* h, int B, int d, hipStream_t st) {
+  hipLaunchKernelGGL(embed_f32_kernel, dim3((d + 255) / 256, B), dim3(256), 0, st, E, tokens, h, B, d);
+}
+void launch_hidden_to_ht(const float* plain, float* hT, int B, int Mpad, int d, hipStream_t st) {
+  hipLaunchKernelGGL(hidden_to_ht_kernel, dim3((d + 7) / 8, Mpad / 32), dim3(32, 8), 0, st, plain, hT, B, Mpad, d);
+}
+void launch_ht_to_hidden(const float* hT, float* plain, int B, int Mpad, int d, hipStream_t st) {
+  hipLaunchKernelGGL(ht_to_hidden_kernel, dim3((d + 7) / 8, Mpad / 32), dim3(32, 8), 0, st, hT, plain, B, Mpad, d);
+}
+void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t st) {
+  int blocks = (int)((n + 255) / 256);
+  if (blocks > 2048) blocks = 2048;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks), dim3(256), 0, st, src, dst, n);
+}
+void launch_rowsq(const float* hT, float* rowsq, int Mpad, int d, Pred pred, hipStream_t st) {
+  hipLaunchKernelGGL(rowsq_kernel, dim3((d + 255) / 256, Mpad / 32), dim3(256), 0, st, hT, rowsq, Mpad, d, pred);
+}
+void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, float eps, int Mpad, int d,
+                   Pred pred, hipStream_t st) {
+  GainTable none{};
+  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 1), dim3(256), 0, st, hT, none, gain, xT, (size_t)0, rowsq, eps,
+                     (const int32_t*)nullptr, 0, 0, Mpad, d, pred);
+}
+void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
+                          float eps, const int32_t* fill_from, int fill_from_stride, int B, int Mpad, int d, Pred pred,
+                          hipStream_t st) {
+  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, n_layers), dim3(256), 0, st, hT, gains,
+                     (const bf16_t*)nullptr, xT_slabs, (size_t)Mpad * d, rowsq, eps, fill_from, fill_from_stride, B, Mpad,
+                     d, pred);
+}
+void launch_rmsnorm_f32(const float* h, const float* gain, float* x, int B, int d, float eps, Pred pred, hipStream_t st) {
+  hipLaunchKernelGGL(rmsnorm_f32_kernel, dim3(B), dim3(256), 0, st, h, gain, x, d, eps, pred);
+}
+void launch_head_stats_f32(const float* logits, float4* partials, int B, int vocab, float scale, Pred pred,
+                           hipStream_t st) {
+  hipLaunchKernelGGL(head_stats_f32_kernel, dim3(B), dim3(256), 0, st, logits, partials, vocab, scale, pred);
+}
+void launch_combine(const CombineArgs& a, Pred pred, hipStream_t st) {
+  hipLaunchKernelGGL(combine_kernel, dim3(a.B), dim3(256), 0, st, a, pred);
+}
+
+}  // namespace ee
