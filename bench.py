@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Decode throughput of the early-exit decode step on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A "step" is one decode iteration of the whole batch (Algorithm 1: layer loop with exit checks, KV filling,
+token selection).  The workload is the Llama-7B-shaped batch-32 configuration: random-init bf16 weights,
+32 prompts of 512 uniform-random tokens prefilled through the decode step itself (full layers), then W + K
+greedy decode iterations.  Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+value      = early-exit decode tokens/s (threshold 0.9, exit head after every layer), batch * K / wall time
+also       = the same K iterations on the full-layer path (no exit heads) and with a threshold that never
+             fires (checks paid, nothing skipped), per-kernel-class times from HIP events, roofline of the
+             dominant kernel, exit-layer histogram, and the CPU oracle timed on one iteration.
+"""
+import argparse
+import collections
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def algorithmic_bytes(cfg, cls, mean_ctx_plus1):
+    """Bytes one launch of a kernel class must move (weights once; K and V of every cached position once)."""
+    d, f, V, B = cfg.d_model, cfg.d_ffn, cfg.vocab, cfg.batch
+    return {
+        "qkv": 3 * d * d * 2,
+        "o_proj": d * d * 2,
+        "gate_up": 2 * f * d * 2,
+        "down": d * f * 2,
+        "head": V * d * 2,
+        "attention": int(B * mean_ctx_plus1 * 2 * d * 2),
+    }.get(cls)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", type=int, default=1, help="index into the benchmark configs (default 1: 7B shape, batch 32)")
+    ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; invalidates the result)")
+    ap.add_argument("--profile-steps", type=int, default=8)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--modes", default="ee,full,never")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2407_20272_amd import binding as B
+    from paper_2407_20272_amd import workloads as W
+
+    B.lib()                                   # no fallback: raises if the HIP library is missing
+    torch.cuda.set_device(0)
+    cfg = W.CONFIGS[args.config]
+    if args.layers:
+        cfg = cfg.with_(n_layers=args.layers, name=cfg.name + f"_{args.layers}layers_DEBUG")
+    K, Wm, P = args.steps, args.warmup, args.profile_steps
+    Bsz, n = cfg.batch, cfg.n_layers
+    t0 = time.time()
+    w = W.make_weights(cfg, seed=0, device="cuda")
+    w_cpu = None if args.no_cpu_baseline else W.weights_to(w, "cpu")
+    model = B.DeviceModel(cfg, w)
+    del w
+    torch.cuda.empty_cache()
+    lens = W.make_context_lens(cfg, seed=0)
+    prompts = W.make_prompts(cfg, seed=0, device="cuda")
+    extra = Wm + K + P + 1
+    bt, nb = W.make_block_tables(lens, extra, cfg.block_size, cfg.shuffled_blocks, 0)
+    cache = B.PagedKV(cfg, nb)
+    bt_dev = bt.cuda()
+    max_ctx = int(lens.max()) + extra
+    ws = B.Workspace(model.desc, Bsz, max_ctx)
+    out_tok = torch.zeros(Bsz, dtype=torch.int32, device="cuda")
+    out_exit = torch.zeros(Bsz, dtype=torch.int32, device="cuda")
+    out_L = torch.zeros(1, dtype=torch.int32, device="cuda")
+    tokens = torch.zeros(Bsz, dtype=torch.int32, device="cuda")
+    ctx = torch.zeros(Bsz, dtype=torch.int32, device="cuda")
+    batch = B.make_batch(tokens, ctx, bt_dev, max_ctx)
+
+    # ---- prefill: teacher-forced through the decode step, no exit heads (positions 0 .. len-1) ----------
+    lens_dev = lens.cuda()
+    first = torch.zeros(Bsz, dtype=torch.int32, device="cuda")
+    assert int(lens.min()) == int(lens.max()), "bench prefill assumes equal prompt lengths"
+    for t in range(int(lens.max())):
+        tokens.copy_(prompts[:, t])
+        ctx.fill_(t)
+        B.ee_decode_iteration(model, cache, batch, 2.0, None, False, out_tok, out_exit, out_L, None, None, ws)
+    first.copy_(out_tok)
+    torch.cuda.synchronize()
+    setup_s = time.time() - t0
+
+    L_log = torch.zeros(Wm + K + P, dtype=torch.int32, device="cuda")
+    E_log = torch.zeros(Wm + K + P, Bsz, dtype=torch.int32, device="cuda")
+
+    def run(mode, steps, start):
+        thr = {"ee": cfg.threshold, "full": 2.0, "never": 2.0}[mode]
+        heads = mode != "full"
+        for s in range(steps):
+            B.ee_decode_iteration(model, cache, batch, thr, None, heads, out_tok, out_exit, out_L, None, None, ws)
+            L_log[start + s].copy_(out_L[0])
+            E_log[start + s].copy_(out_exit)
+            tokens.copy_(out_tok)
+            ctx.add_(1)
+
+    results = {}
+    prof = {}
+    for mode in args.modes.split(","):
+        tokens.copy_(first)
+        ctx.copy_(lens_dev)
+        run(mode, Wm, 0)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        run(mode, K, Wm)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t1
+        Ls = L_log[Wm:Wm + K].cpu().tolist()
+        Es = E_log[Wm:Wm + K].cpu().flatten().tolist()
+        results[mode] = {"tokens_per_s": Bsz * K / dt, "ms_per_step": dt / K * 1e3,
+                         "mean_batch_exit_layer": sum(Ls) / len(Ls),
+                         "batch_exit_layer_hist": dict(sorted(collections.Counter(Ls).items())),
+                         "mean_seq_exit_layer": sum(Es) / len(Es)}
+        # instrumented pass: HIP events around every kernel, on the stream the kernels run on
+        if P > 0:
+            ctx_before = ctx.clone()
+            B.ee_profile_enable(True)
+            run(mode, P, Wm + K)
+            torch.cuda.synchronize()
+            B.ee_profile_enable(False)
+            recs = B.ee_profile_read()
+            Lp = L_log[Wm + K:Wm + K + P].cpu().tolist()
+            mean_ctx1 = float(ctx_before.float().mean()) + 1 + (P - 1) / 2.0
+            per_iter = len(recs) // P
+            agg = collections.defaultdict(lambda: [0, 0.0])
+            for it in range(P):
+                for cls, layer, ms in recs[it * per_iter:(it + 1) * per_iter]:
+                    # kernels of layers above the batch exit layer return at once; KV filling only runs after an
+                    # early exit; the final LM pass (recorded at layer n) only when the loop reached layer n
+                    executed = (Lp[it] < n) if cls == "kv_fill" else (layer == 0 or layer <= Lp[it])
+                    if executed:
+                        agg[cls][0] += 1
+                        agg[cls][1] += ms
+            prof[mode] = {"mean_ctx_plus1": mean_ctx1}
+            for cls, (cnt, ms) in agg.items():
+                avg_us = ms / cnt * 1e3
+                entry = {"launches_per_step": cnt / P, "avg_us": avg_us, "share_of_event_time": None}
+                ab = algorithmic_bytes(cfg, cls, mean_ctx1)
+                if ab:
+                    entry["algorithmic_MB"] = ab / 1e6
+                    entry["GBps"] = ab / (avg_us * 1e-6) / 1e9
+                    entry["frac_hbm_peak"] = entry["GBps"] / HBM_PEAK_GBS
+                prof[mode][cls] = entry
+            tot = sum(v[1] for v in agg.values())
+            for cls, (cnt, ms) in agg.items():
+                prof[mode][cls]["share_of_event_time"] = ms / tot
+
+    head_mode = "ee" if "ee" in results else next(iter(results))
+    r = results[head_mode]
+    # dominant kernel = largest share of the instrumented time among the bandwidth-priced classes
+    roof = None
+    if prof.get(head_mode):
+        cands = [(v["share_of_event_time"], k) for k, v in prof[head_mode].items() if isinstance(v, dict) and "GBps" in v]
+        if cands:
+            _, dom = max(cands)
+            e = prof[head_mode][dom]
+            roof = {"bound": "hbm", "kernel": dom, "achieved": e["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": e["frac_hbm_peak"], "traffic": None, "avg_us": e["avg_us"],
+                    "algorithmic_bytes_per_launch": e["algorithmic_MB"] * 1e6}
+
+    # ---- CPU oracle on a bounded sample: ONE decode iteration of the same workload (all sequences) ----------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import ee_oracle as O
+        m = O.model_from_config(cfg, w_cpu)
+        c0 = int(lens.max())
+        Ks = [W.paged_to_dense(cache.k[i], bt, c0 + 1).cpu() for i in range(n)]
+        Vs = [W.paged_to_dense(cache.v[i], bt, c0 + 1).cpu() for i in range(n)]
+        oc = O.DenseKV.from_tensors(Ks, Vs, lens, cfg.dtype)
+        del Ks, Vs
+        t1 = time.perf_counter()
+        O.decode_iteration(m, oc, first.cpu(), lens.long(), cfg.threshold)
+        dt = time.perf_counter() - t1
+        cpu = {"value": Bsz / dt, "unit": "tokens/s", "cores": torch.get_num_threads(), "kind": "oracle",
+               "sample": f"1 early-exit decode iteration of the same workload (batch {Bsz}, context {c0}, "
+                         f"{n} layers), {dt:.1f} s; tokens/s = batch / that time"}
+
+    line = {
+        "metric": "decode tokens/sec/GPU early-exit vs full-layer; HBM GB/s + MFMA util %",
+        "value": r["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": Bsz, "prompt_len": int(lens.max()), "layers": n, "d_model": cfg.d_model,
+                   "vocab": cfg.vocab, "threshold": cfg.threshold, "logit_scale": cfg.logit_scale,
+                   "exit_every": cfg.exit_every, "kv_block": cfg.block_size, "mode": head_mode},
+        "modes": results,
+        "speedup_ee_vs_full": (results["ee"]["tokens_per_s"] / results["full"]["tokens_per_s"])
+        if "ee" in results and "full" in results else None,
+        "roofline": roof, "kernels": prof, "cpu_baseline": cpu, "setup_s": setup_s,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -169,6 +169,26 @@ int ee_paged_attention_decode(const ee_model_desc* desc, const ee_kv_cache* cach
                               const ee_batch* batch, float* out, void* workspace, size_t workspace_bytes,
                               void* stream);
 
+/* ---- Measurement helpers (not part of the decode path) ------------------------------------------------------
+ * While enabled, every later ee_* call brackets each kernel it enqueues with a pair of HIP events on the call's
+ * stream (the events add a few microseconds per kernel, so throughput is timed with profiling off).
+ * ee_profile_read waits for the recorded events and returns, for up to max_records kernels in launch order,
+ * the kernel class (EE_K_*), the 1-based layer it belongs to (0 = none) and its duration in milliseconds;
+ * the records are then discarded.  Returns the number of records written, or a negative error code. */
+#define EE_K_NORM 0     /* sum of squares + normalised projection input                         */
+#define EE_K_QKV 1      /* QKV projection + rotary + cache write                                */
+#define EE_K_ATTN 2     /* paged decode attention                                               */
+#define EE_K_OPROJ 3    /* output projection + residual                                         */
+#define EE_K_GATEUP 4   /* gate/up projection + SwiGLU                                          */
+#define EE_K_DOWN 5     /* down projection + residual                                           */
+#define EE_K_HEAD 6     /* exit head / LM head projection with softmax statistics               */
+#define EE_K_COMBINE 7  /* exit decision                                                        */
+#define EE_K_KVFILL 8   /* KV filling projection                                                */
+#define EE_K_OTHER 9    /* state reset, embedding, copies                                       */
+#define EE_K_CLASSES 10
+int ee_profile_enable(int32_t on);
+int ee_profile_read(int32_t* kernel_class /*host*/, int32_t* layer /*host*/, float* ms /*host*/, int32_t max_records);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,7 +19,8 @@ EE_ERR_INVALID_ARG, EE_ERR_SHAPE, EE_ERR_UNSUPPORTED, EE_ERR_WORKSPACE, EE_ERR_H
 EE_FP32, EE_BF16 = 0, 1
 EE_PACK_PLAIN, EE_PACK_QKV, EE_PACK_GATE_UP = 0, 1, 2
 EXPORTS = ["ee_last_error", "ee_packed_weight_bytes", "ee_pack_weight", "ee_workspace_bytes", "ee_decode_iteration",
-           "ee_exit_check", "ee_kv_fill", "ee_paged_attention_decode"]
+           "ee_exit_check", "ee_kv_fill", "ee_paged_attention_decode", "ee_profile_enable", "ee_profile_read"]
+KERNEL_CLASSES = ["norm", "qkv", "attention", "o_proj", "gate_up", "down", "head", "combine", "kv_fill", "other"]
 
 
 class ee_model_desc(C.Structure):
@@ -79,6 +80,10 @@ def lib() -> C.CDLL:
                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.ee_paged_attention_decode.argtypes = [C.POINTER(ee_model_desc), C.POINTER(ee_kv_cache), C.c_int32, C.c_void_p,
                                                 C.POINTER(ee_batch), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.ee_profile_enable.argtypes = [C.c_int32]
+        L.ee_profile_read.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int32]
+        L.ee_profile_enable.restype = C.c_int
+        L.ee_profile_read.restype = C.c_int
         for name in ("ee_pack_weight", "ee_decode_iteration", "ee_exit_check", "ee_kv_fill", "ee_paged_attention_decode"):
             getattr(L, name).restype = C.c_int
         _lib = L
@@ -232,3 +237,18 @@ def ee_paged_attention_decode(desc: ee_model_desc, cache: PagedKV, layer: int, q
                               ws: Optional[Workspace] = None):
     _check(lib().ee_paged_attention_decode(C.byref(desc), C.byref(cache.c), layer, _ptr(q), C.byref(batch), _ptr(out),
                                            _ptr(ws.buf) if ws else None, ws.bytes if ws else 0, _stream()))
+
+
+def ee_profile_enable(on: bool):
+    _check(lib().ee_profile_enable(int(bool(on))))
+
+
+def ee_profile_read(max_records: int = 1 << 20):
+    """Returns a list of (class name, layer, milliseconds) for every kernel enqueued since the last read."""
+    cls = (C.c_int32 * max_records)()
+    lay = (C.c_int32 * max_records)()
+    ms = (C.c_float * max_records)()
+    n = lib().ee_profile_read(cls, lay, ms, max_records)
+    if n < 0:
+        raise EEError(n, ee_last_error())
+    return [(KERNEL_CLASSES[cls[i]], lay[i], ms[i]) for i in range(n)]

@@ -3,6 +3,9 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
+#include <vector>
+
 #include "ee_common.h"
 
 namespace ee {
@@ -17,6 +20,47 @@ void set_error(const char* fmt, ...) {
 }
 
 namespace {
+
+// ---- optional per-kernel timing with HIP events --------------------------------------------------------
+struct ProfRecord {
+  int cls, layer;
+  hipEvent_t start, stop;
+};
+struct Profiler {
+  bool on = false;
+  std::vector<ProfRecord> used;
+  std::vector<hipEvent_t> spare;
+  hipEvent_t get() {
+    if (!spare.empty()) {
+      hipEvent_t e = spare.back();
+      spare.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+};
+Profiler g_prof;
+std::mutex g_prof_mutex;
+
+// Brackets the launches made inside its scope with one event pair.
+struct ProfScope {
+  hipStream_t st;
+  hipEvent_t stop = nullptr;
+  ProfScope(int cls, int layer, hipStream_t s) : st(s) {
+    if (!g_prof.on) return;
+    std::lock_guard<std::mutex> lk(g_prof_mutex);
+    hipEvent_t a = g_prof.get(), b = g_prof.get();
+    if (!a || !b) return;
+    g_prof.used.push_back({cls, layer, a, b});
+    (void)hipEventRecord(a, st);
+    stop = b;
+  }
+  ~ProfScope() {
+    if (stop) (void)hipEventRecord(stop, st);
+  }
+};
 
 struct Carver {
   char* base;
@@ -178,15 +222,21 @@ QkvEpi make_qkv_epi(const ee_model_desc& D, const ee_kv_cache& C, const ee_batch
 
 // --- exit head: statistics of (scale * logits) for every row of the hidden state ------------------------
 void enqueue_head_bf16(const ee_model& M, const Workspace& w, int B, int Mpad, float scale, const float* rowsq_slot,
-                       Pred pred, hipStream_t st) {
+                       int layer, Pred pred, hipStream_t st) {
   const ee_model_desc& D = M.desc;
-  launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(M.g_final), w.xT, rowsq_slot, D.rms_eps, Mpad, D.d_model, pred, st);
+  {
+    ProfScope ps(EE_K_NORM, layer, st);
+    launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(M.g_final), w.xT, rowsq_slot, D.rms_eps, Mpad, D.d_model, pred, st);
+  }
   GemmShape g{M.w_lm, w.xT, D.d_model, B, 0, D.vocab / 32, 16, 1};
   LmEpi e{w.partials, nullptr, D.vocab / 32, D.vocab, scale, nullptr, D.rms_eps, D.d_model};
+  ProfScope ps(EE_K_HEAD, layer, st);
   launch_gemm_lm_bf16(g, e, pred, st);
 }
-void enqueue_head_f32(const ee_model& M, const Workspace& w, const float* h, int B, float scale, Pred pred, hipStream_t st) {
+void enqueue_head_f32(const ee_model& M, const Workspace& w, const float* h, int B, float scale, int layer, Pred pred,
+                      hipStream_t st) {
   const ee_model_desc& D = M.desc;
+  ProfScope ps(EE_K_HEAD, layer, st);
   launch_rmsnorm_f32(h, reinterpret_cast<const float*>(M.g_final), w.x, B, D.d_model, D.rms_eps, pred, st);
   SimpleShape g{reinterpret_cast<const float*>(M.w_lm), w.x, D.d_model, B, 0, D.vocab, 1};
   LmEpi e{w.partials, w.logits, 1, D.vocab, scale, nullptr, D.rms_eps, D.d_model};
@@ -204,6 +254,7 @@ void enqueue_fill_bf16(const ee_model& M, const ee_kv_cache& C, const ee_batch& 
     gt.g[i] = M.layers[i].g_attn;
     fl.w_qkv[i] = M.layers[i].w_qkv;
   }
+  ProfScope ps(EE_K_KVFILL, 0, st);
   launch_rowsq(w.hT, rowsq_slot, Mpad, D.d_model, pred, st);
   launch_prep_x_layers(w.hT, gt, D.n_layers, w.fill_x, rowsq_slot, D.rms_eps, fill_from, stride, Bt.batch, Mpad, D.d_model,
                        pred, st);
@@ -216,6 +267,7 @@ void enqueue_fill_bf16(const ee_model& M, const ee_kv_cache& C, const ee_batch& 
 void enqueue_fill_f32(const ee_model& M, const ee_kv_cache& C, const ee_batch& Bt, const Workspace& w, const float* h,
                       const int32_t* fill_from, int stride, Pred pred, hipStream_t st) {
   const ee_model_desc& D = M.desc;
+  ProfScope ps(EE_K_KVFILL, 0, st);
   for (int i = 1; i <= D.n_layers; ++i) {
     const ee_layer_weights& L = M.layers[i - 1];
     launch_rmsnorm_f32(h, reinterpret_cast<const float*>(L.g_attn), w.x, Bt.batch, D.d_model, D.rms_eps, pred, st);
@@ -236,6 +288,33 @@ using namespace ee;
 extern "C" {
 
 const char* ee_last_error(void) { return g_error; }
+
+int ee_profile_enable(int32_t on) {
+  std::lock_guard<std::mutex> lk(g_prof_mutex);
+  g_prof.on = on != 0;
+  return EE_OK;
+}
+
+int ee_profile_read(int32_t* kernel_class, int32_t* layer, float* ms, int32_t max_records) {
+  if (!kernel_class || !layer || !ms || max_records < 0) EE_FAIL(EE_ERR_INVALID_ARG, "ee_profile_read: bad argument");
+  std::lock_guard<std::mutex> lk(g_prof_mutex);
+  int n = 0;
+  for (ProfRecord& r : g_prof.used) {
+    EE_HIP(hipEventSynchronize(r.stop));
+    float t = 0.0f;
+    EE_HIP(hipEventElapsedTime(&t, r.start, r.stop));
+    if (n < max_records) {
+      kernel_class[n] = r.cls;
+      layer[n] = r.layer;
+      ms[n] = t;
+      ++n;
+    }
+    g_prof.spare.push_back(r.start);
+    g_prof.spare.push_back(r.stop);
+  }
+  g_prof.used.clear();
+  return n;
+}
 
 size_t ee_packed_weight_bytes(int32_t n_out, int32_t n_in) {
   if (n_out <= 0 || n_in <= 0) return 0;
@@ -290,15 +369,19 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   const Pred run_fill{w.done, 1};    // KV filling: only after it has
   const Pred always{nullptr, 0};
 
-  // Algorithm 1, initialisation
-  launch_iter_init(s, B, n, out_conf, bf ? w.rowsq : nullptr, bf ? (size_t)(2 * n + 2) * Mpad : 0, st);
-  if (bf)
-    launch_embed_bf16(reinterpret_cast<const bf16_t*>(model->embed), batch->tokens, w.hT, B, Mpad, d, st);
-  else
-    launch_embed_f32(reinterpret_cast<const float*>(model->embed), batch->tokens, w.h, B, d, st);
-  // rowsq slot 0: after the embedding; slot 2i-1: after layer i's attention update; slot 2i: after layer i
+  // Algorithm 1, initialisation.  rowsq slot 0: after the embedding; slot 2i-1: after layer i's attention
+  // update; slot 2i: after layer i.
   auto rs = [&](int slot) { return w.rowsq + (size_t)slot * Mpad; };
-  if (bf) launch_rowsq(w.hT, rs(0), Mpad, d, always, st);
+  {
+    ProfScope ps(EE_K_OTHER, 0, st);
+    launch_iter_init(s, B, n, out_conf, bf ? w.rowsq : nullptr, bf ? (size_t)(2 * n + 2) * Mpad : 0, st);
+    if (bf) {
+      launch_embed_bf16(reinterpret_cast<const bf16_t*>(model->embed), batch->tokens, w.hT, B, Mpad, d, st);
+      launch_rowsq(w.hT, rs(0), Mpad, d, always, st);
+    } else {
+      launch_embed_f32(reinterpret_cast<const float*>(model->embed), batch->tokens, w.h, B, d, st);
+    }
+  }
 
   // Algorithm 1, batch inference loop.  Everything is enqueued; the done flag turns later layers into no-ops.
   for (int i = 1; i <= n; ++i) {
@@ -307,44 +390,84 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     AttnArgs at{w.q, reinterpret_cast<char*>(cache->k_pool) + pool_off, reinterpret_cast<char*>(cache->v_pool) + pool_off,
                 batch->context_lens, batch->block_tables, batch->max_blocks, B, D.n_heads, D.head_dim, nullptr, 0};
     if (bf) {
-      launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_attn), w.xT, rs(2 * i - 2), D.rms_eps, Mpad, d, run_layers, st);
-      GemmShape gq{L.w_qkv, w.xT, d, B, 0, 3 * d / 32, D.head_dim / 2, 1};
-      launch_gemm_qkv_bf16(gq, make_qkv_epi(D, *cache, *batch, i, w.q, nullptr), run_layers, st);
-      at.out = w.aoT;
-      at.out_xt = 1;
-      if ((rc = launch_attention(at, D.dtype, run_layers, st))) return rc;
-      GemmShape go{L.w_o, w.aoT, d, B, 0, d / 32, 16, acc_ksplit(d / 32, d)};
-      launch_gemm_acc_bf16(go, AccEpi{w.hT, Mpad, d}, run_layers, st);
-      launch_rowsq(w.hT, rs(2 * i - 1), Mpad, d, run_layers, st);
-      launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_ffn), w.xT, rs(2 * i - 1), D.rms_eps, Mpad, d, run_layers, st);
-      GemmShape gg{L.w_gate_up, w.xT, d, B, 0, 2 * f / 32, f, 1};
-      launch_gemm_gateup_bf16(gg, GateUpEpi{w.actT, f, nullptr, D.rms_eps, d}, run_layers, st);
-      GemmShape gd{L.w_down, w.actT, f, B, 0, d / 32, 16, acc_ksplit(d / 32, f)};
-      launch_gemm_acc_bf16(gd, AccEpi{w.hT, Mpad, d}, run_layers, st);
-      launch_rowsq(w.hT, rs(2 * i), Mpad, d, run_layers, st);
+      {
+        ProfScope ps(EE_K_NORM, i, st);
+        launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_attn), w.xT, rs(2 * i - 2), D.rms_eps, Mpad, d, run_layers, st);
+      }
+      {
+        ProfScope ps(EE_K_QKV, i, st);
+        GemmShape gq{L.w_qkv, w.xT, d, B, 0, 3 * d / 32, D.head_dim / 2, 1};
+        launch_gemm_qkv_bf16(gq, make_qkv_epi(D, *cache, *batch, i, w.q, nullptr), run_layers, st);
+      }
+      {
+        ProfScope ps(EE_K_ATTN, i, st);
+        at.out = w.aoT;
+        at.out_xt = 1;
+        if ((rc = launch_attention(at, D.dtype, run_layers, st))) return rc;
+      }
+      {
+        ProfScope ps(EE_K_OPROJ, i, st);
+        GemmShape go{L.w_o, w.aoT, d, B, 0, d / 32, 16, acc_ksplit(d / 32, d)};
+        launch_gemm_acc_bf16(go, AccEpi{w.hT, Mpad, d}, run_layers, st);
+      }
+      {
+        ProfScope ps(EE_K_NORM, i, st);
+        launch_rowsq(w.hT, rs(2 * i - 1), Mpad, d, run_layers, st);
+        launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_ffn), w.xT, rs(2 * i - 1), D.rms_eps, Mpad, d, run_layers, st);
+      }
+      {
+        ProfScope ps(EE_K_GATEUP, i, st);
+        GemmShape gg{L.w_gate_up, w.xT, d, B, 0, 2 * f / 32, f, 1};
+        launch_gemm_gateup_bf16(gg, GateUpEpi{w.actT, f, nullptr, D.rms_eps, d}, run_layers, st);
+      }
+      {
+        ProfScope ps(EE_K_DOWN, i, st);
+        GemmShape gd{L.w_down, w.actT, f, B, 0, d / 32, 16, acc_ksplit(d / 32, f)};
+        launch_gemm_acc_bf16(gd, AccEpi{w.hT, Mpad, d}, run_layers, st);
+      }
+      {
+        ProfScope ps(EE_K_NORM, i, st);
+        launch_rowsq(w.hT, rs(2 * i), Mpad, d, run_layers, st);
+      }
     } else {
-      launch_rmsnorm_f32(w.h, reinterpret_cast<const float*>(L.g_attn), w.x, B, d, D.rms_eps, run_layers, st);
-      SimpleShape gq{reinterpret_cast<const float*>(L.w_qkv), w.x, d, B, 0, 3 * d, D.head_dim / 2};
-      launch_simple_qkv(gq, make_qkv_epi(D, *cache, *batch, i, w.q, nullptr), run_layers, st);
-      at.out = w.ao;
-      at.out_xt = 0;
-      if ((rc = launch_attention(at, D.dtype, run_layers, st))) return rc;
-      SimpleShape go{reinterpret_cast<const float*>(L.w_o), w.ao, d, B, 0, d, 1};
-      launch_simple_acc(go, AccEpi{w.h, 0, d}, run_layers, st);
-      launch_rmsnorm_f32(w.h, reinterpret_cast<const float*>(L.g_ffn), w.x, B, d, D.rms_eps, run_layers, st);
-      SimpleShape gg{reinterpret_cast<const float*>(L.w_gate_up), w.x, d, B, 0, 2 * f, f};
-      launch_simple_gateup(gg, GateUpEpi{w.act, f, nullptr, D.rms_eps, d}, run_layers, st);
-      SimpleShape gd{reinterpret_cast<const float*>(L.w_down), w.act, f, B, 0, d, 1};
-      launch_simple_acc(gd, AccEpi{w.h, 0, d}, run_layers, st);
+      {
+        ProfScope ps(EE_K_QKV, i, st);
+        launch_rmsnorm_f32(w.h, reinterpret_cast<const float*>(L.g_attn), w.x, B, d, D.rms_eps, run_layers, st);
+        SimpleShape gq{reinterpret_cast<const float*>(L.w_qkv), w.x, d, B, 0, 3 * d, D.head_dim / 2};
+        launch_simple_qkv(gq, make_qkv_epi(D, *cache, *batch, i, w.q, nullptr), run_layers, st);
+      }
+      {
+        ProfScope ps(EE_K_ATTN, i, st);
+        at.out = w.ao;
+        at.out_xt = 0;
+        if ((rc = launch_attention(at, D.dtype, run_layers, st))) return rc;
+      }
+      {
+        ProfScope ps(EE_K_OPROJ, i, st);
+        SimpleShape go{reinterpret_cast<const float*>(L.w_o), w.ao, d, B, 0, d, 1};
+        launch_simple_acc(go, AccEpi{w.h, 0, d}, run_layers, st);
+      }
+      {
+        ProfScope ps(EE_K_GATEUP, i, st);
+        launch_rmsnorm_f32(w.h, reinterpret_cast<const float*>(L.g_ffn), w.x, B, d, D.rms_eps, run_layers, st);
+        SimpleShape gg{reinterpret_cast<const float*>(L.w_gate_up), w.x, d, B, 0, 2 * f, f};
+        launch_simple_gateup(gg, GateUpEpi{w.act, f, nullptr, D.rms_eps, d}, run_layers, st);
+      }
+      {
+        ProfScope ps(EE_K_DOWN, i, st);
+        SimpleShape gd{reinterpret_cast<const float*>(L.w_down), w.act, f, B, 0, d, 1};
+        launch_simple_acc(gd, AccEpi{w.h, 0, d}, run_layers, st);
+      }
     }
     if (use_exit_heads && has_head(D, i)) {
       const float scale = D.logit_scale * (float)i;
       if (bf)
-        enqueue_head_bf16(*model, w, B, Mpad, scale, rs(2 * i), run_layers, st);
+        enqueue_head_bf16(*model, w, B, Mpad, scale, rs(2 * i), i, run_layers, st);
       else
-        enqueue_head_f32(*model, w, w.h, B, scale, run_layers, st);
+        enqueue_head_f32(*model, w, w.h, B, scale, i, run_layers, st);
       CombineArgs ca{w.partials, bf ? D.vocab / 32 : 1, B, i, scale, thresholds[i - 1], D.conf_mode, forced_exit_layer, s,
                      out_tokens, out_conf ? out_conf + (size_t)(i - 1) * B : nullptr};
+      ProfScope ps(EE_K_COMBINE, i, st);
       launch_combine(ca, run_layers, st);
     }
   }
@@ -361,10 +484,11 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   // hidden state already is the token; the LM head is only streamed again when the loop ran to the last layer.
   {
     if (bf)
-      enqueue_head_bf16(*model, w, B, Mpad, 0.0f, rs(2 * n), run_layers, st);
+      enqueue_head_bf16(*model, w, B, Mpad, 0.0f, rs(2 * n), n, run_layers, st);
     else
-      enqueue_head_f32(*model, w, w.h, B, 0.0f, run_layers, st);
+      enqueue_head_f32(*model, w, w.h, B, 0.0f, n, run_layers, st);
     CombineArgs ca{w.partials, bf ? D.vocab / 32 : 1, B, 0, 0.0f, 0.0f, 0, nullptr, s, out_tokens, nullptr};
+    ProfScope ps(EE_K_COMBINE, n, st);
     launch_combine(ca, run_layers, st);
   }
   if (out_hidden) {
@@ -401,9 +525,9 @@ int ee_exit_check(const ee_model* model, int32_t layer, const float* hidden, int
                      w.rowsq, (size_t)Mpad, st);
     launch_hidden_to_ht(hidden, w.hT, batch, Mpad, D.d_model, st);
     launch_rowsq(w.hT, w.rowsq, Mpad, D.d_model, always, st);
-    enqueue_head_bf16(*model, w, batch, Mpad, scale, w.rowsq, always, st);
+    enqueue_head_bf16(*model, w, batch, Mpad, scale, w.rowsq, layer, always, st);
   } else {
-    enqueue_head_f32(*model, w, hidden, batch, scale, always, st);
+    enqueue_head_f32(*model, w, hidden, batch, scale, layer, always, st);
   }
   IterState s{status, exit_layer, n_exited, done_flag, batch_exit_layer};
   CombineArgs ca{w.partials, D.dtype == EE_BF16 ? D.vocab / 32 : 1, batch, layer, scale, threshold, D.conf_mode,
