@@ -49,6 +49,7 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--modes", default="ee,full,never")
+    ap.add_argument("--no-graph", action="store_true", help="enqueue every iteration eagerly instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -98,45 +99,70 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.time() - t0
 
-    L_log = torch.zeros(Wm + K + P, dtype=torch.int32, device="cuda")
-    E_log = torch.zeros(Wm + K + P, Bsz, dtype=torch.int32, device="cuda")
+    # Per-iteration bookkeeping stays on the device so that one iteration (decode step + token feedback + position
+    # advance + histograms) is a fixed sequence of kernels: it is captured once per mode into a HIP graph and
+    # replayed, which removes the per-launch host cost of the ~300-400 kernels of an iteration.
+    L_hist = torch.zeros(n + 1, dtype=torch.int32, device="cuda")
+    E_hist = torch.zeros(n + 1, dtype=torch.int32, device="cuda")
+    one1 = torch.ones(1, dtype=torch.int32, device="cuda")
+    oneB = torch.ones(Bsz, dtype=torch.int32, device="cuda")
+    L_last = torch.zeros(P + 1, dtype=torch.int32, device="cuda")
 
-    def run(mode, steps, start):
+    def iteration(mode):
         thr = {"ee": cfg.threshold, "full": 2.0, "never": 2.0}[mode]
-        heads = mode != "full"
-        for s in range(steps):
-            B.ee_decode_iteration(model, cache, batch, thr, None, heads, out_tok, out_exit, out_L, None, None, ws)
-            L_log[start + s].copy_(out_L[0])
-            E_log[start + s].copy_(out_exit)
-            tokens.copy_(out_tok)
-            ctx.add_(1)
+        B.ee_decode_iteration(model, cache, batch, thr, None, mode != "full", out_tok, out_exit, out_L, None, None, ws)
+        L_hist.scatter_add_(0, out_L.long(), one1)
+        E_hist.scatter_add_(0, out_exit.long(), oneB)
+        torch.add(out_tok, 0, out=tokens)          # next iteration consumes the tokens just produced
+        ctx.add_(1)
 
     results = {}
     prof = {}
+    side = torch.cuda.Stream()
     for mode in args.modes.split(","):
         tokens.copy_(first)
         ctx.copy_(lens_dev)
-        run(mode, Wm, 0)
+        graph = None
+        if not args.no_graph:
+            with torch.cuda.stream(side):
+                iteration(mode)                     # warm every lazy initialisation outside the capture
+                torch.cuda.synchronize()
+                tokens.copy_(first)
+                ctx.copy_(lens_dev)
+                graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(graph, stream=side):
+                    iteration(mode)
+            torch.cuda.synchronize()
+            tokens.copy_(first)
+            ctx.copy_(lens_dev)
+        step = graph.replay if graph is not None else (lambda: iteration(mode))
+        for _ in range(Wm):
+            step()
+        L_hist.zero_()
+        E_hist.zero_()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        run(mode, K, Wm)
+        for _ in range(K):
+            step()
         torch.cuda.synchronize()
         dt = time.perf_counter() - t1
-        Ls = L_log[Wm:Wm + K].cpu().tolist()
-        Es = E_log[Wm:Wm + K].cpu().flatten().tolist()
+        Lh, Eh = L_hist.cpu().tolist(), E_hist.cpu().tolist()
         results[mode] = {"tokens_per_s": Bsz * K / dt, "ms_per_step": dt / K * 1e3,
-                         "mean_batch_exit_layer": sum(Ls) / len(Ls),
-                         "batch_exit_layer_hist": dict(sorted(collections.Counter(Ls).items())),
-                         "mean_seq_exit_layer": sum(Es) / len(Es)}
-        # instrumented pass: HIP events around every kernel, on the stream the kernels run on
+                         "mean_batch_exit_layer": sum(i * c for i, c in enumerate(Lh)) / K,
+                         "batch_exit_layer_hist": {i: c for i, c in enumerate(Lh) if c},
+                         "mean_seq_exit_layer": sum(i * c for i, c in enumerate(Eh)) / (K * Bsz)}
+        # instrumented pass (eager): HIP events around every kernel, on the stream the kernels run on
         if P > 0:
             ctx_before = ctx.clone()
             B.ee_profile_enable(True)
-            run(mode, P, Wm + K)
+            Lp = []
+            for s_ in range(P):
+                iteration(mode)
+                L_last[s_].copy_(out_L[0])
             torch.cuda.synchronize()
             B.ee_profile_enable(False)
             recs = B.ee_profile_read()
-            Lp = L_log[Wm + K:Wm + K + P].cpu().tolist()
+            Lp = L_last[:P].cpu().tolist()
             mean_ctx1 = float(ctx_before.float().mean()) + 1 + (P - 1) / 2.0
             per_iter = len(recs) // P
             agg = collections.defaultdict(lambda: [0, 0.0])
@@ -199,7 +225,8 @@ def main():
         "dtype": "bf16" if cfg.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": cfg.name, "batch": Bsz, "prompt_len": int(lens.max()), "layers": n, "d_model": cfg.d_model,
                    "vocab": cfg.vocab, "threshold": cfg.threshold, "logit_scale": cfg.logit_scale,
-                   "exit_every": cfg.exit_every, "kv_block": cfg.block_size, "mode": head_mode},
+                   "exit_every": cfg.exit_every, "kv_block": cfg.block_size, "mode": head_mode,
+                   "launch": "eager" if args.no_graph else "hip_graph"},
         "modes": results,
         "speedup_ee_vs_full": (results["ee"]["tokens_per_s"] / results["full"]["tokens_per_s"])
         if "ee" in results and "full" in results else None,
