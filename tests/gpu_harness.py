@@ -33,6 +33,46 @@ def assert_close_scaled(got: torch.Tensor, want: torch.Tensor, tol: float, what:
     return err
 
 
+def logit_tol(cfg) -> float:
+    """Logit error (relative to the row's largest |logit|) that the arithmetic itself explains: bf16 rounding of the
+    normalised input (2^-9 per element, random sign) summed over d terms, at the 4-5 sigma tail of a 32000-entry row,
+    plus the drift of the hidden state over tens of layers.  Much tighter than the 2e-2 stated for logits."""
+    return 1e-5 if cfg.dtype == "fp32" else 4e-3
+
+
+def conf_tolerance(cfg, c: float, scale: float, zmax_abs: float) -> float:
+    """How far a confidence may move when every logit moves by at most eps = logit_tol * max|z|: to first order the
+    softmax probability p moves by p(1-p) * 2 * scale * eps.  A floor covers float rounding of the sum itself."""
+    eps = logit_tol(cfg) * zmax_abs
+    return (1e-4 if cfg.dtype == "fp32" else 1e-3) + 2.0 * scale * eps * max(c * (1.0 - c), 0.05)
+
+
+def check_confidences(cfg, m, tr, g_conf, what, lam_l=None, decisions=None):
+    """GPU confidences [n][rows] against the oracle's trace (tr["conf"], tr["h"]).  Returns the largest error.
+    The tolerance of each entry is derived from the logit tolerance through the softmax (conf_tolerance)."""
+    oc = tr["conf"]
+    worst = 0.0
+    for i in range(oc.shape[0]):
+        for b in range(oc.shape[1]):
+            if math.isnan(float(oc[i, b])):
+                continue
+            err = abs(float(g_conf[i, b]) - float(oc[i, b]))
+            worst = max(worst, err)
+            if err > (1e-4 if cfg.dtype == "fp32" else 1e-3):
+                z = O.head_logits(m, tr["h"][i][b:b + 1])
+                tol_c = conf_tolerance(cfg, float(oc[i, b]), cfg.logit_scale * (i + 1), float(z.abs().max()))
+                assert err <= tol_c, f"{what}: confidence of sequence {b} at layer {i + 1}: {float(g_conf[i, b])} vs " \
+                                     f"{float(oc[i, b])}, tolerance {tol_c:.3e}"
+    return worst
+
+
+def near_threshold(cfg, m, tr, i, b, lam_i) -> bool:
+    """Is the oracle's confidence of sequence b at layer i (1-based) within the derived tolerance of the threshold?"""
+    c = float(tr["conf"][i - 1, b])
+    z = O.head_logits(m, tr["h"][i - 1][b:b + 1])
+    return abs(c - lam_i) <= conf_tolerance(cfg, c, cfg.logit_scale * i, float(z.abs().max()))
+
+
 class GpuRun:
     """Device-side state of one workload: model, paged cache, block tables, workspace, output buffers."""
 
@@ -103,8 +143,8 @@ def lockstep(cfg, seed: int, steps: int, thresholds=None, forced_seq=None, heads
              check_untouched=True, weights=None):
     """Full-trajectory parity: prefill + `steps` decode iterations on both sides, compared after every iteration.
 
-    Exit decisions and tokens must agree exactly, except: a decision whose oracle confidence lies within
-    tol*lambda of the threshold (counted; the oracle replays the iteration with the GPU's decisions forced),
+    Exit decisions and tokens must agree exactly, except: a decision whose oracle confidence lies within the
+    derived confidence tolerance of the threshold (counted; the oracle replays with the GPU's decisions forced),
     and a token whose oracle top-2 logit gap is within tol * max|logit| (counted; both continue from the
     oracle's token).  Everything else is an assertion failure.  Returns the counters.
     """
@@ -152,7 +192,7 @@ def lockstep(cfg, seed: int, steps: int, thresholds=None, forced_seq=None, heads
                 if int(g_exit[b]) != int(o_exit[b]):
                     i = min(int(g_exit[b]), int(o_exit[b]))
                     c = float(tr["conf"][i - 1, b])
-                    assert abs(c - lam_l[i - 1]) <= tol * lam_l[i - 1], \
+                    assert near_threshold(cfg, m, tr, i, b, lam_l[i - 1]), \
                         f"step {s}: exit layer of sequence {b} differs (gpu {int(g_exit[b])}, oracle {int(o_exit[b])}), " \
                         f"oracle confidence {c} is not near the threshold {lam_l[i - 1]}"
                     stats["near_threshold"] += 1
@@ -166,9 +206,7 @@ def lockstep(cfg, seed: int, steps: int, thresholds=None, forced_seq=None, heads
         ev = ~oc.isnan()
         assert torch.equal(ev, ~g_conf.isnan()), f"step {s}: different (layer, sequence) pairs were checked"
         if ev.any():
-            err = float((g_conf.to(F64)[ev] - oc[ev]).abs().max())
-            stats["max_conf_err"] = max(stats["max_conf_err"], err)
-            assert err <= tol, f"step {s}: confidence error {err:.3e}"
+            stats["max_conf_err"] = max(stats["max_conf_err"], check_confidences(cfg, m, tr, g_conf, f"step {s}"))
         assert_close_scaled(g_hid, tr["h_exit"], tol, f"step {s}: hidden state at the exit layer", dim=-1)
         token_check(g_tok, o_tok, tr["h_exit"], f"step {s}")
         pos = pos + 1
