@@ -44,6 +44,22 @@ struct Elems<bf16_t> {
   }
 };
 
+// Sum over the LPT lanes that share a token; every lane of the group ends up with the total.
+// Within a 16-lane row the butterfly runs on the DPP cross-lane network (quad permutes, half-row and row
+// mirrors); only a 32-lane group needs one LDS-crossbar shuffle on top.
+template <int LPT>
+__device__ inline float group_sum(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));  // row_half_mirror
+  if constexpr (LPT >= 16)
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));  // row_mirror
+  if constexpr (LPT >= 32) v += __shfl_xor(v, 16);
+  return v;
+}
+
+constexpr int TABLE_LDS = 512;   // block-table entries staged in LDS (contexts up to 8192 tokens)
+
 template <class T, int DH, bool OUT_XT>
 __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred) {
   if (pred_skip(pred)) return;
@@ -62,6 +78,10 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   const int n_blocks = (n_ctx + 15) >> 4;
   const int32_t* table = a.block_tables + (size_t)b * a.max_blocks;
 
+  // the sequence's block table goes to LDS once, so the block loop never waits on a table read
+  __shared__ int32_t tbl[TABLE_LDS];
+  for (int i = threadIdx.x; i < n_blocks && i < TABLE_LDS; i += blockDim.x) tbl[i] = table[i];
+
   // q slice, pre-scaled so that exp2 can be used: softmax(x) = 2^(x*log2 e)
   float q[EPL];
   {
@@ -70,6 +90,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
 #pragma unroll
     for (int i = 0; i < EPL; ++i) q[i] = qp[i] * sc;
   }
+  __syncthreads();
 
   float m_run = NEG_BIG, l_run = 0.0f, o[EPL];
 #pragma unroll
@@ -80,61 +101,60 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   const T* kbase = reinterpret_cast<const T*>(a.k_pool) + head_off + (size_t)grp * DH + sub * EPL;
   const T* vbase = reinterpret_cast<const T*>(a.v_pool) + head_off + (size_t)grp * DH + sub * EPL;
 
-  uint4 kc[LPB], vc[LPB], kn[LPB], vn[LPB];
-  int lb = wave;
-  if (lb < n_blocks) {
-    const size_t off = (size_t)table[lb] * block_elems;
+  struct Blk {
+    uint4 k[LPB], v[LPB];
+  };
+  auto fetch = [&](Blk& x, int lb) {
+    const int phys = lb < TABLE_LDS ? tbl[lb] : table[lb];
+    const size_t off = (size_t)phys * block_elems;
 #pragma unroll
     for (int i = 0; i < LPB; ++i) {
-      kc[i] = *reinterpret_cast<const uint4*>(kbase + off + (size_t)i * TPL * DH);
-      vc[i] = *reinterpret_cast<const uint4*>(vbase + off + (size_t)i * TPL * DH);
+      x.k[i] = *reinterpret_cast<const uint4*>(kbase + off + (size_t)i * TPL * DH);
+      x.v[i] = *reinterpret_cast<const uint4*>(vbase + off + (size_t)i * TPL * DH);
     }
-  }
-  for (; lb < n_blocks; lb += NW) {
-    const int nxt = lb + NW;
-    if (nxt < n_blocks) {
-      const size_t off = (size_t)table[nxt] * block_elems;
-#pragma unroll
-      for (int i = 0; i < LPB; ++i) {
-        kn[i] = *reinterpret_cast<const uint4*>(kbase + off + (size_t)i * TPL * DH);
-        vn[i] = *reinterpret_cast<const uint4*>(vbase + off + (size_t)i * TPL * DH);
-      }
-    }
-    // scores of this lane group's LPB tokens of the block
+  };
+  auto consume = [&](const Blk& x, int lb) {
     float s[LPB];
     float m_new = m_run;
 #pragma unroll
     for (int i = 0; i < LPB; ++i) {
       float kf[EPL];
-      Elems<T>::unpack(kc[i], kf);
+      Elems<T>::unpack(x.k[i], kf);
       float d = 0.0f;
 #pragma unroll
       for (int e = 0; e < EPL; ++e) d = fmaf(q[e], kf[e], d);
-#pragma unroll
-      for (int x = 1; x < LPT; x <<= 1) d += __shfl_xor(d, x);
+      d = group_sum<LPT>(d);
       const int tok = lb * 16 + i * TPL + grp;
       s[i] = tok < n_ctx ? d : NEG_BIG;
       m_new = fmaxf(m_new, s[i]);
     }
-    const float alpha = exp2f(m_run - m_new);
+    const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
     l_run *= alpha;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) o[e] *= alpha;
 #pragma unroll
     for (int i = 0; i < LPB; ++i) {
       const int tok = lb * 16 + i * TPL + grp;
-      const float p = tok < n_ctx ? exp2f(s[i] - m_new) : 0.0f;
+      const float p = tok < n_ctx ? __builtin_amdgcn_exp2f(s[i] - m_new) : 0.0f;
       l_run += p;
       float vf[EPL];
-      Elems<T>::unpack(vc[i], vf);
+      Elems<T>::unpack(x.v[i], vf);
 #pragma unroll
       for (int e = 0; e < EPL; ++e) o[e] = fmaf(p, vf[e], o[e]);
     }
     m_run = m_new;
-#pragma unroll
-    for (int i = 0; i < LPB; ++i) {
-      kc[i] = kn[i];
-      vc[i] = vn[i];
+  };
+
+  // two blocks of this wavefront in flight at any time
+  Blk A, B;
+  if (wave < n_blocks) fetch(A, wave);
+  if (wave + NW < n_blocks) fetch(B, wave + NW);
+  for (int lb = wave; lb < n_blocks; lb += 2 * NW) {
+    consume(A, lb);
+    if (lb + 2 * NW < n_blocks) fetch(A, lb + 2 * NW);
+    if (lb + NW < n_blocks) {
+      consume(B, lb + NW);
+      if (lb + 3 * NW < n_blocks) fetch(B, lb + 3 * NW);
     }
   }
 
@@ -144,7 +164,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
     const float m_o = __shfl_xor(m_run, x);
     const float l_o = __shfl_xor(l_run, x);
     const float m_new = fmaxf(m_run, m_o);
-    const float wa = exp2f(m_run - m_new), wb = exp2f(m_o - m_new);
+    const float wa = __builtin_amdgcn_exp2f(m_run - m_new), wb = __builtin_amdgcn_exp2f(m_o - m_new);
     l_run = l_run * wa + l_o * wb;
 #pragma unroll
     for (int e = 0; e < EPL; ++e) {
@@ -172,7 +192,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
     float L = 0.0f, acc = 0.0f;
 #pragma unroll
     for (int w = 0; w < NW; ++w) {
-      const float wgt = exp2f(sm[w] - M);
+      const float wgt = __builtin_amdgcn_exp2f(sm[w] - M);
       L += sl[w] * wgt;
       acc += so[w][threadIdx.x] * wgt;
     }

@@ -78,13 +78,17 @@ struct Workspace {
   // shared
   int32_t *status, *n_exited, *done, *scratch_exit_layer, *scratch_L;
   float* q;           // [B][d]
+  float2* rope;       // [B][head_dim/2] (cos, sin) of this iteration's rotary angles
   float4* partials;   // bf16: [Mpad][vocab/32]; fp32: [B]
   // bf16 path
   float* hT;          // [d][Mpad]
-  bf16_t* xT;         // [Mpad][d]
+  bf16_t* xH;         // [Mpad][d] exit-head operand, directly followed by
+  bf16_t* xT;         // [Mpad][d] layer operand (the pair is written by one launch after a layer with a head)
   bf16_t* aoT;        // [Mpad][d]
   bf16_t* actT;       // [Mpad][f]
   float* rowsq;       // [2n + 2][Mpad]: sum of squares of the residual rows after the embedding / each update
+  int32_t* tile_cnt;  // [(d/32) * Mpad/32] arrival counters of the accumulate epilogue (directly behind rowsq)
+  size_t zero_count;  // floats from rowsq on that must be zero when an iteration starts
   bf16_t* fill_x;     // [n][Mpad][d]
   // fp32 path
   float *h, *x, *ao, *act, *logits;
@@ -103,13 +107,17 @@ Workspace carve(const ee_model_desc& D, int B, void* base) {
   w.scratch_exit_layer = c.take<int32_t>(Bp);
   w.scratch_L = c.take<int32_t>(1);
   w.q = c.take<float>(Bp * d);
+  w.rope = c.take<float2>((size_t)Bp * (D.head_dim / 2));
   if (D.dtype == EE_BF16) {
     w.partials = c.take<float4>((size_t)Mpad * (V / 32));
     w.hT = c.take<float>(d * Mpad);
-    w.xT = c.take<bf16_t>(d * Mpad);
+    w.xH = c.take<bf16_t>(2 * d * Mpad);
+    w.xT = w.xH ? w.xH + d * Mpad : nullptr;
     w.aoT = c.take<bf16_t>(d * Mpad);
     w.actT = c.take<bf16_t>(f * Mpad);
-    w.rowsq = c.take<float>((2 * n + 2) * Mpad);
+    w.zero_count = (2 * n + 2) * Mpad + (d / 32) * (Mpad / 32);
+    w.rowsq = c.take<float>(w.zero_count);
+    w.tile_cnt = reinterpret_cast<int32_t*>(w.rowsq ? w.rowsq + (2 * n + 2) * Mpad : nullptr);
     w.fill_x = c.take<bf16_t>(n * Mpad * d);
   } else {
     w.partials = c.take<float4>(Bp);
@@ -186,9 +194,11 @@ int check_workspace(const ee_model_desc& D, int B, void* ws, size_t ws_bytes) {
 
 bool has_head(const ee_model_desc& D, int i) { return i < D.n_layers && i % D.exit_every == 0; }
 
+// Workgroups along the contraction for the accumulate epilogue: enough to cover the chip twice, no more (each
+// extra slice costs one more round of float atomics per output and shortens every wavefront's stream).
 int acc_ksplit(int n_tiles, int K) {
   const int k_steps = K / 16;
-  int s = 1024 / n_tiles;
+  int s = (512 + n_tiles - 1) / n_tiles;
   if (s > k_steps / 64) s = k_steps / 64;
   return s < 1 ? 1 : s;
 }
@@ -198,10 +208,11 @@ size_t pool_layer_elems(const ee_model_desc& D, const ee_kv_cache& C) {
 }
 size_t elem_bytes(const ee_model_desc& D) { return D.dtype == EE_BF16 ? 2 : 4; }
 
-QkvEpi make_qkv_epi(const ee_model_desc& D, const ee_kv_cache& C, const ee_batch& Bt, int layer, float* q,
-                    const float* rowsq) {
+QkvEpi make_qkv_epi(const ee_model_desc& D, const ee_kv_cache& C, const ee_batch& Bt, const Workspace& w, int layer,
+                    float* q) {
   QkvEpi e{};
   e.q = q;
+  e.rope = w.rope;
   const size_t lb = pool_layer_elems(D, C) * elem_bytes(D) * (size_t)(layer - 1);
   e.k_pool = reinterpret_cast<char*>(C.k_pool) + lb;
   e.v_pool = reinterpret_cast<char*>(C.v_pool) + lb;
@@ -215,20 +226,21 @@ QkvEpi make_qkv_epi(const ee_model_desc& D, const ee_kv_cache& C, const ee_batch
   e.head_dim = D.head_dim;
   e.d_model = D.d_model;
   e.rope_theta = D.rope_theta;
-  e.rowsq = rowsq;
+  e.rowsq = nullptr;
   e.eps = D.rms_eps;
   return e;
 }
 
 // --- exit head: statistics of (scale * logits) for every row of the hidden state ------------------------
+// prepped: the normalised operand is already in w.xH (written together with the next layer's operand).
 void enqueue_head_bf16(const ee_model& M, const Workspace& w, int B, int Mpad, float scale, const float* rowsq_slot,
-                       int layer, Pred pred, hipStream_t st) {
+                       int layer, bool prepped, Pred pred, hipStream_t st) {
   const ee_model_desc& D = M.desc;
-  {
+  if (!prepped) {
     ProfScope ps(EE_K_NORM, layer, st);
-    launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(M.g_final), w.xT, rowsq_slot, D.rms_eps, Mpad, D.d_model, pred, st);
+    launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(M.g_final), w.xH, rowsq_slot, D.rms_eps, Mpad, D.d_model, pred, st);
   }
-  GemmShape g{M.w_lm, w.xT, D.d_model, B, 0, D.vocab / 32, 16, 1};
+  GemmShape g{M.w_lm, w.xH, D.d_model, B, 0, D.vocab / 32, 16, 1};
   LmEpi e{w.partials, nullptr, D.vocab / 32, D.vocab, scale, nullptr, D.rms_eps, D.d_model};
   ProfScope ps(EE_K_HEAD, layer, st);
   launch_gemm_lm_bf16(g, e, pred, st);
@@ -245,6 +257,7 @@ void enqueue_head_f32(const ee_model& M, const Workspace& w, const float* h, int
 }
 
 // --- KV filling for layers above fill_from ----------------------------------------------------------------
+// rowsq_slot: zeroed scratch that receives the row sums of squares of the hidden state being projected.
 void enqueue_fill_bf16(const ee_model& M, const ee_kv_cache& C, const ee_batch& Bt, const Workspace& w, int Mpad,
                        const int32_t* fill_from, int stride, float* rowsq_slot, Pred pred, hipStream_t st) {
   const ee_model_desc& D = M.desc;
@@ -259,7 +272,7 @@ void enqueue_fill_bf16(const ee_model& M, const ee_kv_cache& C, const ee_batch& 
   launch_prep_x_layers(w.hT, gt, D.n_layers, w.fill_x, rowsq_slot, D.rms_eps, fill_from, stride, Bt.batch, Mpad, D.d_model,
                        pred, st);
   GemmShape g{nullptr, nullptr, D.d_model, Bt.batch, D.d_model / 32, 2 * D.d_model / 32, D.head_dim / 2, 1};
-  QkvEpi e = make_qkv_epi(D, C, Bt, 1, nullptr, nullptr);
+  QkvEpi e = make_qkv_epi(D, C, Bt, w, 1, nullptr);
   e.fill_from = fill_from;
   e.fill_from_stride = stride;
   launch_gemm_kvfill_bf16(fl, D.n_layers, w.fill_x, (size_t)Mpad * D.d_model, pool_layer_elems(D, C), g, e, pred, st);
@@ -273,7 +286,7 @@ void enqueue_fill_f32(const ee_model& M, const ee_kv_cache& C, const ee_batch& B
     launch_rmsnorm_f32(h, reinterpret_cast<const float*>(L.g_attn), w.x, Bt.batch, D.d_model, D.rms_eps, pred, st);
     SimpleShape g{reinterpret_cast<const float*>(L.w_qkv), w.x, D.d_model, Bt.batch, D.d_model, 2 * D.d_model,
                   D.head_dim / 2};
-    QkvEpi e = make_qkv_epi(D, C, Bt, i, nullptr, nullptr);
+    QkvEpi e = make_qkv_epi(D, C, Bt, w, i, nullptr);
     e.fill_from = fill_from;
     e.fill_from_stride = stride;
     launch_simple_qkv(g, e, pred, st);
@@ -374,7 +387,8 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   auto rs = [&](int slot) { return w.rowsq + (size_t)slot * Mpad; };
   {
     ProfScope ps(EE_K_OTHER, 0, st);
-    launch_iter_init(s, B, n, out_conf, bf ? w.rowsq : nullptr, bf ? (size_t)(2 * n + 2) * Mpad : 0, st);
+    launch_iter_init(s, B, n, out_conf, bf ? w.rowsq : nullptr, bf ? w.zero_count : 0, st);
+    launch_rope_table(batch->context_lens, w.rope, B, D.head_dim, D.rope_theta, st);
     if (bf) {
       launch_embed_bf16(reinterpret_cast<const bf16_t*>(model->embed), batch->tokens, w.hT, B, Mpad, d, st);
       launch_rowsq(w.hT, rs(0), Mpad, d, always, st);
@@ -389,15 +403,16 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     const size_t pool_off = pool_layer_elems(D, *cache) * elem_bytes(D) * (size_t)(i - 1);
     AttnArgs at{w.q, reinterpret_cast<char*>(cache->k_pool) + pool_off, reinterpret_cast<char*>(cache->v_pool) + pool_off,
                 batch->context_lens, batch->block_tables, batch->max_blocks, B, D.n_heads, D.head_dim, nullptr, 0};
+    const bool head_here = use_exit_heads && has_head(D, i);
     if (bf) {
-      {
+      if (i == 1) {
         ProfScope ps(EE_K_NORM, i, st);
-        launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_attn), w.xT, rs(2 * i - 2), D.rms_eps, Mpad, d, run_layers, st);
+        launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_attn), w.xT, rs(0), D.rms_eps, Mpad, d, run_layers, st);
       }
       {
         ProfScope ps(EE_K_QKV, i, st);
         GemmShape gq{L.w_qkv, w.xT, d, B, 0, 3 * d / 32, D.head_dim / 2, 1};
-        launch_gemm_qkv_bf16(gq, make_qkv_epi(D, *cache, *batch, i, w.q, nullptr), run_layers, st);
+        launch_gemm_qkv_bf16(gq, make_qkv_epi(D, *cache, *batch, w, i, w.q), run_layers, st);
       }
       {
         ProfScope ps(EE_K_ATTN, i, st);
@@ -406,13 +421,12 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
         if ((rc = launch_attention(at, D.dtype, run_layers, st))) return rc;
       }
       {
-        ProfScope ps(EE_K_OPROJ, i, st);
+        ProfScope ps(EE_K_OPROJ, i, st);   // also leaves the row sums of squares the FFN norm needs
         GemmShape go{L.w_o, w.aoT, d, B, 0, d / 32, 16, acc_ksplit(d / 32, d)};
-        launch_gemm_acc_bf16(go, AccEpi{w.hT, Mpad, d}, run_layers, st);
+        launch_gemm_acc_bf16(go, AccEpi{w.hT, Mpad, d, rs(2 * i - 1), w.tile_cnt}, run_layers, st);
       }
       {
         ProfScope ps(EE_K_NORM, i, st);
-        launch_rowsq(w.hT, rs(2 * i - 1), Mpad, d, run_layers, st);
         launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_ffn), w.xT, rs(2 * i - 1), D.rms_eps, Mpad, d, run_layers, st);
       }
       {
@@ -421,20 +435,25 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
         launch_gemm_gateup_bf16(gg, GateUpEpi{w.actT, f, nullptr, D.rms_eps, d}, run_layers, st);
       }
       {
-        ProfScope ps(EE_K_DOWN, i, st);
+        ProfScope ps(EE_K_DOWN, i, st);    // row sums for the exit head and for the next layer's attention norm
         GemmShape gd{L.w_down, w.actT, f, B, 0, d / 32, 16, acc_ksplit(d / 32, f)};
-        launch_gemm_acc_bf16(gd, AccEpi{w.hT, Mpad, d}, run_layers, st);
+        launch_gemm_acc_bf16(gd, AccEpi{w.hT, Mpad, d, rs(2 * i), w.tile_cnt}, run_layers, st);
       }
-      {
+      if (i < n) {   // operand of the next layer's attention (and of this layer's exit head, in the same launch)
         ProfScope ps(EE_K_NORM, i, st);
-        launch_rowsq(w.hT, rs(2 * i), Mpad, d, run_layers, st);
+        const bf16_t* g_next = reinterpret_cast<const bf16_t*>(model->layers[i].g_attn);
+        if (head_here)
+          launch_prep_x_pair(w.hT, reinterpret_cast<const bf16_t*>(model->g_final), g_next, w.xH, rs(2 * i), D.rms_eps, Mpad, d,
+                             run_layers, st);
+        else
+          launch_prep_x(w.hT, g_next, w.xT, rs(2 * i), D.rms_eps, Mpad, d, run_layers, st);
       }
     } else {
       {
         ProfScope ps(EE_K_QKV, i, st);
         launch_rmsnorm_f32(w.h, reinterpret_cast<const float*>(L.g_attn), w.x, B, d, D.rms_eps, run_layers, st);
         SimpleShape gq{reinterpret_cast<const float*>(L.w_qkv), w.x, d, B, 0, 3 * d, D.head_dim / 2};
-        launch_simple_qkv(gq, make_qkv_epi(D, *cache, *batch, i, w.q, nullptr), run_layers, st);
+        launch_simple_qkv(gq, make_qkv_epi(D, *cache, *batch, w, i, w.q), run_layers, st);
       }
       {
         ProfScope ps(EE_K_ATTN, i, st);
@@ -445,7 +464,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       {
         ProfScope ps(EE_K_OPROJ, i, st);
         SimpleShape go{reinterpret_cast<const float*>(L.w_o), w.ao, d, B, 0, d, 1};
-        launch_simple_acc(go, AccEpi{w.h, 0, d}, run_layers, st);
+        launch_simple_acc(go, AccEpi{w.h, 0, d, nullptr, nullptr}, run_layers, st);
       }
       {
         ProfScope ps(EE_K_GATEUP, i, st);
@@ -456,13 +475,13 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       {
         ProfScope ps(EE_K_DOWN, i, st);
         SimpleShape gd{reinterpret_cast<const float*>(L.w_down), w.act, f, B, 0, d, 1};
-        launch_simple_acc(gd, AccEpi{w.h, 0, d}, run_layers, st);
+        launch_simple_acc(gd, AccEpi{w.h, 0, d, nullptr, nullptr}, run_layers, st);
       }
     }
-    if (use_exit_heads && has_head(D, i)) {
+    if (head_here) {
       const float scale = D.logit_scale * (float)i;
       if (bf)
-        enqueue_head_bf16(*model, w, B, Mpad, scale, rs(2 * i), i, run_layers, st);
+        enqueue_head_bf16(*model, w, B, Mpad, scale, rs(2 * i), i, true, run_layers, st);
       else
         enqueue_head_f32(*model, w, w.h, B, scale, i, run_layers, st);
       CombineArgs ca{w.partials, bf ? D.vocab / 32 : 1, B, i, scale, thresholds[i - 1], D.conf_mode, forced_exit_layer, s,
@@ -484,7 +503,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   // hidden state already is the token; the LM head is only streamed again when the loop ran to the last layer.
   {
     if (bf)
-      enqueue_head_bf16(*model, w, B, Mpad, 0.0f, rs(2 * n), n, run_layers, st);
+      enqueue_head_bf16(*model, w, B, Mpad, 0.0f, rs(2 * n), n, false, run_layers, st);
     else
       enqueue_head_f32(*model, w, w.h, B, 0.0f, n, run_layers, st);
     CombineArgs ca{w.partials, bf ? D.vocab / 32 : 1, B, 0, 0.0f, 0.0f, 0, nullptr, s, out_tokens, nullptr};
@@ -525,7 +544,7 @@ int ee_exit_check(const ee_model* model, int32_t layer, const float* hidden, int
                      w.rowsq, (size_t)Mpad, st);
     launch_hidden_to_ht(hidden, w.hT, batch, Mpad, D.d_model, st);
     launch_rowsq(w.hT, w.rowsq, Mpad, D.d_model, always, st);
-    enqueue_head_bf16(*model, w, batch, Mpad, scale, w.rowsq, layer, always, st);
+    enqueue_head_bf16(*model, w, batch, Mpad, scale, w.rowsq, layer, false, always, st);
   } else {
     enqueue_head_f32(*model, w, hidden, batch, scale, layer, always, st);
   }
@@ -550,6 +569,7 @@ int ee_kv_fill(const ee_model* model, const ee_kv_cache* cache, const ee_batch* 
   const Workspace w = carve(D, B, workspace);
   const int Mpad = round_up(B, 32);
   const Pred always{nullptr, 0};
+  launch_rope_table(batch->context_lens, w.rope, B, D.head_dim, D.rope_theta, st);
   if (D.dtype == EE_BF16) {
     launch_iter_init(IterState{w.status, w.scratch_exit_layer, w.n_exited, w.done, w.scratch_L}, 0, D.n_layers, nullptr,
                      w.rowsq, (size_t)Mpad, st);

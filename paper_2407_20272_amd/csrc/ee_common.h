@@ -74,6 +74,7 @@ struct QkvEpi {                 // rotary embedding + paged cache write (+ q out
   int layer;
   int max_blocks, n_heads, head_dim, d_model;
   float rope_theta;
+  const float2* rope;           // [M][dh/2] (cos, sin) of the rotary angles at context_lens[m] (rope_theta > 0)
   const float* rowsq;           // nullptr, or [M] sum of squares of the hidden row: value *= rsqrt(rowsq/d + eps)
   float eps;
 };
@@ -81,6 +82,8 @@ struct AccEpi {                 // h += value
   float* h;
   int Mpad;                     // HT pitch (bf16 path) or 0: plain [M][n_out]
   int n_out;
+  float* rowsq;                 // bf16 path: nullptr, or [Mpad] zeroed: receives sum_k h[m][k]^2 of the finished rows
+  int32_t* tile_counters;       // bf16 path with rowsq: [n_tiles * m_tiles] zeroed arrival counters (left at zero)
 };
 struct GateUpEpi {              // act = silu(gate) * up
   void* act;                    // XT bf16 [Mpad][f] (bf16 path) or plain float [M][f]
@@ -118,6 +121,7 @@ void launch_embed_f32(const float* E, const int32_t* tokens, float* h, int B, in
 void launch_hidden_to_ht(const float* plain, float* hT, int B, int Mpad, int d, hipStream_t st);
 void launch_ht_to_hidden(const float* hT, float* plain, int B, int Mpad, int d, hipStream_t st);
 void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t st);
+void launch_rope_table(const int32_t* context_lens, float2* table, int B, int head_dim, float theta, hipStream_t st);
 // RMSNorm of the bf16 path: rowsq[m] += sum_k h^2, then x = bf16(h * rsqrt(rowsq/d + eps) * g) in XT order.
 // launch_prep_x_layers writes one slab per layer with that layer's gain (KV filling).
 struct GainTable {
@@ -126,6 +130,9 @@ struct GainTable {
 void launch_rowsq(const float* hT, float* rowsq, int Mpad, int d, Pred pred, hipStream_t st);
 void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, float eps, int Mpad, int d,
                    Pred pred, hipStream_t st);
+// Two normalisations of the same rows in one launch: slab 0 of xT_pair with gain_a, slab 1 (Mpad * d elements on) with gain_b.
+void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT_pair, const float* rowsq,
+                        float eps, int Mpad, int d, Pred pred, hipStream_t st);
 void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
                           float eps, const int32_t* fill_from, int fill_from_stride, int B, int Mpad, int d, Pred pred,
                           hipStream_t st);

@@ -14,8 +14,9 @@ __device__ inline void store_elem(float* p, float v) { *p = v; }
 __device__ inline void store_elem(bf16_t* p, float v) { *p = (bf16_t)v; }
 
 // Rotary embedding (split-half pairing: channel j with j + dh/2, angle = pos * theta^(-2j/dh)) and the write of
-// this position's K/V into the paged cache; q goes to a dense buffer.  The angle is formed in double so that long
-// contexts do not lose the fraction of the angle to float rounding of the frequency.
+// this position's K/V into the paged cache; q goes to a dense buffer.  The (cos, sin) pairs come from a table
+// that rope_table_kernel fills once per call from angles formed in double (long contexts would lose the fraction
+// of the angle to float rounding of the frequency).
 template <class T>
 __device__ inline void epi_qkv(const QkvEpi& e, int m, int f_lo, float lo, float hi) {
   if (e.fill_from && !(e.fill_from[(size_t)m * e.fill_from_stride] < e.layer)) return;
@@ -29,10 +30,8 @@ __device__ inline void epi_qkv(const QkvEpi& e, int m, int f_lo, float lo, float
   const int j = within - head * dh;  // < dh/2
   const int p = e.context_lens[m];
   if (which < 2 && e.rope_theta > 0.0f) {
-    const double ang = (double)p * exp2(-2.0 * (double)j / (double)dh * log2((double)e.rope_theta));
-    double sn, cs;
-    sincos(ang, &sn, &cs);
-    const float c = (float)cs, s = (float)sn;
+    const float2 cs = e.rope[(size_t)m * half + j];   // (cos, sin) of pos * theta^(-2j/dh), tabulated once per iteration
+    const float c = cs.x, s = cs.y;
     const float a = lo * c - hi * s;
     const float b = hi * c + lo * s;
     lo = a;

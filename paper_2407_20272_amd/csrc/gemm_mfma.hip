@@ -1,11 +1,17 @@
 // bf16 projections of the decode step on the matrix cores (v_mfma_f32_32x32x16_bf16).
 //
 // The decode step multiplies a handful of activation rows (the batch) by large weight matrices, so the
-// kernel is a weight streamer: every weight byte is fetched from HBM exactly once, straight into registers
+// kernels are weight streamers: every weight byte is fetched from HBM exactly once, straight into registers
 // (1 KiB of consecutive bytes per wavefront load thanks to the packed tile order), and the small activation
-// operand comes out of L2 in its own tile order.  A workgroup of four wavefronts owns one 32-row output tile
-// and splits the contraction four ways; the partial tiles meet in LDS and the epilogue (rotary + paged cache
-// write, residual accumulation, SwiGLU, or exit-head softmax statistics) runs on the finished sums.
+// operand comes out of L2.  A workgroup of four wavefronts owns 32-row output tiles and splits the contraction
+// four ways; the partial tiles meet in LDS and the epilogue (rotary + paged cache write, residual accumulation,
+// SwiGLU, or exit-head softmax statistics) runs on the finished sums.
+//
+// The second operand is bf16 in operand-tile order: the attention output, the SwiGLU product, or the normalised
+// hidden state written by prep_x_kernel.  (Building the normalised operand on the fly from the float residual
+// stream inside this loop was tried and measured slower: twice the L2 traffic per weight byte plus the
+// conversion arithmetic cost more than the 4.7 us normalisation launch they replaced.)
+#include <stdlib.h>
 #include <type_traits>
 
 #include "ee_common.h"
@@ -17,6 +23,140 @@ namespace {
 constexpr int NW = 4;  // wavefronts per workgroup
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+struct FillCtl {  // KV filling: one grid.z slice per layer
+  FillLayers layers;
+  const bf16_t* x_slabs;
+  size_t x_slab_elems;
+  size_t pool_layer_bytes;
+};
+
+struct Lds {
+  float red[NW][16][64];
+  float zt[32][33];
+  float part[8][32];
+  int flag;
+};
+
+// KV filling: does any sequence need layer `layer` filled?  (uniform over the workgroup)
+__device__ inline bool fill_needed(const QkvEpi& e, int M, int layer, Lds& s) {
+  if (threadIdx.x == 0) s.flag = 0;
+  __syncthreads();
+  int need = 0;
+  if (e.fill_from_stride == 0) {
+    need = e.fill_from[0] < layer;
+  } else {
+    for (int m = threadIdx.x; m < M; m += blockDim.x) need |= e.fill_from[m] < layer;
+  }
+  if (need) s.flag = 1;
+  __syncthreads();
+  const bool any = s.flag != 0;
+  __syncthreads();
+  return any;
+}
+
+// Meets the four wavefronts' partial 32x32 tiles in LDS and runs the epilogue on the finished sums.
+// Thread t owns result rows r16(a) and r16(a)+16 for a = 2*(t/64), 2*(t/64)+1 in column t%32 (+32*(t%64/32) picks
+// the upper row group): the two rows that an epilogue needs together always sit in the same thread.
+template <class Epi>
+__device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, const GemmShape& g, const Epi& e, Lds& s,
+                                   int wave, int lane) {
+  __syncthreads();
+#pragma unroll
+  for (int a = 0; a < 16; ++a) s.red[wave][a][lane] = acc[a];
+  __syncthreads();
+  const int l2 = threadIdx.x & 63, qq = threadIdx.x >> 6;
+  const int m = mt_global * 32 + (l2 & 31);
+  float vlo[2], vhi[2];
+  int r16[2];
+#pragma unroll
+  for (int ai = 0; ai < 2; ++ai) {
+    const int a = 2 * qq + ai;
+    vlo[ai] = s.red[0][a][l2] + s.red[1][a][l2] + s.red[2][a][l2] + s.red[3][a][l2];
+    vhi[ai] = s.red[0][a + 8][l2] + s.red[1][a + 8][l2] + s.red[2][a + 8][l2] + s.red[3][a + 8][l2];
+    r16[ai] = (a >> 2) * 8 + (l2 >> 5) * 4 + (a & 3);
+  }
+  if constexpr (std::is_same<Epi, LmEpi>::value) {
+    const float r = m < g.M ? row_rinv(e.rowsq, m, e.d_model, e.eps) : 0.0f;
+#pragma unroll
+    for (int ai = 0; ai < 2; ++ai) {
+      s.zt[r16[ai]][l2 & 31] = vlo[ai] * r;
+      s.zt[r16[ai] + 16][l2 & 31] = vhi[ai] * r;
+    }
+    __syncthreads();
+    if (threadIdx.x < 32) {
+      const int mm = mt_global * 32 + threadIdx.x;
+      if (mm < g.M) {
+        HeadStat st = stat_empty();
+        for (int rr = 0; rr < 32; ++rr) st = stat_push(st, s.zt[rr][threadIdx.x], nt * 32 + rr, e.scale);
+        e.partials[(size_t)mm * e.n_parts + (nt - g.tile_begin)] = stat_pack(st);
+      }
+    }
+  } else if constexpr (std::is_same<Epi, AccEpi>::value) {
+    float* p[4];
+#pragma unroll
+    for (int ai = 0; ai < 2; ++ai) {
+      const int f_lo = packed_row_lo(nt, r16[ai], g.pair_stride);
+      p[2 * ai] = e.h + ht_index(m, f_lo, e.Mpad);
+      p[2 * ai + 1] = e.h + ht_index(m, f_lo + g.pair_stride, e.Mpad);
+    }
+    if (m < g.M) {
+#pragma unroll
+      for (int ai = 0; ai < 2; ++ai) {
+        unsafeAtomicAdd(p[2 * ai], vlo[ai]);
+        unsafeAtomicAdd(p[2 * ai + 1], vhi[ai]);
+      }
+    }
+    if (e.rowsq) {
+      // The workgroup that adds the last contraction slice of this tile reads the finished residual values back
+      // and adds their squares to the row sums the next RMSNorm needs (no separate reduction kernel).
+      // Every access to these words is a device-scope atomic (adds above, loads below), so no cache maintenance
+      // is needed: each thread waits until its adds have been performed, then the arrival counter is bumped.
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      const int cidx = (nt - g.tile_begin) * ((g.M + 31) >> 5) + mt_global;
+      if (threadIdx.x == 0) s.flag = atomicAdd(e.tile_counters + cidx, 1);
+      __syncthreads();
+      const bool last = s.flag == (int)gridDim.y - 1;
+      if (last) {
+        float ss = 0.0f;
+        if (m < g.M) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const float v = __hip_atomic_load(p[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ss = fmaf(v, v, ss);
+          }
+        }
+        s.part[(l2 >> 5) * 4 + qq][l2 & 31] = ss;
+      }
+      __syncthreads();
+      if (last) {
+        if (threadIdx.x < 32) {
+          float t = 0.0f;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) t += s.part[j][threadIdx.x];
+          if (mt_global * 32 + threadIdx.x < g.M) unsafeAtomicAdd(e.rowsq + mt_global * 32 + threadIdx.x, t);
+        }
+        if (threadIdx.x == 0) e.tile_counters[cidx] = 0;   // ready for the next launch
+      }
+    }
+  } else {
+    if (m < g.M) {
+#pragma unroll
+      for (int ai = 0; ai < 2; ++ai) {
+        const int f_lo = packed_row_lo(nt, r16[ai], g.pair_stride);
+        if constexpr (std::is_same<Epi, QkvEpi>::value) {
+          epi_qkv<bf16_t>(e, m, f_lo, vlo[ai], vhi[ai]);
+        } else {
+          epi_gateup<bf16_t>(e, m, f_lo, vlo[ai], vhi[ai]);
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Main loop 1: bf16 operand tiles on both sides
+// ---------------------------------------------------------------------------------------------------------
 template <int MT, int U>
 struct Frag {
   u32x4 w[U];
@@ -61,35 +201,14 @@ __device__ inline void frag_mma(const Frag<MT, U>& f, f32x16 (&acc)[MT]) {
                                                         __builtin_bit_cast(bf16x8, f.x[mt][u]), acc[mt], 0, 0, 0);
 }
 
-struct FillCtl {  // KV filling: one grid.z slice per layer
-  int enabled;
-  FillLayers layers;
-  const bf16_t* x_slabs;
-  size_t x_slab_elems;
-  size_t pool_layer_bytes;
-};
-
 template <int MT, int U, class Epi, bool FILL>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred pred, FillCtl fc) {
   if (pred_skip(pred)) return;
-  __shared__ float red[NW][16][64];
-  __shared__ float zt[32][33];
-  __shared__ int any_row;
+  __shared__ Lds s;
 
   if constexpr (FILL) {
     const int layer = blockIdx.z + 1;
-    // rows that need this layer filled: fill_from[m] < layer
-    if (threadIdx.x == 0) any_row = 0;
-    __syncthreads();
-    int need = 0;
-    if (e.fill_from_stride == 0) {
-      need = e.fill_from[0] < layer;
-    } else {
-      for (int m = threadIdx.x; m < g.M; m += blockDim.x) need |= e.fill_from[m] < layer;
-    }
-    if (need) any_row = 1;
-    __syncthreads();
-    if (!any_row) return;
+    if (!fill_needed(e, g.M, layer, s)) return;
     g.w = fc.layers.w_qkv[layer - 1];
     g.x = fc.x_slabs + (size_t)(layer - 1) * fc.x_slab_elems;
     e.layer = layer;
@@ -139,58 +258,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
       frag_load_tail(A, wp, xp, x_tile_stride, k, ks1);
       frag_mma(A, acc);
     }
-
-    // meet the four partial tiles in LDS, one batch tile at a time
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      __syncthreads();
-#pragma unroll
-      for (int a = 0; a < 16; ++a) red[wave][a][lane] = acc[mt][a];
-      __syncthreads();
-      const int l2 = threadIdx.x & 63, qq = threadIdx.x >> 6;
-      const int m = (mt0 + mt) * 32 + (l2 & 31);
-      float vlo[2], vhi[2];
-      int r16[2];
-#pragma unroll
-      for (int ai = 0; ai < 2; ++ai) {
-        const int a = 2 * qq + ai;
-        vlo[ai] = red[0][a][l2] + red[1][a][l2] + red[2][a][l2] + red[3][a][l2];
-        vhi[ai] = red[0][a + 8][l2] + red[1][a + 8][l2] + red[2][a + 8][l2] + red[3][a + 8][l2];
-        r16[ai] = (a >> 2) * 8 + (l2 >> 5) * 4 + (a & 3);
-      }
-      if constexpr (std::is_same<Epi, LmEpi>::value) {
-        const float r = m < g.M ? row_rinv(e.rowsq, m, e.d_model, e.eps) : 0.0f;
-#pragma unroll
-        for (int ai = 0; ai < 2; ++ai) {
-          zt[r16[ai]][l2 & 31] = vlo[ai] * r;
-          zt[r16[ai] + 16][l2 & 31] = vhi[ai] * r;
-        }
-        __syncthreads();
-        if (threadIdx.x < 32) {
-          const int mm = (mt0 + mt) * 32 + threadIdx.x;
-          if (mm < g.M) {
-            HeadStat s = stat_empty();
-            for (int rr = 0; rr < 32; ++rr) s = stat_push(s, zt[rr][threadIdx.x], nt * 32 + rr, e.scale);
-            e.partials[(size_t)mm * e.n_parts + (nt - g.tile_begin)] = stat_pack(s);
-          }
-        }
-      } else {
-        if (m < g.M) {
-#pragma unroll
-          for (int ai = 0; ai < 2; ++ai) {
-            const int f_lo = packed_row_lo(nt, r16[ai], g.pair_stride);
-            if constexpr (std::is_same<Epi, QkvEpi>::value) {
-              epi_qkv<bf16_t>(e, m, f_lo, vlo[ai], vhi[ai]);
-            } else if constexpr (std::is_same<Epi, AccEpi>::value) {
-              epi_acc(e, m, f_lo, vlo[ai]);
-              epi_acc(e, m, f_lo + g.pair_stride, vhi[ai]);
-            } else {
-              epi_gateup<bf16_t>(e, m, f_lo, vlo[ai], vhi[ai]);
-            }
-          }
-        }
-      }
-    }
+    for (int mt = 0; mt < MT; ++mt) tile_finish(acc[mt], nt, mt0 + mt, g, e, s, wave, lane);
   }
 }
 
@@ -237,7 +306,6 @@ void launch_gemm_lm_bf16(const GemmShape& g, const LmEpi& e, Pred pred, hipStrea
 void launch_gemm_kvfill_bf16(const FillLayers& fl, int n_layers, const bf16_t* x_slabs, size_t x_slab_elems,
                              size_t pool_layer_elems, const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st) {
   FillCtl fc{};
-  fc.enabled = 1;
   fc.layers = fl;
   fc.x_slabs = x_slabs;
   fc.x_slab_elems = x_slab_elems;

