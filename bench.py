@@ -39,6 +39,22 @@ def algorithmic_bytes(cfg, cls, mean_ctx_plus1):
     }.get(cls)
 
 
+def traffic_ratios():
+    """Measured HBM bytes per algorithmic byte of each kernel class, from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, calibrated against a plain copy of known size)."""
+    out = {}
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_llama7b_b32_pmc.md")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 3 and parts[0] == "traffic_ratio":
+                    out[parts[1]] = float(parts[2])
+    except OSError:
+        pass
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -49,6 +65,8 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--modes", default="ee,full,never")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run three plain 256 MiB device copies (copy_f32_kernel) so that byte counters can be calibrated")
     ap.add_argument("--no-graph", action="store_true", help="enqueue every iteration eagerly instead of replaying a HIP graph")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -102,6 +120,13 @@ def main():
     # Per-iteration bookkeeping stays on the device so that one iteration (decode step + token feedback + position
     # advance + histograms) is a fixed sequence of kernels: it is captured once per mode into a HIP graph and
     # replayed, which removes the per-launch host cost of the ~300-400 kernels of an iteration.
+    if args.calibrate_copy:
+        ca = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        cb = torch.empty_like(ca)
+        for _ in range(3):
+            B.ee_calibration_copy(ca, cb)
+        torch.cuda.synchronize()
+        del ca, cb
     L_hist = torch.zeros(n + 1, dtype=torch.int32, device="cuda")
     E_hist = torch.zeros(n + 1, dtype=torch.int32, device="cuda")
     one1 = torch.ones(1, dtype=torch.int32, device="cuda")
@@ -218,8 +243,13 @@ def main():
         if cands:
             _, dom = max(cands)
             e = prof[head_mode][dom]
+            ratio = traffic_ratios().get(dom) if args.config == 1 and not args.layers else None
             roof = {"bound": "hbm", "kernel": dom, "achieved": e["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": e["frac_hbm_peak"], "traffic": None, "avg_us": e["avg_us"],
+                    "frac": e["frac_hbm_peak"],
+                    "traffic": (ratio * e["algorithmic_MB"] * 1e6) if ratio else None,
+                    "traffic_source": "profiles/hbm_traffic_llama7b_b32_pmc.md (measured bytes per algorithmic byte x "
+                                      "this launch's algorithmic bytes)" if ratio else None,
+                    "avg_us": e["avg_us"], "raw_event_us": e["raw_event_us"],
                     "algorithmic_bytes_per_launch": e["algorithmic_MB"] * 1e6}
 
     # ---- CPU oracle on a bounded sample: ONE decode iteration of the same workload (all sequences) ----------

@@ -186,6 +186,9 @@ int ee_paged_attention_decode(const ee_model_desc* desc, const ee_kv_cache* cach
 #define EE_K_KVFILL 8   /* KV filling projection                                                */
 #define EE_K_OTHER 9    /* state reset, embedding, copies                                       */
 #define EE_K_CLASSES 10
+/* Plain device copy of n_floats floats (dev to dev) with the library's own copy kernel: a kernel of known traffic
+ * (4 * n_floats bytes read, as many written) against which hardware byte counters are calibrated. */
+int ee_calibration_copy(const float* src, float* dst, size_t n_floats, void* stream);
 int ee_profile_enable(int32_t on);
 int ee_profile_read(int32_t* kernel_class /*host*/, int32_t* layer /*host*/, float* ms /*host*/, int32_t max_records);
 

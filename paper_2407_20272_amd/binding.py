@@ -19,7 +19,7 @@ EE_ERR_INVALID_ARG, EE_ERR_SHAPE, EE_ERR_UNSUPPORTED, EE_ERR_WORKSPACE, EE_ERR_H
 EE_FP32, EE_BF16 = 0, 1
 EE_PACK_PLAIN, EE_PACK_QKV, EE_PACK_GATE_UP = 0, 1, 2
 EXPORTS = ["ee_last_error", "ee_packed_weight_bytes", "ee_pack_weight", "ee_workspace_bytes", "ee_decode_iteration",
-           "ee_exit_check", "ee_kv_fill", "ee_paged_attention_decode", "ee_profile_enable", "ee_profile_read"]
+           "ee_exit_check", "ee_kv_fill", "ee_paged_attention_decode", "ee_profile_enable", "ee_profile_read", "ee_calibration_copy"]
 KERNEL_CLASSES = ["norm", "qkv", "attention", "o_proj", "gate_up", "down", "head", "combine", "kv_fill", "other"]
 
 
@@ -80,6 +80,8 @@ def lib() -> C.CDLL:
                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.ee_paged_attention_decode.argtypes = [C.POINTER(ee_model_desc), C.POINTER(ee_kv_cache), C.c_int32, C.c_void_p,
                                                 C.POINTER(ee_batch), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.ee_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        L.ee_calibration_copy.restype = C.c_int
         L.ee_profile_enable.argtypes = [C.c_int32]
         L.ee_profile_read.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int32]
         L.ee_profile_enable.restype = C.c_int
@@ -252,3 +254,8 @@ def ee_profile_read(max_records: int = 1 << 20):
     if n < 0:
         raise EEError(n, ee_last_error())
     return [(KERNEL_CLASSES[cls[i]], lay[i], ms[i]) for i in range(n)]
+
+
+def ee_calibration_copy(src: torch.Tensor, dst: torch.Tensor):
+    assert src.dtype == torch.float32 and dst.dtype == torch.float32 and src.numel() == dst.numel()
+    _check(lib().ee_calibration_copy(_ptr(src), _ptr(dst), src.numel(), _stream()))

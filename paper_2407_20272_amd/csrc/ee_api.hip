@@ -302,6 +302,13 @@ extern "C" {
 
 const char* ee_last_error(void) { return g_error; }
 
+int ee_calibration_copy(const float* src, float* dst, size_t n_floats, void* stream) {
+  if (!src || !dst) EE_FAIL(EE_ERR_INVALID_ARG, "ee_calibration_copy: NULL pointer");
+  launch_copy_f32(src, dst, n_floats, reinterpret_cast<hipStream_t>(stream));
+  EE_HIP(hipGetLastError());
+  return EE_OK;
+}
+
 int ee_profile_enable(int32_t on) {
   std::lock_guard<std::mutex> lk(g_prof_mutex);
   g_prof.on = on != 0;
