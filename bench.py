@@ -65,6 +65,14 @@ def main():
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--modes", default="ee,full,never")
+    ap.add_argument("--synthetic-kv", action="store_true",
+                    help="fill the cache with seeded random K/V instead of prefilling through the decode step "
+                         "(always used when prompt lengths are ragged)")
+    ap.add_argument("--batch", type=int, default=0, help="override the batch size (exit-rate sweep members)")
+    ap.add_argument("--context", type=int, default=0, help="override the context length (exit-rate sweep members)")
+    ap.add_argument("--forced-mean", type=float, default=0.0,
+                    help="exit-rate sweep: force per-sequence exit layers from the truncated geometric distribution on "
+                         "[8, n] with this mean instead of using the confidence")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three plain 256 MiB device copies (copy_f32_kernel) so that byte counters can be calibrated")
     ap.add_argument("--no-graph", action="store_true", help="enqueue every iteration eagerly instead of replaying a HIP graph")
@@ -82,6 +90,10 @@ def main():
     cfg = W.CONFIGS[args.config]
     if args.layers:
         cfg = cfg.with_(n_layers=args.layers, name=cfg.name + f"_{args.layers}layers_DEBUG")
+    if args.batch:
+        cfg = cfg.with_(batch=args.batch, name=cfg.name + f"_b{args.batch}")
+    if args.context:
+        cfg = cfg.with_(prompt_len=args.context, min_prompt_len=args.context, name=cfg.name + f"_ctx{args.context}")
     K, Wm, P = args.steps, args.warmup, args.profile_steps
     Bsz, n = cfg.batch, cfg.n_layers
     t0 = time.time()
@@ -91,7 +103,8 @@ def main():
     del w
     torch.cuda.empty_cache()
     lens = W.make_context_lens(cfg, seed=0)
-    prompts = W.make_prompts(cfg, seed=0, device="cuda")
+    prompts = W.make_prompts(cfg.with_(prompt_len=min(cfg.prompt_len, 8)) if (args.synthetic_kv or cfg.min_prompt_len != cfg.prompt_len)
+                             else cfg, seed=0, device="cuda")
     extra = Wm + K + P + 1
     bt, nb = W.make_block_tables(lens, extra, cfg.block_size, cfg.shuffled_blocks, 0)
     cache = B.PagedKV(cfg, nb)
@@ -108,13 +121,25 @@ def main():
     # ---- prefill: teacher-forced through the decode step, no exit heads (positions 0 .. len-1) ----------
     lens_dev = lens.cuda()
     first = torch.zeros(Bsz, dtype=torch.int32, device="cuda")
-    assert int(lens.min()) == int(lens.max()), "bench prefill assumes equal prompt lengths"
-    for t in range(int(lens.max())):
-        tokens.copy_(prompts[:, t])
-        ctx.fill_(t)
-        B.ee_decode_iteration(model, cache, batch, 2.0, None, False, out_tok, out_exit, out_L, None, None, ws)
-    first.copy_(out_tok)
+    synthetic_kv = args.synthetic_kv or int(lens.min()) != int(lens.max())
+    if synthetic_kv:
+        g = torch.Generator(device="cuda").manual_seed(1234)
+        for i in range(n):
+            cache.k[i].normal_(0.0, 0.5, generator=g)
+            cache.v[i].normal_(0.0, 0.5, generator=g)
+        first.copy_(prompts[:, 0])
+    else:
+        for t in range(int(lens.max())):
+            tokens.copy_(prompts[:, t])
+            ctx.fill_(t)
+            B.ee_decode_iteration(model, cache, batch, 2.0, None, False, out_tok, out_exit, out_L, None, None, ws)
+        first.copy_(out_tok)
     torch.cuda.synchronize()
+    forced_all = None
+    if args.forced_mean > 0:
+        forced_all = W.make_forced_exit_layers(Bsz, Wm + K + P + 4, args.forced_mean, 8, n, seed=0).cuda()
+        forced_cur = torch.zeros(Bsz, dtype=torch.int32, device="cuda")
+        step_no = torch.zeros(1, dtype=torch.int64, device="cuda")
     setup_s = time.time() - t0
 
     # Per-iteration bookkeeping stays on the device so that one iteration (decode step + token feedback + position
@@ -135,7 +160,12 @@ def main():
 
     def iteration(mode):
         thr = {"ee": cfg.threshold, "full": 2.0, "never": 2.0}[mode]
-        B.ee_decode_iteration(model, cache, batch, thr, None, mode != "full", out_tok, out_exit, out_L, None, None, ws)
+        f = None
+        if forced_all is not None and mode == "ee":
+            torch.index_select(forced_all, 0, step_no % forced_all.shape[0], out=forced_cur.view(1, -1))
+            step_no.add_(1)
+            f = forced_cur
+        B.ee_decode_iteration(model, cache, batch, thr, f, mode != "full", out_tok, out_exit, out_L, None, None, ws)
         L_hist.scatter_add_(0, out_L.long(), one1)
         E_hist.scatter_add_(0, out_exit.long(), oneB)
         torch.add(out_tok, 0, out=tokens)          # next iteration consumes the tokens just produced
@@ -277,6 +307,8 @@ def main():
         "config": {"workload": cfg.name, "batch": Bsz, "prompt_len": int(lens.max()), "layers": n, "d_model": cfg.d_model,
                    "vocab": cfg.vocab, "threshold": cfg.threshold, "logit_scale": cfg.logit_scale,
                    "exit_every": cfg.exit_every, "kv_block": cfg.block_size, "mode": head_mode,
+                   "context_lens": [int(lens.min()), int(lens.max())], "kv": "synthetic" if synthetic_kv else "prefilled",
+                   "forced_exit_mean": args.forced_mean or None,
                    "launch": "eager" if args.no_graph else "hip_graph"},
         "modes": results,
         "speedup_ee_vs_full": (results["ee"]["tokens_per_s"] / results["full"]["tokens_per_s"])
