@@ -11,7 +11,6 @@
 // hidden state written by prep_x_kernel.  (Building the normalised operand on the fly from the float residual
 // stream inside this loop was tried and measured slower: twice the L2 traffic per weight byte plus the
 // conversion arithmetic cost more than the 4.7 us normalisation launch they replaced.)
-#include <stdlib.h>
 #include <type_traits>
 
 #include "ee_common.h"
@@ -263,17 +262,255 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
   }
 }
 
-int pick_mt(int M) {
+// ---------------------------------------------------------------------------------------------------------
+// Main loop 2 (batches of 128 rows and more): the four wavefronts of a workgroup own four different 32-row
+// output tiles over the SAME contraction range, so the activation operand is fetched from L2 once per
+// workgroup, staged in LDS and read by all four; weights still go straight from HBM to registers, each byte
+// once per batch chunk of MT*32 rows.  Groups of UT contraction steps: while group g is multiplied, the loads
+// of groups g+1 and g+2 are in flight (three rotating weight register sets, two activation register sets that
+// drain into two LDS stages).  Every wavefront finishes its own tiles, so the epilogue runs from registers.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int UT = 4;
+
+template <int MT>
+struct TiledLds {
+  u32x4 b[2][UT][MT][64];
+  float part[NW][2][MT][32];
+  int flag;
+};
+
+template <int MT, class Epi, bool FILL>
+__global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pred pred, FillCtl fc) {
+  if (pred_skip(pred)) return;
+  __shared__ TiledLds<MT> s;
+  constexpr int XR = UT * MT / NW;   // activation tiles each wavefront stages per group
+  static_assert(UT * MT % NW == 0, "stage must split evenly over the wavefronts");
+
+  if constexpr (FILL) {
+    const int layer = blockIdx.z + 1;
+    if (threadIdx.x == 0) s.flag = 0;
+    __syncthreads();
+    int need = 0;
+    if (e.fill_from_stride == 0) {
+      need = e.fill_from[0] < layer;
+    } else {
+      for (int m = threadIdx.x; m < g.M; m += blockDim.x) need |= e.fill_from[m] < layer;
+    }
+    if (need) s.flag = 1;
+    __syncthreads();
+    if (!s.flag) return;
+    g.w = fc.layers.w_qkv[layer - 1];
+    g.x = fc.x_slabs + (size_t)(layer - 1) * fc.x_slab_elems;
+    e.layer = layer;
+    e.k_pool = reinterpret_cast<char*>(e.k_pool) + (size_t)(layer - 1) * fc.pool_layer_bytes;
+    e.v_pool = reinterpret_cast<char*>(e.v_pool) + (size_t)(layer - 1) * fc.pool_layer_bytes;
+  }
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m_tiles = (g.M + 31) >> 5;
+  const int chunks = m_tiles / MT;
+  const int ksplit = gridDim.y / chunks;
+  const int chunk = blockIdx.y / ksplit, ksl = blockIdx.y % ksplit;
+  const int nt = g.tile_begin + blockIdx.x * NW + wave;
+  const int k_steps = g.K >> 4;
+  const int ks0 = (int)((long)k_steps * ksl / ksplit);
+  const int ks1 = (int)((long)k_steps * (ksl + 1) / ksplit);
+  const size_t x_tile_stride = (size_t)k_steps * 64;
+  const u32x4* wp = reinterpret_cast<const u32x4*>(g.w) + (size_t)nt * k_steps * 64 + lane;
+  const u32x4* xp = reinterpret_cast<const u32x4*>(g.x) + (size_t)(chunk * MT) * x_tile_stride + lane;
+
+  f32x16 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[mt][i] = 0.0f;
+
+  // Everything in the loop is unconditional (a conditional load would force the compiler to wait for every
+  // outstanding load where the branches meet): the group count is rounded up to the rotation period and
+  // groups past the end load a clamped weight tile against zero activations.
+  u32x4 W[4][UT], X[2][XR];
+  const int n = (ks1 - ks0 + UT - 1) / UT;
+  auto gload = [&](int grp, u32x4 (&wr)[UT], u32x4 (&xr)[XR]) {
+    const int kbase = ks0 + grp * UT;
+#pragma unroll
+    for (int u = 0; u < UT; ++u) {
+      const int kk = kbase + u < ks1 ? kbase + u : ks1 - 1;
+      wr[u] = __builtin_nontemporal_load(wp + (size_t)kk * 64);
+    }
+#pragma unroll
+    for (int j = 0; j < XR; ++j) {
+      const int t = wave + NW * j, u = t / MT, mt = t % MT;
+      const bool ok = kbase + u < ks1;
+      const int kk = ok ? kbase + u : ks1 - 1;
+      const u32x4 v = xp[mt * x_tile_stride + (size_t)kk * 64];
+      xr[j] = ok ? v : u32x4{0, 0, 0, 0};
+    }
+  };
+  // One group: drain its activation registers into LDS stage XS, start the loads of group grp+2 into the
+  // registers just freed and an idle weight set, multiply group grp.
+  auto step = [&](int grp, const u32x4 (&wcur)[UT], u32x4 (&wnext2)[UT], u32x4 (&xs)[XR], int XS) {
+#pragma unroll
+    for (int j = 0; j < XR; ++j) {
+      const int t = wave + NW * j;
+      s.b[XS][t / MT][t % MT][lane] = xs[j];
+    }
+    __syncthreads();
+    gload(grp + 2, wnext2, xs);
+    // the LDS reads of contraction step u+1 are issued before the multiplies of step u
+    u32x4 bf[2][MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) bf[0][mt] = s.b[XS][0][mt][lane];
+#pragma unroll
+    for (int u = 0; u < UT; ++u) {
+      if (u + 1 < UT) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) bf[(u + 1) & 1][mt] = s.b[XS][u + 1][mt][lane];
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wcur[u]),
+                                                          __builtin_bit_cast(bf16x8, bf[u & 1][mt]), acc[mt], 0, 0, 0);
+    }
+  };
+
+  gload(0, W[0], X[0]);
+  gload(1, W[1], X[1]);
+  for (int gi = 0; gi < n; gi += 4) {
+    step(gi, W[0], W[2], X[0], 0);
+    step(gi + 1, W[1], W[3], X[1], 1);
+    step(gi + 2, W[2], W[0], X[0], 0);
+    step(gi + 3, W[3], W[1], X[1], 1);
+  }
+  __syncthreads();
+
+  // epilogue from registers: accumulator a (< 8) of a lane is result row r16 = (a/4)*8 + (lane/32)*4 + a%4 of
+  // column lane%32, accumulator a+8 is row r16+16 (its partner row in the packed order)
+  const int half = lane >> 5, ml = lane & 31;
+  if constexpr (std::is_same<Epi, LmEpi>::value) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      HeadStat st = stat_empty();
+#pragma unroll
+      for (int a = 0; a < 8; ++a) {
+        const int r16 = (a >> 2) * 8 + half * 4 + (a & 3);
+        st = stat_push(st, acc[mt][a], nt * 32 + r16, e.scale);
+        st = stat_push(st, acc[mt][a + 8], nt * 32 + r16 + 16, e.scale);
+      }
+      HeadStat o;
+      o.zmax = __shfl_xor(st.zmax, 32);
+      o.sum = __shfl_xor(st.sum, 32);
+      o.z2 = __shfl_xor(st.z2, 32);
+      o.idx = __shfl_xor(st.idx, 32);
+      st = stat_merge(st, o, e.scale);
+      const int m = (chunk * MT + mt) * 32 + ml;
+      if (half == 0 && m < g.M) e.partials[(size_t)m * e.n_parts + (nt - g.tile_begin)] = stat_pack(st);
+    }
+  } else if constexpr (std::is_same<Epi, AccEpi>::value) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = (chunk * MT + mt) * 32 + ml;
+      if (m < g.M) {
+#pragma unroll
+        for (int a = 0; a < 8; ++a) {
+          const int f_lo = packed_row_lo(nt, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
+          unsafeAtomicAdd(e.h + ht_index(m, f_lo, e.Mpad), acc[mt][a]);
+          unsafeAtomicAdd(e.h + ht_index(m, f_lo + g.pair_stride, e.Mpad), acc[mt][a + 8]);
+        }
+      }
+    }
+    if (e.rowsq) {
+      // last contraction slice of this workgroup's tiles: read the finished values back (device-scope atomic
+      // loads of words that were only ever touched by device-scope atomic adds) and add their squares to the
+      // row sums the next RMSNorm needs
+      __builtin_amdgcn_s_waitcnt(0);
+      __syncthreads();
+      const int cidx = blockIdx.x * chunks + chunk;
+      if (threadIdx.x == 0) s.flag = atomicAdd(e.tile_counters + cidx, 1);
+      __syncthreads();
+      const bool last = s.flag == ksplit - 1;
+      if (last) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          const int m = (chunk * MT + mt) * 32 + ml;
+          float ss = 0.0f;
+          if (m < g.M) {
+#pragma unroll
+            for (int a = 0; a < 8; ++a) {
+              const int f_lo = packed_row_lo(nt, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
+              const float v0 = __hip_atomic_load(e.h + ht_index(m, f_lo, e.Mpad), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              const float v1 = __hip_atomic_load(e.h + ht_index(m, f_lo + g.pair_stride, e.Mpad), __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+              ss = fmaf(v0, v0, ss);
+              ss = fmaf(v1, v1, ss);
+            }
+          }
+          s.part[wave][half][mt][ml] = ss;
+        }
+      }
+      __syncthreads();
+      if (last) {
+        for (int t = threadIdx.x; t < MT * 32; t += blockDim.x) {
+          const int mt = t >> 5, mm = t & 31;
+          float tot = 0.0f;
+#pragma unroll
+          for (int w = 0; w < NW; ++w) tot += s.part[w][0][mt][mm] + s.part[w][1][mt][mm];
+          const int m = (chunk * MT + mt) * 32 + mm;
+          if (m < g.M) unsafeAtomicAdd(e.rowsq + m, tot);
+        }
+        if (threadIdx.x == 0) e.tile_counters[cidx] = 0;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int m = (chunk * MT + mt) * 32 + ml;
+      if (m < g.M) {
+#pragma unroll
+        for (int a = 0; a < 8; ++a) {
+          const int f_lo = packed_row_lo(nt, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
+          if constexpr (std::is_same<Epi, QkvEpi>::value) {
+            epi_qkv<bf16_t>(e, m, f_lo, acc[mt][a], acc[mt][a + 8]);
+          } else {
+            epi_gateup<bf16_t>(e, m, f_lo, acc[mt][a], acc[mt][a + 8]);
+          }
+        }
+      }
+    }
+  }
+}
+
+// Batch tiles per pass of the streaming kernel / per chunk of the tiled kernel.
+int pick_mt(int M, int cap) {
   const int m_tiles = (M + 31) / 32;
-  if (m_tiles % 4 == 0) return 4;
-  if (m_tiles % 2 == 0) return 2;
+  for (int mt = cap; mt > 1; mt >>= 1)
+    if (m_tiles % mt == 0) return mt;
   return 1;
 }
 
 template <class Epi, bool FILL>
 void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int nz, hipStream_t st) {
-  dim3 grid(g.n_tiles, g.ksplit, nz), block(256);
-  switch (pick_mt(g.M)) {
+  dim3 block(256);
+  const int m_tiles = (g.M + 31) / 32;
+  // Batch chunks of 4 tiles (128 rows) measured faster than 8 at batch 256 and 512: twice the workgroups, each
+  // with half the accumulators, keeps more loads in flight; the second chunk's weight reads mostly hit the caches.
+  const int mt_tiled = pick_mt(g.M, 4);
+  if (mt_tiled >= 4 && g.n_tiles % NW == 0) {
+    // tiled kernel: four output tiles per workgroup share the activation operand through LDS
+    const int chunks = m_tiles / mt_tiled;
+    int ksplit = 1;
+    if constexpr (std::is_same<Epi, AccEpi>::value) {
+      const int k_steps = g.K / 16;
+      ksplit = 512 / ((g.n_tiles / NW) * chunks);
+      if (ksplit > k_steps / 64) ksplit = k_steps / 64;
+      if (ksplit < 1) ksplit = 1;
+    }
+    dim3 grid(g.n_tiles / NW, chunks * ksplit, nz);
+    hipLaunchKernelGGL((gemm_tiled_kernel<4, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
+    return;
+  }
+  dim3 grid(g.n_tiles, g.ksplit, nz);
+  switch (pick_mt(g.M, 4)) {
     case 4:
       hipLaunchKernelGGL((gemm_mfma_kernel<4, 2, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
       break;
