@@ -257,9 +257,12 @@ void enqueue_head_f32(const ee_model& M, const Workspace& w, const float* h, int
 }
 
 // --- KV filling for layers above fill_from ----------------------------------------------------------------
-// rowsq_slot: zeroed scratch that receives the row sums of squares of the hidden state being projected.
+// rowsq_layer_stride == 0: rowsq_slot is zeroed scratch and receives the row sums of squares of the hidden state
+// (stand-alone call).  > 0: rowsq_slot is slot 0 of the iteration's table and the sums of the exit hidden state are
+// already in slot 2 * batch_exit_layer, left there by that layer's down projection.
 void enqueue_fill_bf16(const ee_model& M, const ee_kv_cache& C, const ee_batch& Bt, const Workspace& w, int Mpad,
-                       const int32_t* fill_from, int stride, float* rowsq_slot, Pred pred, hipStream_t st) {
+                       const int32_t* fill_from, int stride, float* rowsq_slot, size_t rowsq_layer_stride, Pred pred,
+                       hipStream_t st) {
   const ee_model_desc& D = M.desc;
   GainTable gt{};
   FillLayers fl{};
@@ -268,9 +271,9 @@ void enqueue_fill_bf16(const ee_model& M, const ee_kv_cache& C, const ee_batch& 
     fl.w_qkv[i] = M.layers[i].w_qkv;
   }
   ProfScope ps(EE_K_KVFILL, 0, st);
-  launch_rowsq(w.hT, rowsq_slot, Mpad, D.d_model, pred, st);
-  launch_prep_x_layers(w.hT, gt, D.n_layers, w.fill_x, rowsq_slot, D.rms_eps, fill_from, stride, Bt.batch, Mpad, D.d_model,
-                       pred, st);
+  if (rowsq_layer_stride == 0) launch_rowsq(w.hT, rowsq_slot, Mpad, D.d_model, pred, st);
+  launch_prep_x_layers(w.hT, gt, D.n_layers, w.fill_x, rowsq_slot, rowsq_layer_stride, D.rms_eps, fill_from, stride,
+                       Bt.batch, Mpad, D.d_model, pred, st);
   GemmShape g{nullptr, nullptr, D.d_model, Bt.batch, D.d_model / 32, 2 * D.d_model / 32, D.head_dim / 2, 1};
   QkvEpi e = make_qkv_epi(D, C, Bt, w, 1, nullptr);
   e.fill_from = fill_from;
@@ -501,7 +504,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   // Algorithm 1, KV cache filling for layers output_layer+1..n (runs only if the batch left early)
   if (use_exit_heads) {
     if (bf)
-      enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, out_batch_exit_layer, 0, rs(2 * n + 1), run_fill, st);
+      enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, out_batch_exit_layer, 0, rs(0), (size_t)2 * Mpad, run_fill, st);
     else
       enqueue_fill_f32(*model, *cache, *batch, w, w.h, out_batch_exit_layer, 0, run_fill, st);
   }
@@ -581,7 +584,7 @@ int ee_kv_fill(const ee_model* model, const ee_kv_cache* cache, const ee_batch* 
     launch_iter_init(IterState{w.status, w.scratch_exit_layer, w.n_exited, w.done, w.scratch_L}, 0, D.n_layers, nullptr,
                      w.rowsq, (size_t)Mpad, st);
     launch_hidden_to_ht(hidden, w.hT, B, Mpad, D.d_model, st);
-    enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, fill_from_layer, 1, w.rowsq, always, st);
+    enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, fill_from_layer, 1, w.rowsq, 0, always, st);
   } else {
     enqueue_fill_f32(*model, *cache, *batch, w, hidden, fill_from_layer, 1, always, st);
   }

@@ -133,9 +133,10 @@ void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float*
 // Two normalisations of the same rows in one launch: slab 0 of xT_pair with gain_a, slab 1 (Mpad * d elements on) with gain_b.
 void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT_pair, const float* rowsq,
                         float eps, int Mpad, int d, Pred pred, hipStream_t st);
+// rowsq_layer_stride > 0 (with fill_from_stride == 0): the sums are at rowsq + fill_from[0] * rowsq_layer_stride.
 void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
-                          float eps, const int32_t* fill_from, int fill_from_stride, int B, int Mpad, int d, Pred pred,
-                          hipStream_t st);
+                          size_t rowsq_layer_stride, float eps, const int32_t* fill_from, int fill_from_stride, int B,
+                          int Mpad, int d, Pred pred, hipStream_t st);
 void launch_rmsnorm_f32(const float* h, const float* gain, float* x, int B, int d, float eps, Pred pred, hipStream_t st);
 void launch_head_stats_f32(const float* logits, float4* partials, int B, int vocab, float scale, Pred pred,
                            hipStream_t st);

@@ -206,7 +206,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
   __shared__ Lds s;
 
   if constexpr (FILL) {
-    const int layer = blockIdx.z + 1;
+    const int layer = (int)gridDim.z - (int)blockIdx.z;   // deepest layer first: the slices that have work start first
     if (!fill_needed(e, g.M, layer, s)) return;
     g.w = fc.layers.w_qkv[layer - 1];
     g.x = fc.x_slabs + (size_t)(layer - 1) * fc.x_slab_elems;
@@ -279,7 +279,7 @@ struct TiledLds {
   int flag;
 };
 
-template <int MT, class Epi, bool FILL>
+template <int MT, int NTW, class Epi, bool FILL>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pred pred, FillCtl fc) {
   if (pred_skip(pred)) return;
   __shared__ TiledLds<MT> s;
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
   static_assert(UT * MT % NW == 0, "stage must split evenly over the wavefronts");
 
   if constexpr (FILL) {
-    const int layer = blockIdx.z + 1;
+    const int layer = (int)gridDim.z - (int)blockIdx.z;   // deepest layer first: the slices that have work start first
     if (threadIdx.x == 0) s.flag = 0;
     __syncthreads();
     int need = 0;
@@ -312,31 +312,35 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
   const int chunks = m_tiles / MT;
   const int ksplit = gridDim.y / chunks;
   const int chunk = blockIdx.y / ksplit, ksl = blockIdx.y % ksplit;
-  const int nt = g.tile_begin + blockIdx.x * NW + wave;
+  const int nt0 = g.tile_begin + (blockIdx.x * NW + wave) * NTW;   // this wavefront's NTW consecutive output tiles
   const int k_steps = g.K >> 4;
   const int ks0 = (int)((long)k_steps * ksl / ksplit);
   const int ks1 = (int)((long)k_steps * (ksl + 1) / ksplit);
   const size_t x_tile_stride = (size_t)k_steps * 64;
-  const u32x4* wp = reinterpret_cast<const u32x4*>(g.w) + (size_t)nt * k_steps * 64 + lane;
+  const size_t w_tile_stride = (size_t)k_steps * 64;
+  const u32x4* wp = reinterpret_cast<const u32x4*>(g.w) + (size_t)nt0 * k_steps * 64 + lane;
   const u32x4* xp = reinterpret_cast<const u32x4*>(g.x) + (size_t)(chunk * MT) * x_tile_stride + lane;
 
-  f32x16 acc[MT];
+  f32x16 acc[NTW][MT];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
+  for (int t = 0; t < NTW; ++t)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[mt][i] = 0.0f;
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[t][mt][i] = 0.0f;
 
   // Everything in the loop is unconditional (a conditional load would force the compiler to wait for every
   // outstanding load where the branches meet): the group count is rounded up to the rotation period and
   // groups past the end load a clamped weight tile against zero activations.
-  u32x4 W[4][UT], X[2][XR];
+  u32x4 W[4][NTW][UT], X[2][XR];
   const int n = (ks1 - ks0 + UT - 1) / UT;
-  auto gload = [&](int grp, u32x4 (&wr)[UT], u32x4 (&xr)[XR]) {
+  auto gload = [&](int grp, u32x4 (&wr)[NTW][UT], u32x4 (&xr)[XR]) {
     const int kbase = ks0 + grp * UT;
 #pragma unroll
     for (int u = 0; u < UT; ++u) {
       const int kk = kbase + u < ks1 ? kbase + u : ks1 - 1;
-      wr[u] = __builtin_nontemporal_load(wp + (size_t)kk * 64);
+#pragma unroll
+      for (int t = 0; t < NTW; ++t) wr[t][u] = __builtin_nontemporal_load(wp + t * w_tile_stride + (size_t)kk * 64);
     }
 #pragma unroll
     for (int j = 0; j < XR; ++j) {
@@ -349,7 +353,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
   };
   // One group: drain its activation registers into LDS stage XS, start the loads of group grp+2 into the
   // registers just freed and an idle weight set, multiply group grp.
-  auto step = [&](int grp, const u32x4 (&wcur)[UT], u32x4 (&wnext2)[UT], u32x4 (&xs)[XR], int XS) {
+  auto step = [&](int grp, const u32x4 (&wcur)[NTW][UT], u32x4 (&wnext2)[NTW][UT], u32x4 (&xs)[XR], int XS) {
 #pragma unroll
     for (int j = 0; j < XR; ++j) {
       const int t = wave + NW * j;
@@ -369,8 +373,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
       }
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wcur[u]),
-                                                          __builtin_bit_cast(bf16x8, bf[u & 1][mt]), acc[mt], 0, 0, 0);
+#pragma unroll
+        for (int t = 0; t < NTW; ++t)
+          acc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wcur[t][u]),
+                                                               __builtin_bit_cast(bf16x8, bf[u & 1][mt]), acc[t][mt], 0, 0, 0);
     }
   };
 
@@ -389,36 +395,41 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
   const int half = lane >> 5, ml = lane & 31;
   if constexpr (std::is_same<Epi, LmEpi>::value) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      HeadStat st = stat_empty();
+    for (int t = 0; t < NTW; ++t)
 #pragma unroll
-      for (int a = 0; a < 8; ++a) {
-        const int r16 = (a >> 2) * 8 + half * 4 + (a & 3);
-        st = stat_push(st, acc[mt][a], nt * 32 + r16, e.scale);
-        st = stat_push(st, acc[mt][a + 8], nt * 32 + r16 + 16, e.scale);
-      }
-      HeadStat o;
-      o.zmax = __shfl_xor(st.zmax, 32);
-      o.sum = __shfl_xor(st.sum, 32);
-      o.z2 = __shfl_xor(st.z2, 32);
-      o.idx = __shfl_xor(st.idx, 32);
-      st = stat_merge(st, o, e.scale);
-      const int m = (chunk * MT + mt) * 32 + ml;
-      if (half == 0 && m < g.M) e.partials[(size_t)m * e.n_parts + (nt - g.tile_begin)] = stat_pack(st);
-    }
-  } else if constexpr (std::is_same<Epi, AccEpi>::value) {
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = (chunk * MT + mt) * 32 + ml;
-      if (m < g.M) {
+      for (int mt = 0; mt < MT; ++mt) {
+        const int nt = nt0 + t;
+        HeadStat st = stat_empty();
 #pragma unroll
         for (int a = 0; a < 8; ++a) {
-          const int f_lo = packed_row_lo(nt, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
-          unsafeAtomicAdd(e.h + ht_index(m, f_lo, e.Mpad), acc[mt][a]);
-          unsafeAtomicAdd(e.h + ht_index(m, f_lo + g.pair_stride, e.Mpad), acc[mt][a + 8]);
+          const int r16 = (a >> 2) * 8 + half * 4 + (a & 3);
+          st = stat_push(st, acc[t][mt][a], nt * 32 + r16, e.scale);
+          st = stat_push(st, acc[t][mt][a + 8], nt * 32 + r16 + 16, e.scale);
+        }
+        HeadStat o;
+        o.zmax = __shfl_xor(st.zmax, 32);
+        o.sum = __shfl_xor(st.sum, 32);
+        o.z2 = __shfl_xor(st.z2, 32);
+        o.idx = __shfl_xor(st.idx, 32);
+        st = stat_merge(st, o, e.scale);
+        const int m = (chunk * MT + mt) * 32 + ml;
+        if (half == 0 && m < g.M) e.partials[(size_t)m * e.n_parts + (nt - g.tile_begin)] = stat_pack(st);
+      }
+  } else if constexpr (std::is_same<Epi, AccEpi>::value) {
+#pragma unroll
+    for (int t = 0; t < NTW; ++t)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = (chunk * MT + mt) * 32 + ml;
+        if (m < g.M) {
+#pragma unroll
+          for (int a = 0; a < 8; ++a) {
+            const int f_lo = packed_row_lo(nt0 + t, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
+            unsafeAtomicAdd(e.h + ht_index(m, f_lo, e.Mpad), acc[t][mt][a]);
+            unsafeAtomicAdd(e.h + ht_index(m, f_lo + g.pair_stride, e.Mpad), acc[t][mt][a + 8]);
+          }
         }
       }
-    }
     if (e.rowsq) {
       // last contraction slice of this workgroup's tiles: read the finished values back (device-scope atomic
       // loads of words that were only ever touched by device-scope atomic adds) and add their squares to the
@@ -436,14 +447,16 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
           float ss = 0.0f;
           if (m < g.M) {
 #pragma unroll
-            for (int a = 0; a < 8; ++a) {
-              const int f_lo = packed_row_lo(nt, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
-              const float v0 = __hip_atomic_load(e.h + ht_index(m, f_lo, e.Mpad), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              const float v1 = __hip_atomic_load(e.h + ht_index(m, f_lo + g.pair_stride, e.Mpad), __ATOMIC_RELAXED,
-                                                 __HIP_MEMORY_SCOPE_AGENT);
-              ss = fmaf(v0, v0, ss);
-              ss = fmaf(v1, v1, ss);
-            }
+            for (int t = 0; t < NTW; ++t)
+#pragma unroll
+              for (int a = 0; a < 8; ++a) {
+                const int f_lo = packed_row_lo(nt0 + t, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
+                const float v0 = __hip_atomic_load(e.h + ht_index(m, f_lo, e.Mpad), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float v1 = __hip_atomic_load(e.h + ht_index(m, f_lo + g.pair_stride, e.Mpad), __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_AGENT);
+                ss = fmaf(v0, v0, ss);
+                ss = fmaf(v1, v1, ss);
+              }
           }
           s.part[wave][half][mt][ml] = ss;
         }
@@ -463,20 +476,22 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
     }
   } else {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const int m = (chunk * MT + mt) * 32 + ml;
-      if (m < g.M) {
+    for (int t = 0; t < NTW; ++t)
 #pragma unroll
-        for (int a = 0; a < 8; ++a) {
-          const int f_lo = packed_row_lo(nt, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
-          if constexpr (std::is_same<Epi, QkvEpi>::value) {
-            epi_qkv<bf16_t>(e, m, f_lo, acc[mt][a], acc[mt][a + 8]);
-          } else {
-            epi_gateup<bf16_t>(e, m, f_lo, acc[mt][a], acc[mt][a + 8]);
+      for (int mt = 0; mt < MT; ++mt) {
+        const int m = (chunk * MT + mt) * 32 + ml;
+        if (m < g.M) {
+#pragma unroll
+          for (int a = 0; a < 8; ++a) {
+            const int f_lo = packed_row_lo(nt0 + t, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
+            if constexpr (std::is_same<Epi, QkvEpi>::value) {
+              epi_qkv<bf16_t>(e, m, f_lo, acc[t][mt][a], acc[t][mt][a + 8]);
+            } else {
+              epi_gateup<bf16_t>(e, m, f_lo, acc[t][mt][a], acc[t][mt][a + 8]);
+            }
           }
         }
       }
-    }
   }
 }
 
@@ -496,17 +511,21 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
   // with half the accumulators, keeps more loads in flight; the second chunk's weight reads mostly hit the caches.
   const int mt_tiled = pick_mt(g.M, 4);
   if (mt_tiled >= 4 && g.n_tiles % NW == 0) {
-    // tiled kernel: four output tiles per workgroup share the activation operand through LDS
+    // tiled kernel: the workgroup's output tiles share the activation operand through LDS
     const int chunks = m_tiles / mt_tiled;
+    // One output tile per wavefront.  Two per wavefront (NTW = 2: each LDS operand read feeds two MFMAs, half the
+    // workgroups) measured slower at batch 256 and 512: the kernel is limited by loads in flight per compute unit,
+    // not by LDS bandwidth.
+    const int groups = g.n_tiles / NW;
     int ksplit = 1;
     if constexpr (std::is_same<Epi, AccEpi>::value) {
       const int k_steps = g.K / 16;
-      ksplit = 512 / ((g.n_tiles / NW) * chunks);
+      ksplit = 512 / (groups * chunks);
       if (ksplit > k_steps / 64) ksplit = k_steps / 64;
       if (ksplit < 1) ksplit = 1;
     }
-    dim3 grid(g.n_tiles / NW, chunks * ksplit, nz);
-    hipLaunchKernelGGL((gemm_tiled_kernel<4, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
+    dim3 grid(groups, chunks * ksplit, nz);
+    hipLaunchKernelGGL((gemm_tiled_kernel<4, 1, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
     return;
   }
   dim3 grid(g.n_tiles, g.ksplit, nz);

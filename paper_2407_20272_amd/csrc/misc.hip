@@ -100,9 +100,9 @@ __global__ __launch_bounds__(256) void rowsq_kernel(const float* hT, float* rows
 }
 
 __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable gains, const bf16_t* gain0, bf16_t* xT,
-                                                     size_t slab_elems, const float* rowsq, float eps,
-                                                     const int32_t* fill_from, int fill_from_stride, int B, int Mpad,
-                                                     int d, Pred pred) {
+                                                     size_t slab_elems, const float* rowsq, size_t rowsq_layer_stride,
+                                                     float eps, const int32_t* fill_from, int fill_from_stride, int B,
+                                                     int Mpad, int d, Pred pred) {
   if (pred_skip(pred)) return;
   const int z = blockIdx.z;
   const int ml = threadIdx.x & 31, cl = threadIdx.x >> 5;
@@ -124,6 +124,9 @@ __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable 
   const bf16_t* gain = gains.g[z] ? reinterpret_cast<const bf16_t*>(gains.g[z]) : gain0;
   const int c = blockIdx.x * 8 + cl;  // 8-channel chunk
   const int k0 = c * 8;
+  // KV filling inside a decode iteration: the sums of the exit hidden state were left by the down projection of the
+  // batch exit layer L (= fill_from[0]) in slot 2L of the per-iteration table
+  if (rowsq_layer_stride) rowsq += (size_t)fill_from[0] * rowsq_layer_stride;
   const float r = rsqrtf(rowsq[m] / (float)d + eps);
   bf16x8 out;
 #pragma unroll
@@ -249,7 +252,7 @@ void launch_rowsq(const float* hT, float* rowsq, int Mpad, int d, Pred pred, hip
 void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, float eps, int Mpad, int d,
                    Pred pred, hipStream_t st) {
   GainTable none{};
-  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 1), dim3(256), 0, st, hT, none, gain, xT, (size_t)0, rowsq, eps,
+  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 1), dim3(256), 0, st, hT, none, gain, xT, (size_t)0, rowsq, (size_t)0, eps,
                      (const int32_t*)nullptr, 0, 0, Mpad, d, pred);
 }
 void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT_pair, const float* rowsq,
@@ -258,14 +261,14 @@ void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gai
   two.g[0] = gain_a;
   two.g[1] = gain_b;
   hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 2), dim3(256), 0, st, hT, two, (const bf16_t*)nullptr, xT_pair,
-                     (size_t)Mpad * d, rowsq, eps, (const int32_t*)nullptr, 0, 0, Mpad, d, pred);
+                     (size_t)Mpad * d, rowsq, (size_t)0, eps, (const int32_t*)nullptr, 0, 0, Mpad, d, pred);
 }
 void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
-                          float eps, const int32_t* fill_from, int fill_from_stride, int B, int Mpad, int d, Pred pred,
-                          hipStream_t st) {
+                          size_t rowsq_layer_stride, float eps, const int32_t* fill_from, int fill_from_stride, int B,
+                          int Mpad, int d, Pred pred, hipStream_t st) {
   hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, n_layers), dim3(256), 0, st, hT, gains,
-                     (const bf16_t*)nullptr, xT_slabs, (size_t)Mpad * d, rowsq, eps, fill_from, fill_from_stride, B, Mpad,
-                     d, pred);
+                     (const bf16_t*)nullptr, xT_slabs, (size_t)Mpad * d, rowsq, rowsq_layer_stride, eps, fill_from,
+                     fill_from_stride, B, Mpad, d, pred);
 }
 void launch_rmsnorm_f32(const float* h, const float* gain, float* x, int B, int d, float eps, Pred pred, hipStream_t st) {
   hipLaunchKernelGGL(rmsnorm_f32_kernel, dim3(B), dim3(256), 0, st, h, gain, x, d, eps, pred);
