@@ -58,11 +58,19 @@ __device__ inline float group_sum(float v) {
   return v;
 }
 
-constexpr int TABLE_LDS = 512;   // block-table entries staged in LDS (contexts up to 8192 tokens)
+// 16 bytes of the cache, read once per iteration and never again: a streaming (non-temporal) load, which leaves
+// the caches to the data that is reused.
+template <class T>
+__device__ inline uint4 load_stream(const T* p) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+constexpr int TABLE_LDS_MAX = 16384;   // block-table entries staged in LDS: contexts up to 262144 tokens
 
 template <class T, int DH, bool OUT_XT>
 __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred) {
-  if (pred_skip(pred)) return;
   constexpr int EPL = Elems<T>::N;         // values per 16-byte lane load
   constexpr int LPT = DH / EPL;            // lanes per token
   constexpr int TPL = 64 / LPT;            // tokens per wavefront load
@@ -74,21 +82,36 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int sub = lane % LPT;              // which EPL-wide slice of the head this lane holds
   const int grp = lane / LPT;              // which token of a load this lane sees
-  const int n_ctx = a.context_lens[b] + 1; // positions 0..p inclusive
-  const int n_blocks = (n_ctx + 15) >> 4;
   const int32_t* table = a.block_tables + (size_t)b * a.max_blocks;
 
-  // the sequence's block table goes to LDS once, so the block loop never waits on a table read
-  __shared__ int32_t tbl[TABLE_LDS];
-  for (int i = threadIdx.x; i < n_blocks && i < TABLE_LDS; i += blockDim.x) tbl[i] = table[i];
-
-  // q slice, pre-scaled so that exp2 can be used: softmax(x) = 2^(x*log2 e)
+  // Everything the first K/V load needs is requested before anything is waited for: the predicate word, the
+  // context length, the start of the block-table row (its width is known without the length) and q.  One
+  // memory round trip instead of three in a row.
+  extern __shared__ int32_t tbl[];
+  const int t0 = (int)threadIdx.x < a.max_blocks ? table[threadIdx.x] : 0;
+  const int len = a.context_lens[b];
   float q[EPL];
   {
-    const float sc = 1.4426950408889634f / sqrtf((float)DH);
     const float* qp = a.q + ((size_t)b * a.n_heads + head) * DH + sub * EPL;
 #pragma unroll
-    for (int i = 0; i < EPL; ++i) q[i] = qp[i] * sc;
+    for (int i = 0; i < EPL; ++i) q[i] = qp[i];
+  }
+  if (pred_skip(pred)) return;
+
+  // positions 0..p inclusive, never beyond the block table's width
+  const int n_ctx = min(len + 1, a.max_blocks * 16);
+  const int n_blocks = (n_ctx + 15) >> 4;
+
+  // The sequence's block table goes to LDS once (max_blocks entries of dynamic LDS).  The block loop must not
+  // read it from memory: the wait for such a read would also wait for every K/V load issued before it.
+  if ((int)threadIdx.x < a.max_blocks) tbl[threadIdx.x] = t0;
+  for (int i = threadIdx.x + blockDim.x; i < n_blocks; i += blockDim.x) tbl[i] = table[i];
+
+  // q slice, pre-scaled so that exp2 can be used: softmax(x) = 2^(x*log2 e)
+  {
+    const float sc = 1.4426950408889634f / sqrtf((float)DH);
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) q[i] *= sc;
   }
   __syncthreads();
 
@@ -105,12 +128,12 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
     uint4 k[LPB], v[LPB];
   };
   auto fetch = [&](Blk& x, int lb) {
-    const int phys = lb < TABLE_LDS ? tbl[lb] : table[lb];
+    const int phys = tbl[lb];
     const size_t off = (size_t)phys * block_elems;
 #pragma unroll
     for (int i = 0; i < LPB; ++i) {
-      x.k[i] = *reinterpret_cast<const uint4*>(kbase + off + (size_t)i * TPL * DH);
-      x.v[i] = *reinterpret_cast<const uint4*>(vbase + off + (size_t)i * TPL * DH);
+      x.k[i] = load_stream(kbase + off + (size_t)i * TPL * DH);
+      x.v[i] = load_stream(vbase + off + (size_t)i * TPL * DH);
     }
   };
   auto consume = [&](const Blk& x, int lb) {
@@ -145,17 +168,30 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
     m_run = m_new;
   };
 
-  // two blocks of this wavefront in flight at any time
+  // Two blocks of this wavefront in flight at any time.  The steady loop has no conditional load: a load under
+  // a condition makes the compiler wait for every outstanding load where the paths join, which would drain
+  // the stream once per block; the scheduling fences keep each block's loads together ahead of the arithmetic.
   Blk A, B;
-  if (wave < n_blocks) fetch(A, wave);
-  if (wave + NW < n_blocks) fetch(B, wave + NW);
-  for (int lb = wave; lb < n_blocks; lb += 2 * NW) {
+  int lb = wave;
+  if (lb < n_blocks) fetch(A, lb);
+  if (lb + NW < n_blocks) fetch(B, lb + NW);
+  for (; lb + 3 * NW < n_blocks; lb += 2 * NW) {
     consume(A, lb);
-    if (lb + 2 * NW < n_blocks) fetch(A, lb + 2 * NW);
-    if (lb + NW < n_blocks) {
-      consume(B, lb + NW);
-      if (lb + 3 * NW < n_blocks) fetch(B, lb + 3 * NW);
-    }
+    __builtin_amdgcn_sched_barrier(0);
+    fetch(A, lb + 2 * NW);
+    __builtin_amdgcn_sched_barrier(0);
+    consume(B, lb + NW);
+    __builtin_amdgcn_sched_barrier(0);
+    fetch(B, lb + 3 * NW);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  // at most three blocks left: lb (in A), lb + NW (in B), lb + 2 NW (not fetched yet)
+  if (lb < n_blocks) {
+    consume(A, lb);
+    const bool third = lb + 2 * NW < n_blocks;
+    if (third) fetch(A, lb + 2 * NW);
+    if (lb + NW < n_blocks) consume(B, lb + NW);
+    if (third) consume(A, lb + 2 * NW);
   }
 
   // merge the TPL lane groups of the wavefront
@@ -209,16 +245,19 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
 template <class T, int DH>
 void launch_t(const AttnArgs& a, Pred pred, hipStream_t st) {
   dim3 grid(a.n_heads, a.B), block(256);
+  const size_t lds = (size_t)a.max_blocks * sizeof(int32_t);
   if (a.out_xt)
-    hipLaunchKernelGGL((attn_decode_kernel<T, DH, true>), grid, block, 0, st, a, pred);
+    hipLaunchKernelGGL((attn_decode_kernel<T, DH, true>), grid, block, lds, st, a, pred);
   else
-    hipLaunchKernelGGL((attn_decode_kernel<T, DH, false>), grid, block, 0, st, a, pred);
+    hipLaunchKernelGGL((attn_decode_kernel<T, DH, false>), grid, block, lds, st, a, pred);
 }
 
 }  // namespace
 
 int launch_attention(const AttnArgs& a, int dtype, Pred pred, hipStream_t st) {
   if (a.B == 0) return EE_OK;
+  if (a.max_blocks < 1 || a.max_blocks > TABLE_LDS_MAX)
+    EE_FAIL(EE_ERR_UNSUPPORTED, "attention: max_blocks %d outside 1..%d", a.max_blocks, TABLE_LDS_MAX);
   if (dtype == EE_FP32) {
     if (a.head_dim == 64) launch_t<float, 64>(a, pred, st);
     else if (a.head_dim == 128) launch_t<float, 128>(a, pred, st);

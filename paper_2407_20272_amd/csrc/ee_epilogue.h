@@ -98,6 +98,41 @@ __device__ inline HeadStat stat_push(const HeadStat& a, float z, int idx, float 
   HeadStat b = {z, 1.0f, -INFINITY, idx};
   return stat_merge(a, b, scale);
 }
+// Statistics of 32 logits of one row that sit four each in eight neighbouring lanes (lane & 7 = which four):
+// two short passes (largest with its index, then the sum of exponentials and the runner-up) instead of 32
+// dependent pushes.  z[i] has vocabulary index idx0 + i.  Every one of the eight lanes returns the result.
+__device__ inline HeadStat stat_of_8x4(const float (&z)[4], int idx0, float scale) {
+  float best = z[0];
+  int bi = idx0;
+#pragma unroll
+  for (int i = 1; i < 4; ++i)
+    if (z[i] > best) {   // strict: the lowest index wins among equals
+      best = z[i];
+      bi = idx0 + i;
+    }
+#pragma unroll
+  for (int x = 1; x < 8; x <<= 1) {
+    const float ob = __shfl_xor(best, x);
+    const int oi = __shfl_xor(bi, x);
+    if (ob > best || (ob == best && oi < bi)) {
+      best = ob;
+      bi = oi;
+    }
+  }
+  float sum = 0.0f, z2 = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    sum += expf(scale * (z[i] - best));
+    if (idx0 + i != bi) z2 = fmaxf(z2, z[i]);
+  }
+#pragma unroll
+  for (int x = 1; x < 8; x <<= 1) {
+    sum += __shfl_xor(sum, x);
+    z2 = fmaxf(z2, __shfl_xor(z2, x));
+  }
+  return {best, sum, z2, bi};
+}
+
 __device__ inline float4 stat_pack(const HeadStat& s) { return make_float4(s.zmax, s.sum, s.z2, __int_as_float(s.idx)); }
 __device__ inline HeadStat stat_unpack(const float4& v) { return {v.x, v.y, v.z, __float_as_int(v.w)}; }
 

@@ -82,13 +82,14 @@ __device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, con
       s.zt[r16[ai] + 16][l2 & 31] = vhi[ai] * r;
     }
     __syncthreads();
-    if (threadIdx.x < 32) {
-      const int mm = mt_global * 32 + threadIdx.x;
-      if (mm < g.M) {
-        HeadStat st = stat_empty();
-        for (int rr = 0; rr < 32; ++rr) st = stat_push(st, s.zt[rr][threadIdx.x], nt * 32 + rr, e.scale);
-        e.partials[(size_t)mm * e.n_parts + (nt - g.tile_begin)] = stat_pack(st);
-      }
+    {   // eight neighbouring lanes share one batch row: four logits each
+      const int ml = threadIdx.x >> 3, part = threadIdx.x & 7;
+      float z[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) z[i] = s.zt[part * 4 + i][ml];
+      const HeadStat st = stat_of_8x4(z, nt * 32 + part * 4, e.scale);
+      const int mm = mt_global * 32 + ml;
+      if (part == 0 && mm < g.M) e.partials[(size_t)mm * e.n_parts + (nt - g.tile_begin)] = stat_pack(st);
     }
   } else if constexpr (std::is_same<Epi, AccEpi>::value) {
     float* p[4];
@@ -202,7 +203,12 @@ __device__ inline void frag_mma(const Frag<MT, U>& f, f32x16 (&acc)[MT]) {
 
 template <int MT, int U, class Epi, bool FILL>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred pred, FillCtl fc) {
-  if (pred_skip(pred)) return;
+  // The predicate word comes from memory.  The layer kernels wait for it only after their first group of
+  // loads is on its way (a skipped launch then drops a few loads of valid memory on the floor); KV filling
+  // needs it first, because what it reads depends on what ran.
+  if constexpr (FILL) {
+    if (pred_skip(pred)) return;
+  }
   __shared__ Lds s;
 
   if constexpr (FILL) {
@@ -241,15 +247,32 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
     const int n = (ks1 - ks0) / U;
     int k = ks0;
     if (n > 0) frag_load(A, wp, xp, x_tile_stride, k);
+    if constexpr (!FILL) {
+      if (mt0 == 0 && pred_skip(pred)) return;
+    }
     int i = 0;
-    for (; i + 2 <= n; i += 2) {
+    // steady state: no load of the loop body is conditional, so the counted waits before each multiply are
+    // exact and one whole group stays in flight behind the one being multiplied (a load under a condition
+    // makes the compiler wait for the worst case at the join, which drains the stream)
+    // (the scheduling fences keep the compiler from sinking the loads of a group in between the multiplies
+    // that free their registers, which would leave only a few loads in flight)
+    for (; i + 3 <= n; i += 2) {
       frag_load(B, wp, xp, x_tile_stride, k + U);
+      __builtin_amdgcn_sched_barrier(0);
       frag_mma(A, acc);
-      if (i + 2 < n) frag_load(A, wp, xp, x_tile_stride, k + 2 * U);
+      __builtin_amdgcn_sched_barrier(0);
+      frag_load(A, wp, xp, x_tile_stride, k + 2 * U);
+      __builtin_amdgcn_sched_barrier(0);
       frag_mma(B, acc);
+      __builtin_amdgcn_sched_barrier(0);
       k += 2 * U;
     }
-    if (i < n) {
+    if (n - i == 2) {
+      frag_load(B, wp, xp, x_tile_stride, k + U);
+      frag_mma(A, acc);
+      frag_mma(B, acc);
+      k += 2 * U;
+    } else if (n - i == 1) {
       frag_mma(A, acc);
       k += U;
     }

@@ -103,7 +103,9 @@ __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable 
                                                      size_t slab_elems, const float* rowsq, size_t rowsq_layer_stride,
                                                      float eps, const int32_t* fill_from, int fill_from_stride, int B,
                                                      int Mpad, int d, Pred pred) {
-  if (pred_skip(pred)) return;
+  // The predicate word comes from memory: outside KV filling it is only waited for after this thread's own
+  // loads have been issued (all of valid memory whether or not the launch is skipped).
+  if (fill_from && pred_skip(pred)) return;
   const int z = blockIdx.z;
   const int ml = threadIdx.x & 31, cl = threadIdx.x >> 5;
   const int m = blockIdx.y * 32 + ml;
@@ -127,10 +129,16 @@ __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable 
   // KV filling inside a decode iteration: the sums of the exit hidden state were left by the down projection of the
   // batch exit layer L (= fill_from[0]) in slot 2L of the per-iteration table
   if (rowsq_layer_stride) rowsq += (size_t)fill_from[0] * rowsq_layer_stride;
-  const float r = rsqrtf(rowsq[m] / (float)d + eps);
+  const float rq = rowsq[m];
+  float hv[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) hv[i] = hT[ht_index(m, k0 + i, Mpad)];
+  const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gain + k0);
+  if (!fill_from && pred_skip(pred)) return;
+  const float r = rsqrtf(rq / (float)d + eps);
   bf16x8 out;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) out[i] = (bf16_t)(hT[ht_index(m, k0 + i, Mpad)] * r * (float)gain[k0 + i]);
+  for (int i = 0; i < 8; ++i) out[i] = (bf16_t)(hv[i] * r * (float)gv[i]);
   *reinterpret_cast<bf16x8*>(xT + (size_t)z * slab_elems + xt_index(m, k0, d)) = out;
 }
 
