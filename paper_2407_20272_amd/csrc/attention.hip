@@ -84,10 +84,11 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   const int grp = lane / LPT;              // which token of a load this lane sees
   const int32_t* table = a.block_tables + (size_t)b * a.max_blocks;
 
-  // Everything the first K/V load needs is requested before anything is waited for: the predicate word, the
-  // context length, the start of the block-table row (its width is known without the length) and q.  One
-  // memory round trip instead of three in a row.
   extern __shared__ int32_t tbl[];
+  if (pred_skip(pred)) return;
+  // Everything the first K/V load needs is requested before any of it is waited for: the context length, the
+  // start of the block-table row (its width is known without the length) and q: one memory round trip, not
+  // three in a row.
   const int t0 = (int)threadIdx.x < a.max_blocks ? table[threadIdx.x] : 0;
   const int len = a.context_lens[b];
   float q[EPL];
@@ -96,8 +97,6 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
 #pragma unroll
     for (int i = 0; i < EPL; ++i) q[i] = qp[i];
   }
-  if (pred_skip(pred)) return;
-
   // positions 0..p inclusive, never beyond the block table's width
   const int n_ctx = min(len + 1, a.max_blocks * 16);
   const int n_blocks = (n_ctx + 15) >> 4;

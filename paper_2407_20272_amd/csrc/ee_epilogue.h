@@ -133,6 +133,27 @@ __device__ inline HeadStat stat_of_8x4(const float (&z)[4], int idx0, float scal
   return {best, sum, z2, bi};
 }
 
+// Statistics of N logits held by one thread (z[i] has vocabulary index idx[i], ascending): largest first, then
+// the exponentials, which are independent of each other.
+template <int N>
+__device__ inline HeadStat stat_of(const float (&z)[N], const int (&idx)[N], float scale) {
+  float best = z[0];
+  int bi = idx[0];
+#pragma unroll
+  for (int i = 1; i < N; ++i)
+    if (z[i] > best) {
+      best = z[i];
+      bi = idx[i];
+    }
+  float sum = 0.0f, z2 = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < N; ++i) {
+    sum += expf(scale * (z[i] - best));
+    if (idx[i] != bi) z2 = fmaxf(z2, z[i]);
+  }
+  return {best, sum, z2, bi};
+}
+
 __device__ inline float4 stat_pack(const HeadStat& s) { return make_float4(s.zmax, s.sum, s.z2, __int_as_float(s.idx)); }
 __device__ inline HeadStat stat_unpack(const float4& v) { return {v.x, v.y, v.z, __float_as_int(v.w)}; }
 

@@ -203,12 +203,7 @@ __device__ inline void frag_mma(const Frag<MT, U>& f, f32x16 (&acc)[MT]) {
 
 template <int MT, int U, class Epi, bool FILL>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred pred, FillCtl fc) {
-  // The predicate word comes from memory.  The layer kernels wait for it only after their first group of
-  // loads is on its way (a skipped launch then drops a few loads of valid memory on the floor); KV filling
-  // needs it first, because what it reads depends on what ran.
-  if constexpr (FILL) {
-    if (pred_skip(pred)) return;
-  }
+  if (pred_skip(pred)) return;
   __shared__ Lds s;
 
   if constexpr (FILL) {
@@ -247,32 +242,17 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
     const int n = (ks1 - ks0) / U;
     int k = ks0;
     if (n > 0) frag_load(A, wp, xp, x_tile_stride, k);
-    if constexpr (!FILL) {
-      if (mt0 == 0 && pred_skip(pred)) return;
-    }
     int i = 0;
-    // steady state: no load of the loop body is conditional, so the counted waits before each multiply are
-    // exact and one whole group stays in flight behind the one being multiplied (a load under a condition
-    // makes the compiler wait for the worst case at the join, which drains the stream)
-    // (the scheduling fences keep the compiler from sinking the loads of a group in between the multiplies
-    // that free their registers, which would leave only a few loads in flight)
-    for (; i + 3 <= n; i += 2) {
+    // (An unconditional steady-state loop with counted waits that keeps a whole group in flight behind the one
+    // being multiplied was measured too: no faster in the decode step, so the simpler loop stays.)
+    for (; i + 2 <= n; i += 2) {
       frag_load(B, wp, xp, x_tile_stride, k + U);
-      __builtin_amdgcn_sched_barrier(0);
       frag_mma(A, acc);
-      __builtin_amdgcn_sched_barrier(0);
-      frag_load(A, wp, xp, x_tile_stride, k + 2 * U);
-      __builtin_amdgcn_sched_barrier(0);
+      if (i + 2 < n) frag_load(A, wp, xp, x_tile_stride, k + 2 * U);
       frag_mma(B, acc);
-      __builtin_amdgcn_sched_barrier(0);
       k += 2 * U;
     }
-    if (n - i == 2) {
-      frag_load(B, wp, xp, x_tile_stride, k + U);
-      frag_mma(A, acc);
-      frag_mma(B, acc);
-      k += 2 * U;
-    } else if (n - i == 1) {
+    if (i < n) {
       frag_mma(A, acc);
       k += U;
     }
@@ -422,13 +402,18 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int nt = nt0 + t;
-        HeadStat st = stat_empty();
+        // this lane's 16 logits of the row in ascending vocabulary order: rows r16(a), a = 0..7, then r16(a)+16
+        float z[16];
+        int zi[16];
 #pragma unroll
         for (int a = 0; a < 8; ++a) {
           const int r16 = (a >> 2) * 8 + half * 4 + (a & 3);
-          st = stat_push(st, acc[t][mt][a], nt * 32 + r16, e.scale);
-          st = stat_push(st, acc[t][mt][a + 8], nt * 32 + r16 + 16, e.scale);
+          z[a] = acc[t][mt][a];
+          zi[a] = nt * 32 + r16;
+          z[a + 8] = acc[t][mt][a + 8];
+          zi[a + 8] = nt * 32 + r16 + 16;
         }
+        HeadStat st = stat_of<16>(z, zi, e.scale);
         HeadStat o;
         o.zmax = __shfl_xor(st.zmax, 32);
         o.sum = __shfl_xor(st.sum, 32);

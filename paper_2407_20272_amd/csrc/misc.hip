@@ -103,9 +103,7 @@ __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable 
                                                      size_t slab_elems, const float* rowsq, size_t rowsq_layer_stride,
                                                      float eps, const int32_t* fill_from, int fill_from_stride, int B,
                                                      int Mpad, int d, Pred pred) {
-  // The predicate word comes from memory: outside KV filling it is only waited for after this thread's own
-  // loads have been issued (all of valid memory whether or not the launch is skipped).
-  if (fill_from && pred_skip(pred)) return;
+  if (pred_skip(pred)) return;
   const int z = blockIdx.z;
   const int ml = threadIdx.x & 31, cl = threadIdx.x >> 5;
   const int m = blockIdx.y * 32 + ml;
@@ -134,7 +132,6 @@ __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable 
 #pragma unroll
   for (int i = 0; i < 8; ++i) hv[i] = hT[ht_index(m, k0 + i, Mpad)];
   const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gain + k0);
-  if (!fill_from && pred_skip(pred)) return;
   const float r = rsqrtf(rq / (float)d + eps);
   bf16x8 out;
 #pragma unroll
