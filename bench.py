@@ -221,6 +221,7 @@ def main():
             mean_ctx1 = float(ctx_before.float().mean()) + 1 + (P - 1) / 2.0
             per_iter = len(recs) // P
             agg = collections.defaultdict(lambda: [0, 0.0])
+            fill_bytes = 0.0   # KV filling streams the K and V weight rows of every skipped layer: (n - L) * 2 d^2 * 2 bytes
             for it in range(P):
                 for cls, layer, ms in recs[it * per_iter:(it + 1) * per_iter]:
                     # kernels of layers above the batch exit layer return at once; KV filling only runs after an
@@ -229,13 +230,15 @@ def main():
                     if executed:
                         agg[cls][0] += 1
                         agg[cls][1] += ms
+                        if cls == "kv_fill":
+                            fill_bytes += (n - Lp[it]) * 2.0 * cfg.d_model * cfg.d_model * 2
             prof[mode] = {"mean_ctx_plus1": mean_ctx1}
             for cls, (cnt, ms) in agg.items():
                 # HIP-event time of a kernel = its duration in a rocprofv3 kernel trace + about 2 us (compared on the
                 # same kernels, see profiles/); it is reported as measured, so the rates below are slightly low
                 avg_us = ms / cnt * 1e3
                 entry = {"launches_per_step": cnt / P, "avg_us": avg_us, "share_of_event_time": None}
-                ab = algorithmic_bytes(cfg, cls, mean_ctx1)
+                ab = fill_bytes / cnt if cls == "kv_fill" else algorithmic_bytes(cfg, cls, mean_ctx1)
                 if ab:
                     entry["algorithmic_MB"] = ab / 1e6
                     entry["GBps"] = ab / (avg_us * 1e-6) / 1e9
