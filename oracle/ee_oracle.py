@@ -25,6 +25,12 @@ Readings taken where the paper is silent or inconsistent (each also listed in th
     RMSNorm with layer i's attention gain, the K and V projections, rotary embedding on K.
   * confidence mode 0 = largest softmax probability (the benchmark definition); mode 1 = top-1 minus
     top-2 softmax probability (Section 2.1, softmax response).  Strict '>' against the threshold.
+  * confidence mode 2 = cos(h_{i-1}, h_i) (Section 2.1, hidden states similarity): the hidden states
+    after layers i-1 and i, h_0 being the embedding; taken on the float residual stream.
+  * confidence mode 3 = M(h_i) (Section 2.1, dedicated classifier), read as one linear unit per layer
+    on the hidden state followed by the logistic function: 1 / (1 + exp(-(w_i . h_i + b_i))).
+    Modes 2 and 3 never touch the LM head inside the loop; tokens still come from the hidden state at
+    output_layer through transform_to_tokens, as Algorithm 1 says.
   * exit head = final RMSNorm gain + the LM head, logits multiplied by logit_scale * i (1-based i);
     no check after the last layer; ties in argmax go to the lowest index.
 
@@ -176,13 +182,30 @@ def confidence(z: torch.Tensor, mode: int) -> torch.Tensor:
     return top[:, 0] - second
 
 
+def similarity_confidence(h_prev: torch.Tensor, h: torch.Tensor) -> torch.Tensor:
+    """Section 2.1, hidden states similarity: cos(h_{i-1}, h_i) per row of [R][d]."""
+    a, b = h_prev.to(F64), h.to(F64)
+    return (a * b).sum(dim=-1) / (a.pow(2).sum(dim=-1).sqrt() * b.pow(2).sum(dim=-1).sqrt())
+
+
+def classifier_confidence(m: OracleModel, i: int, h: torch.Tensor) -> torch.Tensor:
+    """Section 2.1, dedicated early-exit classifier M(h_i): logistic function of one linear unit per layer."""
+    t = h.to(F64) @ m.weights["w_cls"][i - 1].to(F64) + float(m.weights["b_cls"][i - 1])
+    return 1.0 / (1.0 + torch.exp(-t))
+
+
 def has_exit_head(m: OracleModel, i: int) -> bool:
     """Layers that carry an exit head: every exit_every-th layer, never the last one."""
     return i < m.n_layers and i % m.exit_every == 0
 
 
-def exit_check(m: OracleModel, i: int, h: torch.Tensor, rows: List[int]):
-    """Exit-head confidence (and arg max) at layer i for the listed rows of h."""
+def exit_check(m: OracleModel, i: int, h: torch.Tensor, rows: List[int], h_prev: Optional[torch.Tensor] = None):
+    """Confidence at layer i for the listed rows of h (and the exit head's arg max, where there is one).
+    h_prev: the hidden state before layer i (only read by the similarity measure)."""
+    if m.conf_mode == 2:
+        return similarity_confidence(h_prev[rows], h[rows]), None
+    if m.conf_mode == 3:
+        return classifier_confidence(m, i, h[rows]), None
     z = head_logits(m, h[rows])
     return confidence((m.logit_scale * i) * z, m.conf_mode), torch.argmax(z, dim=-1)
 
@@ -241,12 +264,13 @@ def decode_iteration(m: OracleModel, cache: DenseKV, tokens: torch.Tensor, pos: 
     if trace is not None:
         trace["h"] = []
     for i in range(1, n + 1):
+        h_prev = h
         h = layer_forward(m, i, h, cache, pos)
         if trace is not None:
             trace["h"].append(h.clone())
         if heads and B > 0 and has_exit_head(m, i):
             rows = [b for b in range(B) if not status[b]]
-            c, _ = exit_check(m, i, h, rows)
+            c, _ = exit_check(m, i, h, rows, h_prev)
             conf = {b: float(c[r]) for r, b in enumerate(rows)}
             for b in rows:
                 conf_log[i - 1, b] = conf[b]

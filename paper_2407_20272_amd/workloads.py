@@ -44,7 +44,9 @@ class EEConfig:
     shuffled_blocks: bool = False
     rms_eps: float = 1e-5
     rope_theta: float = 10000.0
-    conf_mode: int = 0          # 0 = max softmax prob, 1 = top1 - top2 (softmax response as the paper writes it)
+    # 0 = max softmax prob, 1 = top1 - top2 (softmax response as the paper writes it),
+    # 2 = cosine similarity of consecutive hidden states, 3 = dedicated linear classifier (Section 2.1)
+    conf_mode: int = 0
     weight_std: float = 0.02
 
     @property
@@ -146,6 +148,12 @@ def make_weights(cfg: EEConfig, seed: int = 0, device="cpu", gain_jitter: float 
             "w_down": _normal((d, f), std, seed, f"l{i}.w_down", device, dt),
         })
     w["layers"] = layers
+    # Synthetic dedicated exit classifier (Section 2.1, third measure): one float32 weight row and one bias
+    # per layer.  No trained classifier exists here: rows are N(0, 1) and the bias rises linearly from -2 at
+    # layer 1 to +2 at layer n, so that deeper layers accept more often, as a trained one would.
+    n = cfg.n_layers
+    w["w_cls"] = _normal((n, d), 1.0, seed, "w_cls", device, torch.float32)
+    w["b_cls"] = torch.tensor([-2.0 + 4.0 * i / max(n - 1, 1) for i in range(n)], dtype=torch.float32, device=device)
     return w
 
 
@@ -154,6 +162,9 @@ def weights_to(w: Dict, device) -> Dict:
     out = {"embed": w["embed"].to(device), "g_final": w["g_final"].to(device)}
     out["w_lm"] = out["embed"] if w["w_lm"] is w["embed"] else w["w_lm"].to(device)
     out["layers"] = [{k: v.to(device) for k, v in lw.items()} for lw in w["layers"]]
+    for k in ("w_cls", "b_cls"):
+        if k in w:
+            out[k] = w[k].to(device)
     return out
 
 

@@ -201,7 +201,7 @@ def run_control(monkeypatch, conf, lam, exit_every=1):
     executed, filled, checked = [], [], []
     monkeypatch.setattr(O, "layer_forward", lambda m, i, h, cache, pos: (executed.append(i), h)[1])
     monkeypatch.setattr(O, "exit_check",
-                        lambda m, i, h, rows: (checked.append((i, tuple(rows))),
+                        lambda m, i, h, rows, h_prev=None: (checked.append((i, tuple(rows))),
                                                (conf[i - 1, rows], torch.zeros(len(rows))))[1])
     monkeypatch.setattr(O, "kv_fill", lambda m, cache, h, pos, first: filled.extend(range(first, m.n_layers + 1)))
     monkeypatch.setattr(O, "transform_to_tokens", lambda m, h: torch.zeros(h.shape[0], dtype=torch.int32))
@@ -370,3 +370,114 @@ def test_bf16_storage_rounding_is_nearest_even():
     got = O.store(x, "bf16")
     assert got.tolist()[:5] == [1.0, 1.0, 1.0 + 4 * e, 1.0 + 2 * e, -1.0]
     assert torch.equal(O.store(x, "fp32"), x)
+
+
+# ------------------------------------------------------------------------------------------------
+# P7: hidden-state similarity and dedicated classifier (Section 2.1, second and third measure)
+# ------------------------------------------------------------------------------------------------
+def brute_hidden_states(cfg, w, toks):
+    """Hidden state of the LAST position after the embedding and after every layer, from an uncached causal
+    forward built of library routines: list of n+1 vectors [d], float64."""
+    T = toks.shape[0]
+    H, dh = cfg.n_heads, cfg.head_dim
+    h = w["embed"].to(F64)[toks.long()]
+    out = [h[-1].clone()]
+    for lw in w["layers"]:
+        x = F.rms_norm(h, (cfg.d_model,), lw["g_attn"].to(F64), cfg.rms_eps)
+        q = rope_complex(F.linear(x, lw["w_q"].to(F64)).view(T, H, dh), cfg.rope_theta)
+        k = rope_complex(F.linear(x, lw["w_k"].to(F64)).view(T, H, dh), cfg.rope_theta)
+        v = F.linear(x, lw["w_v"].to(F64)).view(T, H, dh)
+        a = F.scaled_dot_product_attention(q.transpose(0, 1), k.transpose(0, 1), v.transpose(0, 1), is_causal=True)
+        h = h + F.linear(a.transpose(0, 1).reshape(T, H * dh), lw["w_o"].to(F64))
+        x = F.rms_norm(h, (cfg.d_model,), lw["g_ffn"].to(F64), cfg.rms_eps)
+        h = h + F.linear(F.silu(F.linear(x, lw["w_gate"].to(F64))) * F.linear(x, lw["w_up"].to(F64)),
+                         lw["w_down"].to(F64))
+        out.append(h[-1].clone())
+    return out
+
+
+def test_p7_similarity_closed_forms():
+    g = torch.Generator().manual_seed(5)
+    a = torch.randn(6, 40, generator=g, dtype=F64)
+    b = torch.randn(6, 40, generator=g, dtype=F64)
+    torch.testing.assert_close(O.similarity_confidence(a, a), torch.ones(6, dtype=F64))
+    torch.testing.assert_close(O.similarity_confidence(a, -3.0 * a), -torch.ones(6, dtype=F64))
+    torch.testing.assert_close(O.similarity_confidence(a, b), F.cosine_similarity(a, b, dim=-1, eps=0.0))
+    torch.testing.assert_close(O.similarity_confidence(2.5 * a, 0.1 * b), O.similarity_confidence(a, b))   # scale free
+    e0, e1 = torch.zeros(1, 40, dtype=F64), torch.zeros(1, 40, dtype=F64)
+    e0[0, 3], e1[0, 7] = 2.0, 5.0
+    assert float(O.similarity_confidence(e0, e1)) == 0.0                       # orthogonal
+    e1[0, 3] = 5.0                                                             # 45 degrees
+    assert abs(float(O.similarity_confidence(e0, e1)) - math.sqrt(0.5)) < 1e-15
+    assert float(O.similarity_confidence(a, b).abs().max()) <= 1.0
+
+
+def test_p7_classifier_closed_forms():
+    cfg = small_cfg(dtype="fp32")
+    w = W.make_weights(cfg, seed=6)
+    m = O.model_from_config(cfg, w, conf_mode=3)
+    g = torch.Generator().manual_seed(6)
+    h = torch.randn(5, cfg.d_model, generator=g, dtype=F64)
+    for i in (1, cfg.n_layers):
+        want = torch.sigmoid(F.linear(h, w["w_cls"][i - 1:i].to(F64), w["b_cls"][i - 1:i].to(F64)))[:, 0]
+        torch.testing.assert_close(O.classifier_confidence(m, i, h), want)
+    # zero weights: the logistic function of the bias alone; a shift of the bias by ln 3 turns 1/2 into 3/4
+    w0 = dict(w, w_cls=torch.zeros_like(w["w_cls"]), b_cls=torch.tensor([0.0, math.log(3.0), -math.log(3.0)]))
+    m0 = O.model_from_config(cfg, w0, conf_mode=3)
+    assert torch.allclose(O.classifier_confidence(m0, 1, h), torch.full((5,), 0.5, dtype=F64))
+    assert torch.allclose(O.classifier_confidence(m0, 2, h), torch.full((5,), 0.75, dtype=F64))
+    assert torch.allclose(O.classifier_confidence(m0, 3, h), torch.full((5,), 0.25, dtype=F64))
+    # the unit of layer i is used at layer i (not another layer's): unit vector rows pick one channel
+    wu = torch.zeros_like(w["w_cls"])
+    for i in range(cfg.n_layers):
+        wu[i, i] = 1.0
+    mu = O.model_from_config(cfg, dict(w, w_cls=wu, b_cls=torch.zeros(cfg.n_layers)), conf_mode=3)
+    for i in range(1, cfg.n_layers + 1):
+        torch.testing.assert_close(O.classifier_confidence(mu, i, h), torch.sigmoid(h[:, i - 1]))
+
+
+@pytest.mark.parametrize("conf_mode", [2, 3])
+def test_p7_iteration_confidences_against_bruteforce(conf_mode):
+    """The confidences an iteration logs equal the measure applied to brute-force hidden states of the same
+    token history (never exiting: threshold 2), for every layer that has a check."""
+    cfg = small_cfg(n_layers=4, dtype="fp32", prompt_len=6, min_prompt_len=3)
+    w = W.make_weights(cfg, seed=7, gain_jitter=0.2)
+    m = O.model_from_config(cfg, w, conf_mode=conf_mode)
+    prompts, lens = W.make_prompts(cfg, seed=7), W.make_context_lens(cfg, seed=7)
+    cache = O.DenseKV(cfg.n_layers, cfg.batch, int(lens.max()) + 1, cfg.n_heads, cfg.head_dim, cfg.dtype)
+    tok = O.prefill(m, cache, prompts, lens)
+    tr = {}
+    out, e, L = O.decode_iteration(m, cache, tok, lens.long(), 2.0, trace=tr)
+    assert L == cfg.n_layers and bool((e == cfg.n_layers).all())
+    for b in range(cfg.batch):
+        hist = torch.cat([prompts[b, :int(lens[b])], tok[b:b + 1]])
+        hs = brute_hidden_states(cfg, w, hist)
+        for i in range(1, cfg.n_layers):          # checks after layers 1..n-1
+            if conf_mode == 2:
+                want = float(F.cosine_similarity(hs[i - 1], hs[i], dim=0, eps=0.0))
+            else:
+                want = float(torch.sigmoid(hs[i] @ w["w_cls"][i - 1].to(F64) + w["b_cls"][i - 1].to(F64)))
+            assert abs(float(tr["conf"][i - 1, b]) - want) < 1e-9, (b, i)
+        assert math.isnan(float(tr["conf"][cfg.n_layers - 1, b]))       # no check after the last layer
+
+
+@pytest.mark.parametrize("conf_mode", [2, 3])
+def test_p7_thresholds_that_always_and_never_fire(conf_mode):
+    cfg = small_cfg(n_layers=4, dtype="bf16")
+    w = W.make_weights(cfg, seed=8, gain_jitter=0.1)
+    prompts, lens = W.make_prompts(cfg, seed=8), W.make_context_lens(cfg, seed=8)
+    # cos <= 1 and a logistic value < 1: a threshold of 1 never fires -> the head-less full-layer pass
+    t1, e1, L1, c1 = run_oracle(cfg, w, prompts, lens, 3, 1.0, conf_mode=conf_mode)
+    t0, e0, L0, c0 = run_oracle(cfg, w, prompts, lens, 3, 0.5, heads=False)
+    assert torch.equal(t1, t0) and all(L == cfg.n_layers for L in L1)
+    for i in range(cfg.n_layers):
+        assert torch.equal(c1.K[i], c0.K[i]) and torch.equal(c1.V[i], c0.V[i])
+    # cos >= -1 and a logistic value > 0: a threshold of -1.5 fires at the first check for every sequence
+    t2, e2, L2, c2 = run_oracle(cfg, w, prompts, lens, 3, -1.5, conf_mode=conf_mode)
+    assert all(L == 1 for L in L2) and all(bool((e == 1).all()) for e in e2)
+    # ... which is the forced exit at layer 1 of the softmax-response run (same control path, same filling)
+    forced = [torch.ones(cfg.batch, dtype=torch.int32)] * 3
+    t3, e3, L3, c3 = run_oracle(cfg, w, prompts, lens, 3, 0.5, forced=forced, conf_mode=0)
+    assert torch.equal(t2, t3)
+    for i in range(cfg.n_layers):
+        assert torch.equal(c2.K[i], c3.K[i]) and torch.equal(c2.V[i], c3.V[i])
