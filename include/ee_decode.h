@@ -61,8 +61,14 @@ typedef struct ee_model_desc {
   float rope_theta;    /* rotary base; <= 0 disables the rotary embedding                         */
   int32_t exit_every;  /* exit head after layers i with i % exit_every == 0 and i < n_layers       */
   float logit_scale;   /* s: exit-head logits at layer i are multiplied by s * i                   */
-  int32_t conf_mode;   /* 0: largest softmax probability; 1: top-1 minus top-2 probability, the
-                          softmax-response measure of the paper's Section 2.1                      */
+  int32_t conf_mode;   /* confidence measure of the paper's Section 2.1.
+                          0: largest softmax probability of the exit head;
+                          1: top-1 minus top-2 probability (softmax response as the paper writes it);
+                          2: hidden states similarity, cos(h_{i-1}, h_i) of the hidden states before and
+                             after layer i (h_0 = the embedding), on the float residual stream;
+                          3: dedicated classifier, 1 / (1 + exp(-(w_cls[i] . h_i + b_cls[i]))).
+                          2 and 3 touch no LM head inside the layer loop (logit_scale is unused); the
+                          tokens then come from one LM-head pass over the hidden state at output_layer */
 } ee_model_desc;
 
 /* Weights of one decoder layer (all dev).  Plain shapes: g_attn,g_ffn [d]; w_qkv [3d][d] (q rows, then
@@ -79,6 +85,9 @@ typedef struct ee_model {
   const void* w_lm;               /* dev [vocab][d]; LM head (packed PLAIN for EE_BF16), shared by
                                      every exit head and by the final token selection              */
   const ee_layer_weights* layers; /* host array [n_layers]                                         */
+  const float* w_cls;             /* dev [n_layers][d] float, row i-1 = classifier of layer i; may be
+                                     NULL unless conf_mode == 3                                     */
+  const float* b_cls;             /* dev [n_layers] float, its biases; may be NULL unless conf_mode == 3 */
 } ee_model;
 
 /* Paged KV cache (the block-virtualised cache the paper inherits, Section 2.2 / 3.2).
@@ -141,7 +150,8 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
                         int32_t* out_tokens, int32_t* out_exit_layer, int32_t* out_batch_exit_layer,
                         float* out_conf, float* out_hidden, void* workspace, size_t workspace_bytes, void* stream);
 
-/* The exit check of one layer (Section 3.1 status rule with the softmax-response confidence of Section 2.1):
+/* The exit check of one layer (Section 3.1 status rule with the softmax-response confidence of Section 2.1;
+ * conf_mode 0 or 1 only: EE_ERR_UNSUPPORTED for the measures without an exit head, which need the layer loop):
  * z = (logit_scale * layer) * (RMSNorm(hidden; g_final) . W_lm^T); confidence per conf_mode; a sequence whose
  * status is 0 and whose confidence exceeds `threshold` gets status 1 and exit_layer = layer; statuses never
  * revert.  n_exited counts the sequences with status 1; done_flag is set to 1 (and batch_exit_layer to `layer`)

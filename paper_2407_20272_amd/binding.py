@@ -36,7 +36,7 @@ class ee_layer_weights(C.Structure):
 
 class ee_model(C.Structure):
     _fields_ = [("desc", ee_model_desc), ("embed", C.c_void_p), ("g_final", C.c_void_p), ("w_lm", C.c_void_p),
-                ("layers", C.POINTER(ee_layer_weights))]
+                ("layers", C.POINTER(ee_layer_weights)), ("w_cls", C.c_void_p), ("b_cls", C.c_void_p)]
 
 
 class ee_kv_cache(C.Structure):
@@ -179,7 +179,12 @@ class DeviceModel:
             L.w_gate_up = mat(gu, EE_PACK_GATE_UP, cfg.d_ffn).data_ptr()
             L.w_down = mat(lw["w_down"]).data_ptr()
             del qkv, gu
-        self.c = ee_model(self.desc, self.embed.data_ptr(), self.g_final.data_ptr(), self.w_lm.data_ptr(), self.layers)
+        # dedicated-classifier rows and biases (float32 in every dtype), if the weight set has them
+        self.w_cls = dev(weights["w_cls"].float()) if "w_cls" in weights else None
+        self.b_cls = dev(weights["b_cls"].float()) if "b_cls" in weights else None
+        self.c = ee_model(self.desc, self.embed.data_ptr(), self.g_final.data_ptr(), self.w_lm.data_ptr(), self.layers,
+                          self.w_cls.data_ptr() if self.w_cls is not None else None,
+                          self.b_cls.data_ptr() if self.b_cls is not None else None)
         torch.cuda.synchronize()
 
 

@@ -90,6 +90,9 @@ struct Workspace {
   int32_t* tile_cnt;  // [(d/32) * Mpad/32] arrival counters of the accumulate epilogue (directly behind rowsq)
   size_t zero_count;  // floats from rowsq on that must be zero when an iteration starts
   bf16_t* fill_x;     // [n][Mpad][d]
+  float* dots;        // [n][Mpad] per-layer row dot products of the head-less confidence measures (zeroed with rowsq)
+  float* hprev;       // bf16: [d][Mpad], fp32: [B][d]: hidden state before the current layer (similarity measure)
+  float* msr;         // fp32: [3][B] sums of the head-less confidence measures
   // fp32 path
   float *h, *x, *ao, *act, *logits;
   size_t bytes;
@@ -115,10 +118,12 @@ Workspace carve(const ee_model_desc& D, int B, void* base) {
     w.xT = w.xH ? w.xH + d * Mpad : nullptr;
     w.aoT = c.take<bf16_t>(d * Mpad);
     w.actT = c.take<bf16_t>(f * Mpad);
-    w.zero_count = (2 * n + 2) * Mpad + (d / 32) * (Mpad / 32);
+    w.zero_count = (2 * n + 2) * Mpad + (d / 32) * (Mpad / 32) + n * Mpad;
     w.rowsq = c.take<float>(w.zero_count);
     w.tile_cnt = reinterpret_cast<int32_t*>(w.rowsq ? w.rowsq + (2 * n + 2) * Mpad : nullptr);
+    w.dots = w.rowsq ? w.rowsq + (2 * n + 2) * Mpad + (d / 32) * (Mpad / 32) : nullptr;
     w.fill_x = c.take<bf16_t>(n * Mpad * d);
+    w.hprev = c.take<float>(d * Mpad);
   } else {
     w.partials = c.take<float4>(Bp);
     w.h = c.take<float>(Bp * d);
@@ -126,6 +131,8 @@ Workspace carve(const ee_model_desc& D, int B, void* base) {
     w.ao = c.take<float>(Bp * d);
     w.act = c.take<float>(Bp * f);
     w.logits = c.take<float>(Bp * V);
+    w.hprev = c.take<float>(Bp * d);
+    w.msr = c.take<float>(3 * Bp);
   }
   w.bytes = (c.off + 255) & ~(size_t)255;
   return w;
@@ -141,7 +148,7 @@ int check_desc(const ee_model_desc* D) {
     EE_FAIL(EE_ERR_SHAPE, "d_model %d != n_heads %d * head_dim %d", D->d_model, D->n_heads, D->head_dim);
   if (D->head_dim != 64 && D->head_dim != 128) EE_FAIL(EE_ERR_UNSUPPORTED, "head_dim %d: only 64 and 128", D->head_dim);
   if (D->exit_every < 1) EE_FAIL(EE_ERR_INVALID_ARG, "exit_every must be >= 1");
-  if (D->conf_mode != 0 && D->conf_mode != 1) EE_FAIL(EE_ERR_INVALID_ARG, "conf_mode must be 0 or 1");
+  if (D->conf_mode < 0 || D->conf_mode > 3) EE_FAIL(EE_ERR_INVALID_ARG, "conf_mode must be 0, 1, 2 or 3");
   if (!(D->logit_scale >= 0.0f)) EE_FAIL(EE_ERR_INVALID_ARG, "logit_scale must be >= 0");
   if (!(D->rms_eps >= 0.0f)) EE_FAIL(EE_ERR_INVALID_ARG, "rms_eps must be >= 0");
   if (D->vocab % 2) EE_FAIL(EE_ERR_UNSUPPORTED, "vocab must be even");
@@ -382,6 +389,12 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   if (use_exit_heads && !thresholds) EE_FAIL(EE_ERR_INVALID_ARG, "thresholds is NULL");
   if (!out_tokens || !out_exit_layer || !out_batch_exit_layer) EE_FAIL(EE_ERR_INVALID_ARG, "an output pointer is NULL");
   if ((rc = check_workspace(D, B, workspace, workspace_bytes))) return rc;
+  // Confidence measures that need no LM head (Section 2.1): 2 = similarity of consecutive hidden states,
+  // 3 = dedicated classifier.  Both are one dot product per row, taken while the next operand is prepared.
+  const bool dotmode = use_exit_heads && D.conf_mode >= 2;
+  const bool simmode = use_exit_heads && D.conf_mode == 2;
+  if (use_exit_heads && D.conf_mode == 3 && (!model->w_cls || !model->b_cls))
+    EE_FAIL(EE_ERR_INVALID_ARG, "conf_mode 3 needs the classifier weights w_cls and b_cls");
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const Workspace w = carve(D, B, workspace);
   const int Mpad = round_up(B, 32);
@@ -404,6 +417,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       launch_rowsq(w.hT, rs(0), Mpad, d, always, st);
     } else {
       launch_embed_f32(reinterpret_cast<const float*>(model->embed), batch->tokens, w.h, B, d, st);
+      if (simmode) launch_copy_f32(w.h, w.hprev, (size_t)B * d, st);   // h_0, the "previous" state of layer 1
     }
   }
 
@@ -417,7 +431,11 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     if (bf) {
       if (i == 1) {
         ProfScope ps(EE_K_NORM, i, st);
-        launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_attn), w.xT, rs(0), D.rms_eps, Mpad, d, run_layers, st);
+        if (simmode)   // also keeps h_0 as the "previous" hidden state of layer 1
+          launch_prep_x_dot(w.hT, reinterpret_cast<const bf16_t*>(L.g_attn), w.xT, rs(0), nullptr, 0, D.rms_eps, Mpad, d,
+                            RowDot{nullptr, w.hprev, nullptr, 0}, run_layers, st);
+        else
+          launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_attn), w.xT, rs(0), D.rms_eps, Mpad, d, run_layers, st);
       }
       {
         ProfScope ps(EE_K_QKV, i, st);
@@ -452,11 +470,21 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       if (i < n) {   // operand of the next layer's attention (and of this layer's exit head, in the same launch)
         ProfScope ps(EE_K_NORM, i, st);
         const bf16_t* g_next = reinterpret_cast<const bf16_t*>(model->layers[i].g_attn);
-        if (head_here)
+        if (head_here && !dotmode) {
           launch_prep_x_pair(w.hT, reinterpret_cast<const bf16_t*>(model->g_final), g_next, w.xH, rs(2 * i), D.rms_eps, Mpad, d,
                              run_layers, st);
-        else
+        } else if (simmode) {
+          // h_{i-1} . h_i where a check follows; the snapshot moves on after every layer
+          float* dots = head_here ? w.dots + (size_t)(i - 1) * Mpad : nullptr;
+          launch_prep_x_dot(w.hT, g_next, w.xT, rs(2 * i), nullptr, 0, D.rms_eps, Mpad, d,
+                            RowDot{dots ? w.hprev : nullptr, w.hprev, dots, 1}, run_layers, st);
+        } else if (head_here && dotmode) {
+          launch_prep_x_dot(w.hT, g_next, w.xT, rs(2 * i), nullptr, 0, D.rms_eps, Mpad, d,
+                            RowDot{model->w_cls + (size_t)(i - 1) * d, nullptr, w.dots + (size_t)(i - 1) * Mpad, 0},
+                            run_layers, st);
+        } else {
           launch_prep_x(w.hT, g_next, w.xT, rs(2 * i), D.rms_eps, Mpad, d, run_layers, st);
+        }
       }
     } else {
       {
@@ -488,7 +516,32 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
         launch_simple_acc(gd, AccEpi{w.h, 0, d, nullptr, nullptr}, run_layers, st);
       }
     }
-    if (head_here) {
+    if (!bf && simmode && !head_here && i < n) launch_copy_f32(w.h, w.hprev, (size_t)B * d, st);
+    if (head_here && dotmode) {
+      DecideArgs da{};
+      if (bf) {
+        da.dots = w.dots + (size_t)(i - 1) * Mpad;
+        da.sq_a = rs(2 * i - 2);
+        da.sq_b = rs(2 * i);
+      } else {
+        ProfScope ps(EE_K_HEAD, i, st);
+        float* other = simmode ? w.hprev : const_cast<float*>(model->w_cls) + (size_t)(i - 1) * d;
+        launch_measure_f32(w.h, other, simmode ? 1 : 0, w.msr, B, d, run_layers, st);
+        da.dots = w.msr;
+        da.sq_a = w.msr + B;
+        da.sq_b = w.msr + 2 * (size_t)B;
+      }
+      da.bias = D.conf_mode == 3 ? model->b_cls + (i - 1) : nullptr;
+      da.B = B;
+      da.layer = i;
+      da.threshold = thresholds[i - 1];
+      da.conf_mode = D.conf_mode;
+      da.forced_exit_layer = forced_exit_layer;
+      da.s = s;
+      da.conf_out = out_conf ? out_conf + (size_t)(i - 1) * B : nullptr;
+      ProfScope ps(EE_K_COMBINE, i, st);
+      launch_decide(da, run_layers, st);
+    } else if (head_here) {
       const float scale = D.logit_scale * (float)i;
       if (bf)
         enqueue_head_bf16(*model, w, B, Mpad, scale, rs(2 * i), i, true, run_layers, st);
@@ -511,14 +564,25 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
 
   // Algorithm 1, transform_to_tokens.  When the batch left at an exit head, that head's arg max over the same
   // hidden state already is the token; the LM head is only streamed again when the loop ran to the last layer.
+  // With a head-less confidence measure no exit head has produced a token: the LM head then always runs, on the
+  // hidden state at output_layer (still in place: later layers were skipped), normalised with that layer's sums.
   {
-    if (bf)
+    const Pred final_pred = dotmode ? always : run_layers;
+    if (bf && dotmode) {
+      {
+        ProfScope ps(EE_K_NORM, n, st);
+        launch_prep_x_dot(w.hT, reinterpret_cast<const bf16_t*>(model->g_final), w.xH, rs(0), out_batch_exit_layer,
+                          (size_t)2 * Mpad, D.rms_eps, Mpad, d, RowDot{}, always, st);
+      }
+      enqueue_head_bf16(*model, w, B, Mpad, 0.0f, nullptr, n, true, always, st);
+    } else if (bf) {
       enqueue_head_bf16(*model, w, B, Mpad, 0.0f, rs(2 * n), n, false, run_layers, st);
-    else
-      enqueue_head_f32(*model, w, w.h, B, 0.0f, n, run_layers, st);
+    } else {
+      enqueue_head_f32(*model, w, w.h, B, 0.0f, n, final_pred, st);
+    }
     CombineArgs ca{w.partials, bf ? D.vocab / 32 : 1, B, 0, 0.0f, 0.0f, 0, nullptr, s, out_tokens, nullptr};
     ProfScope ps(EE_K_COMBINE, n, st);
-    launch_combine(ca, run_layers, st);
+    launch_combine(ca, final_pred, st);
   }
   if (out_hidden) {
     if (bf)
@@ -541,6 +605,9 @@ int ee_exit_check(const ee_model* model, int32_t layer, const float* hidden, int
   if (batch < 0) EE_FAIL(EE_ERR_INVALID_ARG, "batch size %d is negative", batch);
   if (batch == 0) return EE_OK;
   if (layer < 1 || layer > D.n_layers) EE_FAIL(EE_ERR_INVALID_ARG, "layer %d outside 1..%d", layer, D.n_layers);
+  if (D.conf_mode >= 2)
+    EE_FAIL(EE_ERR_UNSUPPORTED, "ee_exit_check: conf_mode %d has no exit head; it only runs inside ee_decode_iteration",
+            D.conf_mode);
   if (!hidden || !status || !exit_layer || !n_exited || !done_flag || !batch_exit_layer)
     EE_FAIL(EE_ERR_INVALID_ARG, "ee_exit_check: NULL pointer");
   if ((rc = check_workspace(D, batch, workspace, workspace_bytes))) return rc;

@@ -137,7 +137,24 @@ void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gai
 void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
                           size_t rowsq_layer_stride, float eps, const int32_t* fill_from, int fill_from_stride, int B,
                           int Mpad, int d, Pred pred, hipStream_t st);
+// Optional second job of an operand preparation (confidence measures that need no LM head, Section 2.1):
+// dots[m] += sum_k h[m][k] * other, where other is the previous hidden state (per_row: HT layout, the
+// similarity measure) or one weight row shared by all rows ([d], the dedicated classifier); snapshot, if set,
+// receives h in HT layout (it may be the buffer `other` points to: every element is read before it is written).
+struct RowDot {
+  const float* other;
+  float* snapshot;
+  float* dots;      // [Mpad], zero before the launch
+  int per_row;
+};
+// Like launch_prep_x, with the second job above, and with the row sums taken from slot *slot_ptr of a table
+// (rowsq + *slot_ptr * slot_stride) when slot_ptr is set.
+void launch_prep_x_dot(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, const int32_t* slot_ptr,
+                       size_t slot_stride, float eps, int Mpad, int d, const RowDot& rd, Pred pred, hipStream_t st);
 void launch_rmsnorm_f32(const float* h, const float* gain, float* x, int B, int d, float eps, Pred pred, hipStream_t st);
+// fp32 path: out[0][m] = h[m] . other, out[1][m] = |other|^2, out[2][m] = |h[m]|^2 (out is [3][B]); other is
+// the previous hidden state [B][d] (per_row) or one row [d]; with per_row, h is then copied over other.
+void launch_measure_f32(const float* h, float* other, int per_row, float* out, int B, int d, Pred pred, hipStream_t st);
 void launch_head_stats_f32(const float* logits, float4* partials, int B, int vocab, float scale, Pred pred,
                            hipStream_t st);
 struct CombineArgs {
@@ -154,6 +171,22 @@ struct CombineArgs {
   float* conf_out;      // [B] or nullptr
 };
 void launch_combine(const CombineArgs& a, Pred pred, hipStream_t st);
+// Exit decision from a measure that is one dot product per row (conf_mode 2: cosine of consecutive hidden
+// states = dots / sqrt(sq_a * sq_b); conf_mode 3: logistic function of dots + bias[0]).
+struct DecideArgs {
+  const float* dots;   // [B]
+  const float* sq_a;   // [B] squared norms (conf_mode 2)
+  const float* sq_b;
+  const float* bias;   // device, this layer's bias (conf_mode 3)
+  int B;
+  int layer;
+  float threshold;
+  int conf_mode;
+  const int32_t* forced_exit_layer;
+  IterState s;
+  float* conf_out;
+};
+void launch_decide(const DecideArgs& a, Pred pred, hipStream_t st);
 
 // pack.hip
 void launch_pack_weight(const bf16_t* w, int n_out, int n_in, int pair_stride, bf16_t* packed, hipStream_t st);

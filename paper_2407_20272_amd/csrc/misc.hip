@@ -101,8 +101,8 @@ __global__ __launch_bounds__(256) void rowsq_kernel(const float* hT, float* rows
 
 __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable gains, const bf16_t* gain0, bf16_t* xT,
                                                      size_t slab_elems, const float* rowsq, size_t rowsq_layer_stride,
-                                                     float eps, const int32_t* fill_from, int fill_from_stride, int B,
-                                                     int Mpad, int d, Pred pred) {
+                                                     const int32_t* slot_ptr, float eps, const int32_t* fill_from,
+                                                     int fill_from_stride, int B, int Mpad, int d, RowDot rd, Pred pred) {
   if (pred_skip(pred)) return;
   const int z = blockIdx.z;
   const int ml = threadIdx.x & 31, cl = threadIdx.x >> 5;
@@ -124,9 +124,9 @@ __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable 
   const bf16_t* gain = gains.g[z] ? reinterpret_cast<const bf16_t*>(gains.g[z]) : gain0;
   const int c = blockIdx.x * 8 + cl;  // 8-channel chunk
   const int k0 = c * 8;
-  // KV filling inside a decode iteration: the sums of the exit hidden state were left by the down projection of the
-  // batch exit layer L (= fill_from[0]) in slot 2L of the per-iteration table
-  if (rowsq_layer_stride) rowsq += (size_t)fill_from[0] * rowsq_layer_stride;
+  // Hidden state of the batch exit layer L (KV filling and the final token inside a decode iteration): its sums
+  // were left by the down projection of layer L in slot 2L of the per-iteration table; *slot_ptr = L
+  if (rowsq_layer_stride) rowsq += (size_t)slot_ptr[0] * rowsq_layer_stride;
   const float rq = rowsq[m];
   float hv[8];
 #pragma unroll
@@ -137,6 +137,58 @@ __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable 
 #pragma unroll
   for (int i = 0; i < 8; ++i) out[i] = (bf16_t)(hv[i] * r * (float)gv[i]);
   *reinterpret_cast<bf16x8*>(xT + (size_t)z * slab_elems + xt_index(m, k0, d)) = out;
+  if (z != 0) return;
+  // second job (uniform over the launch): dot product of every row with the previous hidden state or a weight
+  // row, and the snapshot that becomes the next layer's "previous hidden state"
+  if (rd.dots) {
+    float acc = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float o = rd.per_row ? rd.other[ht_index(m, k0 + i, Mpad)] : rd.other[k0 + i];
+      acc = fmaf(hv[i], o, acc);
+    }
+    __shared__ float part[8][32];
+    part[cl][ml] = acc;
+    __syncthreads();
+    if (cl == 0) {
+      float t = 0.0f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) t += part[j][ml];
+      unsafeAtomicAdd(rd.dots + m, t);
+    }
+  }
+  if (rd.snapshot) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) rd.snapshot[ht_index(m, k0 + i, Mpad)] = hv[i];
+  }
+}
+
+// fp32 path: the three sums a one-dot-product confidence measure needs, one workgroup per row.
+__global__ __launch_bounds__(256) void measure_f32_kernel(const float* h, float* other, int per_row, float* out, int B,
+                                                          int d, Pred pred) {
+  if (pred_skip(pred)) return;
+  const int m = blockIdx.x;
+  const float* hp = h + (size_t)m * d;
+  float* op = per_row ? other + (size_t)m * d : other;
+  float dot = 0.0f, so = 0.0f, sh = 0.0f;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) {
+    const float a = hp[k], b = op[k];
+    dot = fmaf(a, b, dot);
+    so = fmaf(b, b, so);
+    sh = fmaf(a, a, sh);
+    if (per_row) op[k] = a;   // this hidden state is the next layer's previous one
+  }
+  __shared__ float red[3][256];
+  red[0][threadIdx.x] = dot;
+  red[1][threadIdx.x] = so;
+  red[2][threadIdx.x] = sh;
+  __syncthreads();
+  for (int s = 128; s > 0; s >>= 1) {
+    if (threadIdx.x < s)
+      for (int j = 0; j < 3; ++j) red[j][threadIdx.x] += red[j][threadIdx.x + s];
+    __syncthreads();
+  }
+  if (threadIdx.x < 3) out[(size_t)threadIdx.x * B + m] = red[threadIdx.x][0];
 }
 
 // fp32 path: plain RMSNorm, one workgroup per row.
@@ -181,6 +233,26 @@ __global__ __launch_bounds__(256) void head_stats_f32_kernel(const float* logits
 // apply the sticky status rule, count accepted sequences and raise the all-exited flag.  One workgroup per row.
 // layer == 0: final token selection only.
 // ---------------------------------------------------------------------------------------------------
+// Section 3.1 status rule for one sequence: an accepted sequence stays accepted (and is not re-checked);
+// otherwise the confidence (or the forced exit layer) decides; the last acceptance of the batch raises `done`.
+__device__ inline void decide_row(const IterState& s, int m, int B, int layer, float conf, float threshold,
+                                  const int32_t* forced_exit_layer, float* conf_out) {
+  if (s.status[m] != 0) {
+    if (conf_out) conf_out[m] = __builtin_nanf("");
+    return;
+  }
+  if (conf_out) conf_out[m] = conf;
+  const bool accepted = forced_exit_layer ? (layer >= forced_exit_layer[m]) : (conf > threshold);
+  if (!accepted) return;
+  s.status[m] = 1;
+  s.exit_layer[m] = layer;
+  const int before = atomicAdd(s.n_exited, 1);
+  if (before + 1 == B) {
+    *s.batch_exit_layer = layer;
+    *s.done = 1;
+  }
+}
+
 __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, Pred pred) {
   if (pred_skip(pred)) return;
   const int m = blockIdx.x;
@@ -201,20 +273,21 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, Pred pred) 
   if (a.layer == 0) return;
   float conf = 1.0f / s.sum;                                          // largest softmax probability
   if (a.conf_mode == 1) conf = (1.0f - expf(a.scale * (s.z2 - s.zmax))) / s.sum;  // top-1 minus top-2
-  if (a.s.status[m] != 0) {                                           // already accepted: stays accepted
-    if (a.conf_out) a.conf_out[m] = __builtin_nanf("");
-    return;
+  decide_row(a.s, m, a.B, a.layer, conf, a.threshold, a.forced_exit_layer, a.conf_out);
+}
+
+// One thread per row: confidence from one dot product (hidden states similarity, dedicated classifier).
+__global__ __launch_bounds__(256) void decide_kernel(DecideArgs a, Pred pred) {
+  if (pred_skip(pred)) return;
+  const int m = blockIdx.x * blockDim.x + threadIdx.x;
+  if (m >= a.B) return;
+  float conf;
+  if (a.conf_mode == 2) {
+    conf = a.dots[m] / (sqrtf(a.sq_a[m]) * sqrtf(a.sq_b[m]));
+  } else {
+    conf = 1.0f / (1.0f + expf(-(a.dots[m] + a.bias[0])));
   }
-  if (a.conf_out) a.conf_out[m] = conf;
-  const bool accepted = a.forced_exit_layer ? (a.layer >= a.forced_exit_layer[m]) : (conf > a.threshold);
-  if (!accepted) return;
-  a.s.status[m] = 1;
-  a.s.exit_layer[m] = a.layer;
-  const int before = atomicAdd(a.s.n_exited, 1);
-  if (before + 1 == a.B) {
-    *a.s.batch_exit_layer = a.layer;
-    *a.s.done = 1;
-  }
+  decide_row(a.s, m, a.B, a.layer, conf, a.threshold, a.forced_exit_layer, a.conf_out);
 }
 
 }  // namespace
@@ -257,8 +330,14 @@ void launch_rowsq(const float* hT, float* rowsq, int Mpad, int d, Pred pred, hip
 void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, float eps, int Mpad, int d,
                    Pred pred, hipStream_t st) {
   GainTable none{};
-  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 1), dim3(256), 0, st, hT, none, gain, xT, (size_t)0, rowsq, (size_t)0, eps,
-                     (const int32_t*)nullptr, 0, 0, Mpad, d, pred);
+  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 1), dim3(256), 0, st, hT, none, gain, xT, (size_t)0, rowsq, (size_t)0,
+                     (const int32_t*)nullptr, eps, (const int32_t*)nullptr, 0, 0, Mpad, d, RowDot{}, pred);
+}
+void launch_prep_x_dot(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, const int32_t* slot_ptr,
+                       size_t slot_stride, float eps, int Mpad, int d, const RowDot& rd, Pred pred, hipStream_t st) {
+  GainTable none{};
+  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 1), dim3(256), 0, st, hT, none, gain, xT, (size_t)0, rowsq,
+                     slot_ptr ? slot_stride : (size_t)0, slot_ptr, eps, (const int32_t*)nullptr, 0, 0, Mpad, d, rd, pred);
 }
 void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT_pair, const float* rowsq,
                         float eps, int Mpad, int d, Pred pred, hipStream_t st) {
@@ -266,14 +345,15 @@ void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gai
   two.g[0] = gain_a;
   two.g[1] = gain_b;
   hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 2), dim3(256), 0, st, hT, two, (const bf16_t*)nullptr, xT_pair,
-                     (size_t)Mpad * d, rowsq, (size_t)0, eps, (const int32_t*)nullptr, 0, 0, Mpad, d, pred);
+                     (size_t)Mpad * d, rowsq, (size_t)0, (const int32_t*)nullptr, eps, (const int32_t*)nullptr, 0, 0, Mpad, d,
+                     RowDot{}, pred);
 }
 void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
                           size_t rowsq_layer_stride, float eps, const int32_t* fill_from, int fill_from_stride, int B,
                           int Mpad, int d, Pred pred, hipStream_t st) {
   hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, n_layers), dim3(256), 0, st, hT, gains,
-                     (const bf16_t*)nullptr, xT_slabs, (size_t)Mpad * d, rowsq, rowsq_layer_stride, eps, fill_from,
-                     fill_from_stride, B, Mpad, d, pred);
+                     (const bf16_t*)nullptr, xT_slabs, (size_t)Mpad * d, rowsq, rowsq_layer_stride, fill_from, eps, fill_from,
+                     fill_from_stride, B, Mpad, d, RowDot{}, pred);
 }
 void launch_rmsnorm_f32(const float* h, const float* gain, float* x, int B, int d, float eps, Pred pred, hipStream_t st) {
   hipLaunchKernelGGL(rmsnorm_f32_kernel, dim3(B), dim3(256), 0, st, h, gain, x, d, eps, pred);
@@ -281,6 +361,12 @@ void launch_rmsnorm_f32(const float* h, const float* gain, float* x, int B, int 
 void launch_head_stats_f32(const float* logits, float4* partials, int B, int vocab, float scale, Pred pred,
                            hipStream_t st) {
   hipLaunchKernelGGL(head_stats_f32_kernel, dim3(B), dim3(256), 0, st, logits, partials, vocab, scale, pred);
+}
+void launch_measure_f32(const float* h, float* other, int per_row, float* out, int B, int d, Pred pred, hipStream_t st) {
+  hipLaunchKernelGGL(measure_f32_kernel, dim3(B), dim3(256), 0, st, h, other, per_row, out, B, d, pred);
+}
+void launch_decide(const DecideArgs& a, Pred pred, hipStream_t st) {
+  hipLaunchKernelGGL(decide_kernel, dim3((a.B + 255) / 256), dim3(256), 0, st, a, pred);
 }
 void launch_combine(const CombineArgs& a, Pred pred, hipStream_t st) {
   hipLaunchKernelGGL(combine_kernel, dim3(a.B), dim3(256), 0, st, a, pred);

@@ -52,7 +52,8 @@ def test_workspace_sizes():
     (dict(dtype=7), B.EE_ERR_INVALID_ARG),
     (dict(d_model=260), B.EE_ERR_SHAPE),
     (dict(exit_every=0), B.EE_ERR_INVALID_ARG),
-    (dict(conf_mode=2), B.EE_ERR_INVALID_ARG),
+    (dict(conf_mode=4), B.EE_ERR_INVALID_ARG),
+    (dict(conf_mode=-1), B.EE_ERR_INVALID_ARG),
     (dict(logit_scale=-1.0), B.EE_ERR_INVALID_ARG),
 ])
 def test_bad_descriptions_are_rejected(bad, code):
@@ -94,6 +95,11 @@ def test_bad_arguments_are_rejected_before_any_launch():
     bad_layers = (B.ee_layer_weights * 4)(*[B.ee_layer_weights(1, 1, None, 1, 1, 1) for _ in range(4)])
     assert call(model=B.ee_model(d, 1, 1, 1, bad_layers)) == B.EE_ERR_INVALID_ARG
     assert "layer 1" in B.ee_last_error()
+    # measures without an exit head: the classifier needs its weights; the stand-alone check has no head to run
+    assert call(model=B.ee_model(desc(conf_mode=3), 1, 1, 1, layers, None, None)) == B.EE_ERR_INVALID_ARG
+    assert "w_cls" in B.ee_last_error()
+    m2 = B.ee_model(desc(conf_mode=2), 1, 1, 1, layers)
+    assert L.ee_exit_check(C.byref(m2), 1, 1, 2, 0.5, None, 1, 1, 1, 1, 1, None, None, 256, 1 << 30, None) == B.EE_ERR_UNSUPPORTED
     # the other entry points validate the same way
     assert L.ee_exit_check(C.byref(model), 9, 1, 2, 0.5, None, 1, 1, 1, 1, 1, None, None, 256, 1 << 30, None) == B.EE_ERR_INVALID_ARG
     assert L.ee_exit_check(C.byref(model), 1, None, 2, 0.5, None, 1, 1, 1, 1, 1, None, None, 256, 1 << 30, None) == B.EE_ERR_INVALID_ARG

@@ -132,3 +132,43 @@ def test_empty_batch_is_a_noop():
     tok, e, L, conf, hid = run.step(torch.zeros(0, dtype=torch.int32), torch.zeros(0, dtype=torch.long), 0.5,
                                     rows=[])
     assert tok.numel() == 0 and e.numel() == 0
+
+
+# ------------------------------------------------------------------------------------------------
+# confidence measures without an exit head (Section 2.1): hidden states similarity (2), dedicated classifier (3)
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("conf_mode,threshold", [(2, 0.65), (3, 0.6)])
+def test_fp32_headless_measures_lockstep(conf_mode, threshold):
+    cfg = TINY.with_(decode_steps=4, n_layers=6, conf_mode=conf_mode, threshold=threshold)
+    stats = lockstep(cfg, seed=31, steps=4)
+    assert stats["near_threshold"] == 0 and stats["near_tie"] == 0
+    assert min(stats["L"]) < cfg.n_layers, stats["L"]          # the batch did leave early at least once
+
+
+@pytest.mark.parametrize("batch", [7, 40])
+@pytest.mark.parametrize("conf_mode,threshold", [(2, 0.78), (3, 0.5)])
+def test_bf16_headless_measures_lockstep(conf_mode, threshold, batch):
+    cfg = small_bf16(n_layers=6, batch=batch, prompt_len=12, min_prompt_len=4, shuffled_blocks=True,
+                     conf_mode=conf_mode, threshold=threshold)
+    stats = lockstep(cfg, seed=32, steps=5)
+    total = stats["decisions"] + stats["tokens"]
+    assert stats["near_threshold"] + stats["near_tie"] <= max(2, total // 20), stats
+    assert stats["max_conf_err"] < 2e-2
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_similarity_with_checks_every_second_layer(dtype):
+    """The previous hidden state is the one before layer i also where layer i-1 had no check."""
+    base = TINY.with_(decode_steps=3) if dtype == "fp32" else small_bf16(batch=9)
+    cfg = base.with_(n_layers=7, exit_every=2, conf_mode=2, threshold=0.7)
+    lockstep(cfg, seed=33, steps=3)
+
+
+@pytest.mark.parametrize("conf_mode", [2, 3])
+def test_headless_measures_forced_exits(conf_mode):
+    cfg = small_bf16(n_layers=6, conf_mode=conf_mode)
+    g = torch.Generator().manual_seed(11)
+    forced = torch.randint(1, cfg.n_layers + 1, (3, cfg.batch), generator=g, dtype=torch.int32)
+    forced[1] = 1
+    stats = lockstep(cfg, seed=34, steps=3, forced_seq=forced)
+    assert stats["L"] == [int(forced[s].max()) for s in range(3)]
