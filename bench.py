@@ -39,6 +39,12 @@ def algorithmic_bytes(cfg, cls, mean_ctx_plus1):
     }.get(cls)
 
 
+# Thresholds of the two measures that need no LM head.  The weights are random, so no value is "right": these are
+# set where the batch leaves around the middle of the model (see the exit-layer histograms in the output).
+SIM_THRESHOLD = {1: 0.967}
+CLS_THRESHOLD = {1: 0.5}
+
+
 def traffic_ratios():
     """Measured HBM bytes per algorithmic byte of each kernel class, from the committed rocprofv3 --pmc summary
     (FETCH_SIZE + WRITE_SIZE, calibrated against a plain copy of known size)."""
@@ -64,7 +70,11 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; invalidates the result)")
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--modes", default="ee,full,never")
+    ap.add_argument("--modes", default="ee,full,never",
+                    help="ee: the config's softmax-response heads; full: no heads; never: heads that never fire; "
+                         "sim / cls: hidden-state-similarity / dedicated-classifier checks (no LM head in the loop)")
+    ap.add_argument("--sim-threshold", type=float, default=0.0, help="threshold of mode sim (0: a built-in per-config value)")
+    ap.add_argument("--cls-threshold", type=float, default=0.0, help="threshold of mode cls (0: a built-in per-config value)")
     ap.add_argument("--synthetic-kv", action="store_true",
                     help="fill the cache with seeded random K/V instead of prefilling through the decode step "
                          "(always used when prompt lengths are ragged)")
@@ -158,14 +168,20 @@ def main():
     oneB = torch.ones(Bsz, dtype=torch.int32, device="cuda")
     L_last = torch.zeros(P + 1, dtype=torch.int32, device="cuda")
 
+    variants = {"sim": model.with_conf_mode(2), "cls": model.with_conf_mode(3)}
+    thr_of = {"ee": cfg.threshold, "full": 2.0, "never": 2.0,
+              "sim": args.sim_threshold or SIM_THRESHOLD.get(args.config, 0.99),
+              "cls": args.cls_threshold or CLS_THRESHOLD.get(args.config, 0.9)}
+
     def iteration(mode):
-        thr = {"ee": cfg.threshold, "full": 2.0, "never": 2.0}[mode]
+        thr = thr_of[mode]
         f = None
-        if forced_all is not None and mode == "ee":
+        if forced_all is not None and mode != "full" and mode != "never":
             torch.index_select(forced_all, 0, step_no % forced_all.shape[0], out=forced_cur.view(1, -1))
             step_no.add_(1)
             f = forced_cur
-        B.ee_decode_iteration(model, cache, batch, thr, f, mode != "full", out_tok, out_exit, out_L, None, None, ws)
+        B.ee_decode_iteration(variants.get(mode, model), cache, batch, thr, f, mode != "full", out_tok, out_exit, out_L,
+                              None, None, ws)
         L_hist.scatter_add_(0, out_L.long(), one1)
         E_hist.scatter_add_(0, out_exit.long(), oneB)
         torch.add(out_tok, 0, out=tokens)          # next iteration consumes the tokens just produced
@@ -227,6 +243,9 @@ def main():
                     # kernels of layers above the batch exit layer return at once; KV filling only runs after an
                     # early exit; the final LM pass (recorded at layer n) only when the loop reached layer n
                     executed = (Lp[it] < n) if cls == "kv_fill" else (layer == 0 or layer <= Lp[it])
+                    # measures without an exit head: the one LM-head pass for the tokens (recorded at layer n) always runs
+                    if mode in ("sim", "cls") and layer == n and cls in ("head", "norm", "combine"):
+                        executed = True
                     if executed:
                         agg[cls][0] += 1
                         agg[cls][1] += ms

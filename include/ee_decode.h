@@ -66,7 +66,8 @@ typedef struct ee_model_desc {
                           1: top-1 minus top-2 probability (softmax response as the paper writes it);
                           2: hidden states similarity, cos(h_{i-1}, h_i) of the hidden states before and
                              after layer i (h_0 = the embedding), on the float residual stream;
-                          3: dedicated classifier, 1 / (1 + exp(-(w_cls[i] . h_i + b_cls[i]))).
+                          3: dedicated classifier, 1 / (1 + exp(-(w_cls[i] . x_i + b_cls[i]))) with
+                             x_i = h_i / sqrt(mean(h_i^2) + rms_eps), the hidden state at unit root mean square.
                           2 and 3 touch no LM head inside the layer loop (logit_scale is unused); the
                           tokens then come from one LM-head pass over the hidden state at output_layer */
 } ee_model_desc;

@@ -27,8 +27,11 @@ Readings taken where the paper is silent or inconsistent (each also listed in th
     top-2 softmax probability (Section 2.1, softmax response).  Strict '>' against the threshold.
   * confidence mode 2 = cos(h_{i-1}, h_i) (Section 2.1, hidden states similarity): the hidden states
     after layers i-1 and i, h_0 being the embedding; taken on the float residual stream.
-  * confidence mode 3 = M(h_i) (Section 2.1, dedicated classifier), read as one linear unit per layer
-    on the hidden state followed by the logistic function: 1 / (1 + exp(-(w_i . h_i + b_i))).
+  * confidence mode 3 = M(h_i) (Section 2.1, dedicated classifier; the paper leaves M open), read as
+    one linear unit per layer on the hidden state scaled to unit root mean square (no gain), followed
+    by the logistic function: 1 / (1 + exp(-(w_i . h_i / sqrt(mean(h_i^2) + eps) + b_i))).  The scaling
+    is what every other consumer of the residual stream in this model family applies; without it the
+    unit's input grows with the norm of the residual stream, by orders of magnitude over the layers.
     Modes 2 and 3 never touch the LM head inside the loop; tokens still come from the hidden state at
     output_layer through transform_to_tokens, as Algorithm 1 says.
   * exit head = final RMSNorm gain + the LM head, logits multiplied by logit_scale * i (1-based i);
@@ -189,8 +192,11 @@ def similarity_confidence(h_prev: torch.Tensor, h: torch.Tensor) -> torch.Tensor
 
 
 def classifier_confidence(m: OracleModel, i: int, h: torch.Tensor) -> torch.Tensor:
-    """Section 2.1, dedicated early-exit classifier M(h_i): logistic function of one linear unit per layer."""
-    t = h.to(F64) @ m.weights["w_cls"][i - 1].to(F64) + float(m.weights["b_cls"][i - 1])
+    """Section 2.1, dedicated early-exit classifier M(h_i): logistic function of one linear unit per layer on
+    the hidden state scaled to unit root mean square."""
+    h = h.to(F64)
+    x = h / torch.sqrt(h.pow(2).mean(dim=-1, keepdim=True) + m.rms_eps)
+    t = x @ m.weights["w_cls"][i - 1].to(F64) + float(m.weights["b_cls"][i - 1])
     return 1.0 / (1.0 + torch.exp(-t))
 
 

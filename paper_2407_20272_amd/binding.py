@@ -187,6 +187,15 @@ class DeviceModel:
                           self.b_cls.data_ptr() if self.b_cls is not None else None)
         torch.cuda.synchronize()
 
+    def with_conf_mode(self, conf_mode: int) -> "DeviceModel":
+        """The same device weights under another confidence measure (a second host-side record, nothing copied)."""
+        import copy
+        v = copy.copy(self)
+        v.cfg = self.cfg.with_(conf_mode=conf_mode)
+        v.desc = make_desc(v.cfg)
+        v.c = ee_model(v.desc, self.c.embed, self.c.g_final, self.c.w_lm, self.layers, self.c.w_cls, self.c.b_cls)
+        return v
+
 
 class PagedKV:
     """Paged K/V pools [n_layers][num_blocks][H][16][dh] in the model dtype."""

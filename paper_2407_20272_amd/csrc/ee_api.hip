@@ -532,6 +532,8 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
         da.sq_b = w.msr + 2 * (size_t)B;
       }
       da.bias = D.conf_mode == 3 ? model->b_cls + (i - 1) : nullptr;
+      da.d = d;
+      da.eps = D.rms_eps;
       da.B = B;
       da.layer = i;
       da.threshold = thresholds[i - 1];

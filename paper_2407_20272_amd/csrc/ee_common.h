@@ -172,12 +172,15 @@ struct CombineArgs {
 };
 void launch_combine(const CombineArgs& a, Pred pred, hipStream_t st);
 // Exit decision from a measure that is one dot product per row (conf_mode 2: cosine of consecutive hidden
-// states = dots / sqrt(sq_a * sq_b); conf_mode 3: logistic function of dots + bias[0]).
+// states = dots / sqrt(sq_a * sq_b); conf_mode 3: logistic function of dots * rsqrt(sq_b / d + eps) + bias[0],
+// the classifier's unit applied to the hidden state at unit root mean square).
 struct DecideArgs {
   const float* dots;   // [B]
   const float* sq_a;   // [B] squared norms (conf_mode 2)
   const float* sq_b;
   const float* bias;   // device, this layer's bias (conf_mode 3)
+  int d;               // width of the hidden state
+  float eps;
   int B;
   int layer;
   float threshold;

@@ -149,10 +149,11 @@ def make_weights(cfg: EEConfig, seed: int = 0, device="cpu", gain_jitter: float 
         })
     w["layers"] = layers
     # Synthetic dedicated exit classifier (Section 2.1, third measure): one float32 weight row and one bias
-    # per layer.  No trained classifier exists here: rows are N(0, 1) and the bias rises linearly from -2 at
-    # layer 1 to +2 at layer n, so that deeper layers accept more often, as a trained one would.
+    # per layer, applied to the hidden state at unit root mean square.  No trained classifier exists here:
+    # rows are N(0, 1.5^2 / d), i.e. the unit's input has standard deviation 1.5 in every layer; the bias rises
+    # linearly from -2 at layer 1 to +2 at layer n, so that deeper layers accept more often, as a trained one would.
     n = cfg.n_layers
-    w["w_cls"] = _normal((n, d), 1.0, seed, "w_cls", device, torch.float32)
+    w["w_cls"] = _normal((n, d), 1.5 / d ** 0.5, seed, "w_cls", device, torch.float32)
     w["b_cls"] = torch.tensor([-2.0 + 4.0 * i / max(n - 1, 1) for i in range(n)], dtype=torch.float32, device=device)
     return w
 

@@ -69,14 +69,15 @@ def measure_tolerance(cfg, m, tr, i, b) -> float:
     """Tolerance of the confidence of sequence b at layer i (1-based), derived from the arithmetic of the measure.
     conf_mode 0/1: through the softmax from a logit tolerance (conf_tolerance).
     conf_mode 2: cos of two vectors that are each off by a relative error delta moves by about 2 delta sin(angle).
-    conf_mode 3: the unit's input w.h moves by about |w_unit| delta |h| (4 sigma of a random-direction error:
-      4 delta |h| for rows of unit variance), and the logistic function has slope c(1-c)."""
+    conf_mode 3: the unit's input w.x (x at unit root mean square, |x| = sqrt(d)) moves by about |w| delta sqrt(d)
+      along a random direction, i.e. by 1.5 delta for the generator's rows of variance 1.5^2/d; 4 sigma of that
+      and the logistic function's slope c(1-c)."""
     c = float(tr["conf"][i - 1, b])
     h = tr["h"][i - 1][b]
     if m.conf_mode == 2:
         return (1e-5 if cfg.dtype == "fp32" else 1e-3) + 2.0 * hidden_rel_err(cfg) * math.sqrt(max(1.0 - c * c, 0.0))
     if m.conf_mode == 3:
-        return (1e-5 if cfg.dtype == "fp32" else 1e-3) + max(c * (1.0 - c), 1e-3) * 4.0 * hidden_rel_err(cfg) * float(h.norm())
+        return (1e-5 if cfg.dtype == "fp32" else 1e-3) + max(c * (1.0 - c), 1e-3) * 4.0 * 1.5 * hidden_rel_err(cfg)
     z = O.head_logits(m, h[None])
     return conf_tolerance(cfg, c, cfg.logit_scale * i, float(z.abs().max()))
 

@@ -419,7 +419,9 @@ def test_p7_classifier_closed_forms():
     g = torch.Generator().manual_seed(6)
     h = torch.randn(5, cfg.d_model, generator=g, dtype=F64)
     for i in (1, cfg.n_layers):
-        want = torch.sigmoid(F.linear(h, w["w_cls"][i - 1:i].to(F64), w["b_cls"][i - 1:i].to(F64)))[:, 0]
+        x = F.rms_norm(h, (cfg.d_model,), None, cfg.rms_eps)                    # unit root mean square, no gain
+        want = torch.sigmoid(F.linear(x, w["w_cls"][i - 1:i].to(F64), w["b_cls"][i - 1:i].to(F64)))[:, 0]
+        torch.testing.assert_close(O.classifier_confidence(m, i, 7.5 * h), want, rtol=1e-4, atol=1e-5)   # scale free up to eps
         torch.testing.assert_close(O.classifier_confidence(m, i, h), want)
     # zero weights: the logistic function of the bias alone; a shift of the bias by ln 3 turns 1/2 into 3/4
     w0 = dict(w, w_cls=torch.zeros_like(w["w_cls"]), b_cls=torch.tensor([0.0, math.log(3.0), -math.log(3.0)]))
@@ -433,7 +435,8 @@ def test_p7_classifier_closed_forms():
         wu[i, i] = 1.0
     mu = O.model_from_config(cfg, dict(w, w_cls=wu, b_cls=torch.zeros(cfg.n_layers)), conf_mode=3)
     for i in range(1, cfg.n_layers + 1):
-        torch.testing.assert_close(O.classifier_confidence(mu, i, h), torch.sigmoid(h[:, i - 1]))
+        torch.testing.assert_close(O.classifier_confidence(mu, i, h),
+                                   torch.sigmoid(h[:, i - 1] / torch.sqrt(h.pow(2).mean(-1) + cfg.rms_eps)))
 
 
 @pytest.mark.parametrize("conf_mode", [2, 3])
@@ -456,7 +459,8 @@ def test_p7_iteration_confidences_against_bruteforce(conf_mode):
             if conf_mode == 2:
                 want = float(F.cosine_similarity(hs[i - 1], hs[i], dim=0, eps=0.0))
             else:
-                want = float(torch.sigmoid(hs[i] @ w["w_cls"][i - 1].to(F64) + w["b_cls"][i - 1].to(F64)))
+                x = F.rms_norm(hs[i], (cfg.d_model,), None, cfg.rms_eps)
+                want = float(torch.sigmoid(x @ w["w_cls"][i - 1].to(F64) + w["b_cls"][i - 1].to(F64)))
             assert abs(float(tr["conf"][i - 1, b]) - want) < 1e-9, (b, i)
         assert math.isnan(float(tr["conf"][cfg.n_layers - 1, b]))       # no check after the last layer
 
