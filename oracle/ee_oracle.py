@@ -37,6 +37,9 @@ Readings taken where the paper is silent or inconsistent (each also listed in th
   * exit head = final RMSNorm gain + the LM head, logits multiplied by logit_scale * i (1-based i);
     no check after the last layer; ties in argmax go to the lowest index.
 
+decode_iteration_freeze is an extension that the paper does not define (per-sequence exit instead of
+the batch leaving together); its docstring states its rule.
+
 Pins (tests/test_oracle_*.py): brute-force uncached causal forward, threshold > 1 equals the
 head-less full-layer pass, forced exit on a saturated model leaves the cache identical to a full
 pass, control logic against its three-line definition, closed forms of the confidence, rotary and
@@ -287,6 +290,60 @@ def decode_iteration(m: OracleModel, cache: DenseKV, tokens: torch.Tensor, pos: 
             output_layer = i
             break
     kv_fill(m, cache, h, pos, output_layer + 1)
+    out = transform_to_tokens(m, h) if B > 0 else torch.zeros(0, dtype=torch.int32)
+    if trace is not None:
+        trace["conf"] = conf_log
+        trace["h_exit"] = h.clone()
+    return out, torch.tensor(exit_layer, dtype=torch.int32), output_layer
+
+
+def decode_iteration_freeze(m: OracleModel, cache: DenseKV, tokens: torch.Tensor, pos: torch.Tensor,
+                            thresholds, forced_exit_layer: Optional[torch.Tensor] = None,
+                            trace: Optional[dict] = None):
+    """One decode iteration with PER-SEQUENCE early exit: an extension beyond Algorithm 1, which makes the
+    whole batch leave together.  Same status rule (Section 3.1) and the same cache filling (Section 3.2), but
+    applied to each sequence on its own:
+      * a sequence whose status turns true at layer e_b stops there: layers e_b+1.. neither run for it nor
+        cache K/V for it; it leaves the active set;
+      * the loop ends after the first layer that leaves the active set empty (output_layer = max_b e_b),
+        or after layer n;
+      * K/V of this position for layers e_b+1..n are filled from the sequence's own hidden state at e_b;
+      * its token comes from that same hidden state.
+    A sequence never accepted has e_b = n and behaves as in a full-layer pass.  Every sequence's result is
+    therefore what it would be in a batch of one.  Arguments and return value as decode_iteration
+    (trace["h_exit"] holds each sequence's own exit hidden state; trace["h"] is not recorded).
+    """
+    n = m.n_layers
+    B = int(tokens.shape[0])
+    lam = [float(thresholds)] * n if isinstance(thresholds, (int, float)) else [float(t) for t in thresholds]
+    h = store(m.weights["embed"][tokens.long()], m.dtype).clone()
+    status = [False] * B
+    exit_layer = [n] * B
+    output_layer = n
+    conf_log = torch.full((n, B), float("nan"), dtype=F64)
+    for i in range(1, n + 1):
+        active = [b for b in range(B) if not status[b]]
+        if not active:
+            break
+        h_prev = h[active]
+        h_new = layer_forward(m, i, h_prev, _RowView(cache, active), pos[active])
+        if B > 0 and has_exit_head(m, i):
+            full_prev, full_new = h.clone(), h.clone()
+            full_new[active] = h_new
+            c, _ = exit_check(m, i, full_new, active, full_prev)
+            conf = {b: float(c[r]) for r, b in enumerate(active)}
+            for b in active:
+                conf_log[i - 1, b] = conf[b]
+            if forced_exit_layer is not None:
+                conf = {b: (math.inf if i >= int(forced_exit_layer[b]) else -math.inf) for b in active}
+            update_status(status, exit_layer, i, conf, lam[i - 1])
+        h[active] = h_new
+        if B > 0 and all(status):
+            output_layer = i
+            break
+    for e in sorted(set(exit_layer)):
+        rows = [b for b in range(B) if exit_layer[b] == e]
+        kv_fill(m, _RowView(cache, rows), h[rows], pos[rows], e + 1)
     out = transform_to_tokens(m, h) if B > 0 else torch.zeros(0, dtype=torch.int32)
     if trace is not None:
         trace["conf"] = conf_log

@@ -485,3 +485,109 @@ def test_p7_thresholds_that_always_and_never_fire(conf_mode):
     assert torch.equal(t2, t3)
     for i in range(cfg.n_layers):
         assert torch.equal(c2.K[i], c3.K[i]) and torch.equal(c2.V[i], c3.V[i])
+
+
+# ------------------------------------------------------------------------------------------------
+# P8: per-sequence exit (the extension decode_iteration_freeze), pinned against Algorithm 1's function
+# ------------------------------------------------------------------------------------------------
+def run_freeze(cfg, w, prompts, lens, steps, thresholds, forced=None, conf_mode=None, rows=None):
+    """Prefill (full layers) + `steps` per-sequence-exit iterations; rows: run only these sequences as a batch."""
+    m = O.model_from_config(cfg, w) if conf_mode is None else O.model_from_config(cfg, w, conf_mode=conf_mode)
+    if rows is not None:
+        prompts, lens = prompts[rows], lens[rows]
+    B = prompts.shape[0]
+    cache = O.DenseKV(cfg.n_layers, B, int(lens.max()) + steps, cfg.n_heads, cfg.head_dim, cfg.dtype)
+    tok = O.prefill(m, cache, prompts, lens)
+    pos = lens.clone().long()
+    out, exits, Ls = [tok.clone()], [], []
+    for s in range(steps):
+        f = None if forced is None else (forced[s] if rows is None else forced[s][rows])
+        tok, e, L = O.decode_iteration_freeze(m, cache, tok, pos, thresholds, forced_exit_layer=f)
+        out.append(tok.clone())
+        exits.append(e)
+        Ls.append(L)
+        pos += 1
+    return torch.stack(out, 1), exits, Ls, cache
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_p8_freeze_never_firing_is_full_layer(dtype):
+    cfg = small_cfg(dtype=dtype, n_layers=4)
+    w = W.make_weights(cfg, seed=12, gain_jitter=0.1)
+    prompts, lens = W.make_prompts(cfg, seed=12), W.make_context_lens(cfg, seed=12)
+    t1, e1, L1, c1 = run_freeze(cfg, w, prompts, lens, 3, 1.0 + 1e-6)
+    t0, e0, L0, c0 = run_oracle(cfg, w, prompts, lens, 3, 0.5, heads=False)
+    assert torch.equal(t1, t0) and all(L == cfg.n_layers for L in L1)
+    for i in range(cfg.n_layers):
+        assert torch.equal(c1.K[i], c0.K[i]) and torch.equal(c1.V[i], c0.V[i])
+
+
+@pytest.mark.parametrize("conf_mode", [0, 2])
+def test_p8_freeze_equals_each_sequence_alone_under_algorithm_1(conf_mode):
+    """With per-sequence exit no sequence depends on its batch mates: the batch result equals, sequence by
+    sequence, Algorithm 1 run on a batch of one (where 'the batch leaves together' is the same rule)."""
+    cfg = small_cfg(n_layers=5, dtype="fp32", batch=4, prompt_len=6, min_prompt_len=3)
+    w = W.make_weights(cfg, seed=13, gain_jitter=0.1)
+    prompts, lens = W.make_prompts(cfg, seed=13), W.make_context_lens(cfg, seed=13)
+    thr = 0.9 if conf_mode == 0 else 0.75
+    steps = 3
+    tb, eb, Lb, cb = run_freeze(cfg, w, prompts, lens, steps, thr, conf_mode=conf_mode)
+    seen = set()
+    for b in range(cfg.batch):
+        t1, e1, L1, c1 = run_oracle(cfg, w, prompts[b:b + 1], lens[b:b + 1], steps, thr, conf_mode=conf_mode)
+        assert torch.equal(t1[0], tb[b]), b
+        T = int(lens[b]) + steps
+        for s in range(steps):
+            assert int(e1[s][0]) == int(eb[s][b]) == L1[s]
+            seen.add(int(eb[s][b]))
+        for i in range(cfg.n_layers):
+            torch.testing.assert_close(cb.K[i][b, :T], c1.K[i][0, :T], rtol=1e-9, atol=1e-11)   # matmul row blocking
+            torch.testing.assert_close(cb.V[i][b, :T], c1.V[i][0, :T], rtol=1e-9, atol=1e-11)
+    for s in range(steps):
+        assert Lb[s] == int(eb[s].max())                      # the loop ends when the last sequence has left
+    assert len(seen) >= 2, seen                                 # the thresholds did spread the exit layers
+
+
+def test_p8_freeze_uniform_forced_exit_equals_algorithm_1():
+    """When every sequence leaves at the same layer, leaving one by one and leaving together coincide."""
+    cfg = small_cfg(n_layers=5, dtype="bf16", batch=3)
+    w = W.make_weights(cfg, seed=14, gain_jitter=0.1)
+    prompts, lens = W.make_prompts(cfg, seed=14), W.make_context_lens(cfg, seed=14)
+    forced = [torch.full((cfg.batch,), 2, dtype=torch.int32), torch.full((cfg.batch,), 4, dtype=torch.int32)]
+    t1, e1, L1, c1 = run_freeze(cfg, w, prompts, lens, 2, 0.5, forced=forced)
+    t0, e0, L0, c0 = run_oracle(cfg, w, prompts, lens, 2, 0.5, forced=forced)
+    assert torch.equal(t1, t0) and L1 == L0 == [2, 4]
+    for i in range(cfg.n_layers):
+        assert torch.equal(c1.K[i], c0.K[i]) and torch.equal(c1.V[i], c0.V[i])
+
+
+def test_p8_freeze_differs_from_algorithm_1_where_it_should():
+    """Mixed forced exit layers: a sequence that left early keeps the token of its own exit layer and the
+    filled K/V above it, while Algorithm 1 runs it on to the batch exit layer."""
+    cfg = small_cfg(n_layers=5, dtype="fp32", batch=2)
+    w = W.make_weights(cfg, seed=15, gain_jitter=0.1)
+    m = O.model_from_config(cfg, w)
+    prompts, lens = W.make_prompts(cfg, seed=15), W.make_context_lens(cfg, seed=15)
+    forced = torch.tensor([1, 4], dtype=torch.int32)
+    ctx = int(lens.max()) + 1
+    ca, cb = (O.DenseKV(cfg.n_layers, 2, ctx, cfg.n_heads, cfg.head_dim, cfg.dtype) for _ in range(2))
+    tok = O.prefill(m, ca, prompts, lens)
+    O.prefill(m, cb, prompts, lens)
+    pos = lens.clone().long()
+    tr = {}
+    tf, ef, Lf = O.decode_iteration_freeze(m, ca, tok, pos, 0.5, forced_exit_layer=forced, trace=tr)
+    ts, es, Ls = O.decode_iteration(m, cb, tok, pos, 0.5, forced_exit_layer=forced)
+    assert ef.tolist() == es.tolist() == [1, 4] and Lf == Ls == 4
+    p0 = int(pos[0])
+    # sequence 1 (left last, at the batch exit layer) is the same in both; sequence 0 is not above its exit layer
+    for i in range(cfg.n_layers):
+        assert torch.equal(ca.K[i][1], cb.K[i][1])
+    assert torch.equal(ca.K[0][0, p0], cb.K[0][0, p0])          # layer 1 ran for it in both
+    assert not torch.equal(ca.K[2][0, p0], cb.K[2][0, p0])      # layer 3: filled from h_1 vs computed
+    # its filled K/V are the closed form of Section 3.2 applied to its own exit hidden state
+    h1 = tr["h_exit"][0:1]
+    for i in range(2, cfg.n_layers + 1):
+        x = F.rms_norm(h1, (cfg.d_model,), w["layers"][i - 1]["g_attn"].to(F64), cfg.rms_eps)
+        v = F.linear(x, w["layers"][i - 1]["w_v"].to(F64)).view(cfg.n_heads, cfg.head_dim)
+        torch.testing.assert_close(ca.V[i - 1][0, p0], v, rtol=1e-12, atol=1e-12)
+    assert bool(ca.written[4][0, p0]) and bool(ca.written[4][1, p0])
