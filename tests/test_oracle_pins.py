@@ -581,9 +581,9 @@ def test_p8_freeze_differs_from_algorithm_1_where_it_should():
     p0 = int(pos[0])
     # sequence 1 (left last, at the batch exit layer) is the same in both; sequence 0 is not above its exit layer
     for i in range(cfg.n_layers):
-        assert torch.equal(ca.K[i][1], cb.K[i][1])
-    assert torch.equal(ca.K[0][0, p0], cb.K[0][0, p0])          # layer 1 ran for it in both
-    assert not torch.equal(ca.K[2][0, p0], cb.K[2][0, p0])      # layer 3: filled from h_1 vs computed
+        torch.testing.assert_close(ca.K[i][1], cb.K[i][1], rtol=1e-9, atol=1e-11)       # (matmul row blocking)
+    torch.testing.assert_close(ca.K[0][0, p0], cb.K[0][0, p0], rtol=1e-9, atol=1e-11)   # layer 1 ran for it in both
+    assert float((ca.K[2][0, p0] - cb.K[2][0, p0]).abs().max()) > 1e-3                  # layer 3: filled from h_1 vs computed
     # its filled K/V are the closed form of Section 3.2 applied to its own exit hidden state
     h1 = tr["h_exit"][0:1]
     for i in range(2, cfg.n_layers + 1):
