@@ -139,13 +139,22 @@ size_t ee_workspace_bytes(const ee_model_desc* desc, int32_t max_batch, int32_t 
  *   thresholds        host [n_layers]: lambda_i; accepted means confidence > lambda_i (strict).
  *   forced_exit_layer dev [B] or NULL: synthetic confidence injection; the decision of sequence b at layer i
  *                     becomes (i >= forced_exit_layer[b]) while the exit-head arithmetic still runs.
- *   use_exit_heads    0 = full-layer baseline: no exit head is evaluated, output_layer = n.
+ *   use_exit_heads    EE_EXIT_NONE (0): full-layer baseline, no exit check is made, output_layer = n.
+ *                     EE_EXIT_BATCH (1): Algorithm 1 as above.
+ *                     EE_EXIT_PER_SEQUENCE (2): an extension of Algorithm 1 in which each sequence leaves on its
+ *                     own: once its status is true, later layers neither cache K/V for it nor attend for it nor
+ *                     change its hidden state; the loop still ends at the first layer after which every status
+ *                     is true (output_layer = the largest exit layer); K/V of layers above a sequence's OWN exit
+ *                     layer are filled from its own exit hidden state, and its token comes from that state.
  *   out_tokens        dev [B] int32: greedy token (lowest index on ties).
  *   out_exit_layer    dev [B] int32: first layer whose check accepted the sequence, n_layers if none.
  *   out_batch_exit_layer dev [1] int32: output_layer.
  *   out_conf          dev [n_layers][B] float or NULL: confidence evaluated at each layer; NaN where no check
  *                     was made (no head, sequence already accepted, layer not run).
  *   out_hidden        dev [B][d] float or NULL: hidden state at output_layer (what the tokens come from). */
+#define EE_EXIT_NONE 0
+#define EE_EXIT_BATCH 1
+#define EE_EXIT_PER_SEQUENCE 2
 int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const ee_batch* batch,
                         const float* thresholds, const int32_t* forced_exit_layer, int32_t use_exit_heads,
                         int32_t* out_tokens, int32_t* out_exit_layer, int32_t* out_batch_exit_layer,

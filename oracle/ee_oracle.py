@@ -311,7 +311,8 @@ def decode_iteration_freeze(m: OracleModel, cache: DenseKV, tokens: torch.Tensor
       * its token comes from that same hidden state.
     A sequence never accepted has e_b = n and behaves as in a full-layer pass.  Every sequence's result is
     therefore what it would be in a batch of one.  Arguments and return value as decode_iteration
-    (trace["h_exit"] holds each sequence's own exit hidden state; trace["h"] is not recorded).
+    (trace["h_exit"] holds each sequence's own exit hidden state; trace["h"][i-1] the batch's hidden states
+    after layer i, a sequence that has left keeping its exit hidden state).
     """
     n = m.n_layers
     B = int(tokens.shape[0])
@@ -321,6 +322,8 @@ def decode_iteration_freeze(m: OracleModel, cache: DenseKV, tokens: torch.Tensor
     exit_layer = [n] * B
     output_layer = n
     conf_log = torch.full((n, B), float("nan"), dtype=F64)
+    if trace is not None:
+        trace["h"] = []
     for i in range(1, n + 1):
         active = [b for b in range(B) if not status[b]]
         if not active:
@@ -338,6 +341,8 @@ def decode_iteration_freeze(m: OracleModel, cache: DenseKV, tokens: torch.Tensor
                 conf = {b: (math.inf if i >= int(forced_exit_layer[b]) else -math.inf) for b in active}
             update_status(status, exit_layer, i, conf, lam[i - 1])
         h[active] = h_new
+        if trace is not None:
+            trace["h"].append(h.clone())
         if B > 0 and all(status):
             output_layer = i
             break

@@ -226,13 +226,16 @@ class Workspace:
         assert self.buf.data_ptr() % 256 == 0
 
 
+EE_EXIT_NONE, EE_EXIT_BATCH, EE_EXIT_PER_SEQUENCE = 0, 1, 2
+
+
 def ee_decode_iteration(model: DeviceModel, cache: PagedKV, batch: ee_batch, thresholds, forced_exit_layer,
-                        use_exit_heads: bool, out_tokens, out_exit_layer, out_batch_exit_layer, out_conf, out_hidden,
+                        use_exit_heads, out_tokens, out_exit_layer, out_batch_exit_layer, out_conf, out_hidden,
                         ws: Workspace):
     n = model.cfg.n_layers
     th = (C.c_float * n)(*([float(thresholds)] * n if isinstance(thresholds, (int, float)) else list(thresholds)))
     _check(lib().ee_decode_iteration(C.byref(model.c), C.byref(cache.c), C.byref(batch), th,
-                                     _ptr(forced_exit_layer), int(bool(use_exit_heads)), _ptr(out_tokens),
+                                     _ptr(forced_exit_layer), int(use_exit_heads), _ptr(out_tokens),
                                      _ptr(out_exit_layer), _ptr(out_batch_exit_layer), _ptr(out_conf), _ptr(out_hidden),
                                      _ptr(ws.buf), ws.bytes, _stream()))
 

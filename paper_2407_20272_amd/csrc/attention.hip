@@ -91,12 +91,14 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   // three in a row.
   const int t0 = (int)threadIdx.x < a.max_blocks ? table[threadIdx.x] : 0;
   const int len = a.context_lens[b];
+  const int left = a.skip ? a.skip[b] : 0;
   float q[EPL];
   {
     const float* qp = a.q + ((size_t)b * a.n_heads + head) * DH + sub * EPL;
 #pragma unroll
     for (int i = 0; i < EPL; ++i) q[i] = qp[i];
   }
+  if (left != 0) return;   // the sequence has left at an earlier layer: nothing to attend, nothing read
   // positions 0..p inclusive, never beyond the block table's width
   const int n_ctx = min(len + 1, a.max_blocks * 16);
   const int n_blocks = (n_ctx + 15) >> 4;

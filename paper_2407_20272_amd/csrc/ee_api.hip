@@ -268,8 +268,8 @@ void enqueue_head_f32(const ee_model& M, const Workspace& w, const float* h, int
 // (stand-alone call).  > 0: rowsq_slot is slot 0 of the iteration's table and the sums of the exit hidden state are
 // already in slot 2 * batch_exit_layer, left there by that layer's down projection.
 void enqueue_fill_bf16(const ee_model& M, const ee_kv_cache& C, const ee_batch& Bt, const Workspace& w, int Mpad,
-                       const int32_t* fill_from, int stride, float* rowsq_slot, size_t rowsq_layer_stride, Pred pred,
-                       hipStream_t st) {
+                       const int32_t* fill_from, int stride, float* rowsq_slot, size_t rowsq_layer_stride,
+                       const int32_t* slot_ptr, Pred pred, hipStream_t st) {
   const ee_model_desc& D = M.desc;
   GainTable gt{};
   FillLayers fl{};
@@ -279,8 +279,8 @@ void enqueue_fill_bf16(const ee_model& M, const ee_kv_cache& C, const ee_batch& 
   }
   ProfScope ps(EE_K_KVFILL, 0, st);
   if (rowsq_layer_stride == 0) launch_rowsq(w.hT, rowsq_slot, Mpad, D.d_model, pred, st);
-  launch_prep_x_layers(w.hT, gt, D.n_layers, w.fill_x, rowsq_slot, rowsq_layer_stride, D.rms_eps, fill_from, stride,
-                       Bt.batch, Mpad, D.d_model, pred, st);
+  launch_prep_x_layers(w.hT, gt, D.n_layers, w.fill_x, rowsq_slot, rowsq_layer_stride, slot_ptr, D.rms_eps, fill_from,
+                       stride, Bt.batch, Mpad, D.d_model, pred, st);
   GemmShape g{nullptr, nullptr, D.d_model, Bt.batch, D.d_model / 32, 2 * D.d_model / 32, D.head_dim / 2, 1};
   QkvEpi e = make_qkv_epi(D, C, Bt, w, 1, nullptr);
   e.fill_from = fill_from;
@@ -391,6 +391,8 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   if ((rc = check_workspace(D, B, workspace, workspace_bytes))) return rc;
   // Confidence measures that need no LM head (Section 2.1): 2 = similarity of consecutive hidden states,
   // 3 = dedicated classifier.  Both are one dot product per row, taken while the next operand is prepared.
+  if (use_exit_heads < 0 || use_exit_heads > EE_EXIT_PER_SEQUENCE)
+    EE_FAIL(EE_ERR_INVALID_ARG, "use_exit_heads must be EE_EXIT_NONE, EE_EXIT_BATCH or EE_EXIT_PER_SEQUENCE");
   const bool dotmode = use_exit_heads && D.conf_mode >= 2;
   const bool simmode = use_exit_heads && D.conf_mode == 2;
   if (use_exit_heads && D.conf_mode == 3 && (!model->w_cls || !model->b_cls))
@@ -401,6 +403,10 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   const int n = D.n_layers, d = D.d_model, f = D.d_ffn;
   const bool bf = D.dtype == EE_BF16;
   IterState s{w.status, out_exit_layer, w.n_exited, w.done, out_batch_exit_layer};
+  // Per-sequence exit (an extension of Algorithm 1): a sequence whose status is set has left.  Layers still run
+  // over the whole batch, but for such a sequence they cache no K/V, attend nothing and leave its hidden state as
+  // it is, so at the end every sequence's column of the residual stream is its own exit hidden state.
+  const int32_t* left = use_exit_heads == EE_EXIT_PER_SEQUENCE ? w.status : nullptr;
   const Pred run_layers{w.done, 0};  // kernels of the layer loop: only while the batch has not left
   const Pred run_fill{w.done, 1};    // KV filling: only after it has
   const Pred always{nullptr, 0};
@@ -426,7 +432,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     const ee_layer_weights& L = model->layers[i - 1];
     const size_t pool_off = pool_layer_elems(D, *cache) * elem_bytes(D) * (size_t)(i - 1);
     AttnArgs at{w.q, reinterpret_cast<char*>(cache->k_pool) + pool_off, reinterpret_cast<char*>(cache->v_pool) + pool_off,
-                batch->context_lens, batch->block_tables, batch->max_blocks, B, D.n_heads, D.head_dim, nullptr, 0};
+                batch->context_lens, batch->block_tables, batch->max_blocks, B, D.n_heads, D.head_dim, nullptr, 0, left};
     const bool head_here = use_exit_heads && has_head(D, i);
     if (bf) {
       if (i == 1) {
@@ -440,7 +446,9 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       {
         ProfScope ps(EE_K_QKV, i, st);
         GemmShape gq{L.w_qkv, w.xT, d, B, 0, 3 * d / 32, D.head_dim / 2, 1};
-        launch_gemm_qkv_bf16(gq, make_qkv_epi(D, *cache, *batch, w, i, w.q), run_layers, st);
+        QkvEpi qe = make_qkv_epi(D, *cache, *batch, w, i, w.q);
+        qe.skip = left;
+        launch_gemm_qkv_bf16(gq, qe, run_layers, st);
       }
       {
         ProfScope ps(EE_K_ATTN, i, st);
@@ -451,7 +459,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       {
         ProfScope ps(EE_K_OPROJ, i, st);   // also leaves the row sums of squares the FFN norm needs
         GemmShape go{L.w_o, w.aoT, d, B, 0, d / 32, 16, acc_ksplit(d / 32, d)};
-        launch_gemm_acc_bf16(go, AccEpi{w.hT, Mpad, d, rs(2 * i - 1), w.tile_cnt}, run_layers, st);
+        launch_gemm_acc_bf16(go, AccEpi{w.hT, Mpad, d, rs(2 * i - 1), w.tile_cnt, left}, run_layers, st);
       }
       {
         ProfScope ps(EE_K_NORM, i, st);
@@ -465,7 +473,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       {
         ProfScope ps(EE_K_DOWN, i, st);    // row sums for the exit head and for the next layer's attention norm
         GemmShape gd{L.w_down, w.actT, f, B, 0, d / 32, 16, acc_ksplit(d / 32, f)};
-        launch_gemm_acc_bf16(gd, AccEpi{w.hT, Mpad, d, rs(2 * i), w.tile_cnt}, run_layers, st);
+        launch_gemm_acc_bf16(gd, AccEpi{w.hT, Mpad, d, rs(2 * i), w.tile_cnt, left}, run_layers, st);
       }
       if (i < n) {   // operand of the next layer's attention (and of this layer's exit head, in the same launch)
         ProfScope ps(EE_K_NORM, i, st);
@@ -491,7 +499,9 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
         ProfScope ps(EE_K_QKV, i, st);
         launch_rmsnorm_f32(w.h, reinterpret_cast<const float*>(L.g_attn), w.x, B, d, D.rms_eps, run_layers, st);
         SimpleShape gq{reinterpret_cast<const float*>(L.w_qkv), w.x, d, B, 0, 3 * d, D.head_dim / 2};
-        launch_simple_qkv(gq, make_qkv_epi(D, *cache, *batch, w, i, w.q), run_layers, st);
+        QkvEpi qe = make_qkv_epi(D, *cache, *batch, w, i, w.q);
+        qe.skip = left;
+        launch_simple_qkv(gq, qe, run_layers, st);
       }
       {
         ProfScope ps(EE_K_ATTN, i, st);
@@ -502,7 +512,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       {
         ProfScope ps(EE_K_OPROJ, i, st);
         SimpleShape go{reinterpret_cast<const float*>(L.w_o), w.ao, d, B, 0, d, 1};
-        launch_simple_acc(go, AccEpi{w.h, 0, d, nullptr, nullptr}, run_layers, st);
+        launch_simple_acc(go, AccEpi{w.h, 0, d, nullptr, nullptr, left}, run_layers, st);
       }
       {
         ProfScope ps(EE_K_GATEUP, i, st);
@@ -513,7 +523,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       {
         ProfScope ps(EE_K_DOWN, i, st);
         SimpleShape gd{reinterpret_cast<const float*>(L.w_down), w.act, f, B, 0, d, 1};
-        launch_simple_acc(gd, AccEpi{w.h, 0, d, nullptr, nullptr}, run_layers, st);
+        launch_simple_acc(gd, AccEpi{w.h, 0, d, nullptr, nullptr, left}, run_layers, st);
       }
     }
     if (!bf && simmode && !head_here && i < n) launch_copy_f32(w.h, w.hprev, (size_t)B * d, st);
@@ -556,10 +566,19 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     }
   }
 
-  // Algorithm 1, KV cache filling for layers output_layer+1..n (runs only if the batch left early)
-  if (use_exit_heads) {
+  // Algorithm 1, KV cache filling for layers output_layer+1..n (runs only if the batch left early).
+  // Per-sequence exit: every sequence fills the layers above its own exit layer from its own hidden state,
+  // whether or not the whole batch left; layers nobody needs return at once.
+  if (use_exit_heads == EE_EXIT_PER_SEQUENCE) {
     if (bf)
-      enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, out_batch_exit_layer, 0, rs(0), (size_t)2 * Mpad, run_fill, st);
+      enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, out_exit_layer, 1, rs(0), (size_t)2 * Mpad, out_batch_exit_layer,
+                        always, st);
+    else
+      enqueue_fill_f32(*model, *cache, *batch, w, w.h, out_exit_layer, 1, always, st);
+  } else if (use_exit_heads) {
+    if (bf)
+      enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, out_batch_exit_layer, 0, rs(0), (size_t)2 * Mpad,
+                        out_batch_exit_layer, run_fill, st);
     else
       enqueue_fill_f32(*model, *cache, *batch, w, w.h, out_batch_exit_layer, 0, run_fill, st);
   }
@@ -653,7 +672,7 @@ int ee_kv_fill(const ee_model* model, const ee_kv_cache* cache, const ee_batch* 
     launch_iter_init(IterState{w.status, w.scratch_exit_layer, w.n_exited, w.done, w.scratch_L}, 0, D.n_layers, nullptr,
                      w.rowsq, (size_t)Mpad, st);
     launch_hidden_to_ht(hidden, w.hT, B, Mpad, D.d_model, st);
-    enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, fill_from_layer, 1, w.rowsq, 0, always, st);
+    enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, fill_from_layer, 1, w.rowsq, 0, nullptr, always, st);
   } else {
     enqueue_fill_f32(*model, *cache, *batch, w, hidden, fill_from_layer, 1, always, st);
   }
@@ -673,7 +692,7 @@ int ee_paged_attention_decode(const ee_model_desc* desc, const ee_kv_cache* cach
   const size_t off = pool_layer_elems(*desc, *cache) * elem_bytes(*desc) * (size_t)(layer - 1);
   AttnArgs at{q, reinterpret_cast<char*>(cache->k_pool) + off, reinterpret_cast<char*>(cache->v_pool) + off,
               batch->context_lens, batch->block_tables, batch->max_blocks, batch->batch, desc->n_heads, desc->head_dim,
-              out, 0};
+              out, 0, nullptr};
   const Pred always{nullptr, 0};
   if ((rc = launch_attention(at, desc->dtype, always, reinterpret_cast<hipStream_t>(stream)))) return rc;
   EE_HIP(hipGetLastError());

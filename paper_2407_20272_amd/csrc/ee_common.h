@@ -77,6 +77,7 @@ struct QkvEpi {                 // rotary embedding + paged cache write (+ q out
   const float2* rope;           // [M][dh/2] (cos, sin) of the rotary angles at context_lens[m] (rope_theta > 0)
   const float* rowsq;           // nullptr, or [M] sum of squares of the hidden row: value *= rsqrt(rowsq/d + eps)
   float eps;
+  const int32_t* skip;          // nullptr, or [M]: rows with skip[m] != 0 write nothing (sequences that have left)
 };
 struct AccEpi {                 // h += value
   float* h;
@@ -84,6 +85,7 @@ struct AccEpi {                 // h += value
   int n_out;
   float* rowsq;                 // bf16 path: nullptr, or [Mpad] zeroed: receives sum_k h[m][k]^2 of the finished rows
   int32_t* tile_counters;       // bf16 path with rowsq: [n_tiles * m_tiles] zeroed arrival counters (left at zero)
+  const int32_t* skip;          // nullptr, or [M]: rows with skip[m] != 0 keep their hidden state (sequences that have left)
 };
 struct GateUpEpi {              // act = silu(gate) * up
   void* act;                    // XT bf16 [Mpad][f] (bf16 path) or plain float [M][f]
@@ -133,10 +135,10 @@ void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float*
 // Two normalisations of the same rows in one launch: slab 0 of xT_pair with gain_a, slab 1 (Mpad * d elements on) with gain_b.
 void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT_pair, const float* rowsq,
                         float eps, int Mpad, int d, Pred pred, hipStream_t st);
-// rowsq_layer_stride > 0 (with fill_from_stride == 0): the sums are at rowsq + fill_from[0] * rowsq_layer_stride.
+// rowsq_layer_stride > 0: the sums are at rowsq + slot_ptr[0] * rowsq_layer_stride.
 void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
-                          size_t rowsq_layer_stride, float eps, const int32_t* fill_from, int fill_from_stride, int B,
-                          int Mpad, int d, Pred pred, hipStream_t st);
+                          size_t rowsq_layer_stride, const int32_t* slot_ptr, float eps, const int32_t* fill_from,
+                          int fill_from_stride, int B, int Mpad, int d, Pred pred, hipStream_t st);
 // Optional second job of an operand preparation (confidence measures that need no LM head, Section 2.1):
 // dots[m] += sum_k h[m][k] * other, where other is the previous hidden state (per_row: HT layout, the
 // similarity measure) or one weight row shared by all rows ([d], the dedicated classifier); snapshot, if set,
@@ -240,6 +242,7 @@ struct AttnArgs {
   int max_blocks, B, n_heads, head_dim;
   void* out;                    // fp32 plain [B][H*dh], or XT bf16 [Mpad][H*dh]
   int out_xt;                   // 1: XT bf16
+  const int32_t* skip;          // nullptr, or [B]: sequences with skip[b] != 0 are not attended (they have left)
 };
 int launch_attention(const AttnArgs& a, int dtype, Pred pred, hipStream_t st);
 

@@ -99,7 +99,7 @@ __device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, con
       p[2 * ai] = e.h + ht_index(m, f_lo, e.Mpad);
       p[2 * ai + 1] = e.h + ht_index(m, f_lo + g.pair_stride, e.Mpad);
     }
-    if (m < g.M) {
+    if (m < g.M && !(e.skip && e.skip[m] != 0)) {   // a sequence that has left keeps its hidden state
 #pragma unroll
       for (int ai = 0; ai < 2; ++ai) {
         unsafeAtomicAdd(p[2 * ai], vlo[ai]);
@@ -429,7 +429,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int m = (chunk * MT + mt) * 32 + ml;
-        if (m < g.M) {
+        if (m < g.M && !(e.skip && e.skip[m] != 0)) {
 #pragma unroll
           for (int a = 0; a < 8; ++a) {
             const int f_lo = packed_row_lo(nt0 + t, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);

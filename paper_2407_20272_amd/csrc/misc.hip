@@ -349,10 +349,10 @@ void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gai
                      RowDot{}, pred);
 }
 void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
-                          size_t rowsq_layer_stride, float eps, const int32_t* fill_from, int fill_from_stride, int B,
-                          int Mpad, int d, Pred pred, hipStream_t st) {
+                          size_t rowsq_layer_stride, const int32_t* slot_ptr, float eps, const int32_t* fill_from,
+                          int fill_from_stride, int B, int Mpad, int d, Pred pred, hipStream_t st) {
   hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, n_layers), dim3(256), 0, st, hT, gains,
-                     (const bf16_t*)nullptr, xT_slabs, (size_t)Mpad * d, rowsq, rowsq_layer_stride, fill_from, eps, fill_from,
+                     (const bf16_t*)nullptr, xT_slabs, (size_t)Mpad * d, rowsq, rowsq_layer_stride, slot_ptr, eps, fill_from,
                      fill_from_stride, B, Mpad, d, RowDot{}, pred);
 }
 void launch_rmsnorm_f32(const float* h, const float* gain, float* x, int B, int d, float eps, Pred pred, hipStream_t st) {

@@ -166,8 +166,13 @@ class GpuRun:
 
 
 def oracle_step(m, cache, tokens, pos, thresholds, forced=None, heads=True):
+    """heads: False = no exit checks, True/1 = Algorithm 1, 2 = per-sequence exit (the extension)."""
     tr = {}
-    tok, e, L = O.decode_iteration(m, cache, tokens, pos, thresholds, forced_exit_layer=forced, heads=heads, trace=tr)
+    if int(heads) == 2:
+        tok, e, L = O.decode_iteration_freeze(m, cache, tokens, pos, thresholds, forced_exit_layer=forced, trace=tr)
+    else:
+        tok, e, L = O.decode_iteration(m, cache, tokens, pos, thresholds, forced_exit_layer=forced, heads=bool(heads),
+                                       trace=tr)
     return tok, e, L, tr
 
 

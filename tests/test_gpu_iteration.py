@@ -172,3 +172,36 @@ def test_headless_measures_forced_exits(conf_mode):
     forced[1] = 1
     stats = lockstep(cfg, seed=34, steps=3, forced_seq=forced)
     assert stats["L"] == [int(forced[s].max()) for s in range(3)]
+
+
+# ------------------------------------------------------------------------------------------------
+# per-sequence exit (extension of Algorithm 1): every sequence leaves at its own layer
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("conf_mode,threshold", [(0, 0.8), (2, 0.65), (3, 0.62)])
+def test_fp32_per_sequence_exit_lockstep(conf_mode, threshold):
+    cfg = TINY.with_(decode_steps=4, n_layers=6, conf_mode=conf_mode, threshold=threshold)
+    stats = lockstep(cfg, seed=31, steps=4, heads=2)
+    assert stats["near_threshold"] == 0 and stats["near_tie"] == 0
+
+
+@pytest.mark.parametrize("batch", [7, 40, 70])
+@pytest.mark.parametrize("conf_mode,threshold", [(0, 0.5), (2, 0.78)])
+def test_bf16_per_sequence_exit_lockstep(conf_mode, threshold, batch):
+    cfg = small_bf16(n_layers=6, batch=batch, prompt_len=12, min_prompt_len=4, shuffled_blocks=True,
+                     conf_mode=conf_mode, threshold=threshold)
+    stats = lockstep(cfg, seed=41, steps=5, heads=2)
+    total = stats["decisions"] + stats["tokens"]
+    assert stats["near_threshold"] + stats["near_tie"] <= max(2, total // 20), stats
+
+
+@pytest.mark.parametrize("cfg", [TINY.with_(n_layers=6, decode_steps=3), small_bf16(n_layers=6, batch=9)], ids=["fp32", "bf16"])
+def test_per_sequence_forced_exits(cfg):
+    """Mixed forced exit layers: sequences leave one by one; their K/V above their own exit layer is filled from
+    their own hidden state (checked slot by slot against the oracle by the lock-step comparison)."""
+    g = torch.Generator().manual_seed(19)
+    forced = torch.randint(1, cfg.n_layers + 1, (4, cfg.batch), generator=g, dtype=torch.int32)
+    forced[1] = 3                                  # everybody at layer 3: coincides with Algorithm 1
+    forced[2] = cfg.n_layers                       # nobody leaves early
+    forced[3, 0] = 1                               # one sequence leaves at once, the rest later
+    stats = lockstep(cfg, seed=42, steps=4, forced_seq=forced, heads=2)
+    assert stats["L"] == [int(forced[s].max()) for s in range(4)]
