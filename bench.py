@@ -73,6 +73,9 @@ def main():
     ap.add_argument("--modes", default="ee,full,never",
                     help="ee: the config's softmax-response heads; full: no heads; never: heads that never fire; "
                          "sim / cls: hidden-state-similarity / dedicated-classifier checks (no LM head in the loop)")
+    ap.add_argument("--per-sequence", action="store_true",
+                    help="modes ee, sim and cls let each sequence leave at its own layer (extension of Algorithm 1) "
+                         "instead of the whole batch leaving together")
     ap.add_argument("--sim-threshold", type=float, default=0.0, help="threshold of mode sim (0: a built-in per-config value)")
     ap.add_argument("--cls-threshold", type=float, default=0.0, help="threshold of mode cls (0: a built-in per-config value)")
     ap.add_argument("--synthetic-kv", action="store_true",
@@ -180,8 +183,9 @@ def main():
             torch.index_select(forced_all, 0, step_no % forced_all.shape[0], out=forced_cur.view(1, -1))
             step_no.add_(1)
             f = forced_cur
-        B.ee_decode_iteration(variants.get(mode, model), cache, batch, thr, f, mode != "full", out_tok, out_exit, out_L,
-                              None, None, ws)
+        how = B.EE_EXIT_NONE if mode == "full" else (
+            B.EE_EXIT_PER_SEQUENCE if args.per_sequence and mode != "never" else B.EE_EXIT_BATCH)
+        B.ee_decode_iteration(variants.get(mode, model), cache, batch, thr, f, how, out_tok, out_exit, out_L, None, None, ws)
         L_hist.scatter_add_(0, out_L.long(), one1)
         E_hist.scatter_add_(0, out_exit.long(), oneB)
         torch.add(out_tok, 0, out=tokens)          # next iteration consumes the tokens just produced
@@ -312,7 +316,8 @@ def main():
                    "exit_every": cfg.exit_every, "kv_block": cfg.block_size, "mode": head_mode,
                    "context_lens": [int(lens.min()), int(lens.max())], "kv": "synthetic" if synthetic_kv else "prefilled",
                    "forced_exit_mean": args.forced_mean or None,
-                   "launch": "eager" if args.no_graph else "hip_graph"},
+                   "launch": "eager" if args.no_graph else "hip_graph",
+                   "exit_rule": "per_sequence" if args.per_sequence else "batch (Algorithm 1)"},
         "modes": results,
         "speedup_ee_vs_full": (results["ee"]["tokens_per_s"] / results["full"]["tokens_per_s"])
         if "ee" in results and "full" in results else None,
