@@ -16,11 +16,9 @@ from gpu_harness import F64, GpuRun, assert_close_scaled, check_confidences, nea
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
 
-def one_iteration_case(cfg, seed, sample, forced=None, kv_scale=0.5, threshold=None, expect_early=None):
-    """Synthetic cache contents (no prefill), ONE decode iteration on the GPU over the whole batch; the oracle runs
-    the sampled sequences with the GPU's batch exit layer imposed through forced exits of the remaining ones."""
-    tol = tol_of(cfg)
-    lam = cfg.threshold if threshold is None else threshold
+def setup_case(cfg, seed, sample, kv_scale=0.5):
+    """Model, synthetic cache contents (generated per layer on the GPU, handed to both sides), one token per
+    sequence.  Returns (run, w_cpu, lens, tokens, Ks_s, Vs_s): the last two are the sampled sequences' dense K/V."""
     n, Bsz = cfg.n_layers, cfg.batch
     w = W.make_weights(cfg, seed=seed, device="cuda", gain_jitter=0.1)
     lens = W.make_context_lens(cfg, seed=seed)
@@ -28,8 +26,6 @@ def one_iteration_case(cfg, seed, sample, forced=None, kv_scale=0.5, threshold=N
     w_cpu = W.weights_to(w, "cpu")
     del w
     max_ctx = int(lens.max()) + 1
-    # cache contents: generated per layer on the GPU, handed to both sides
-    sub_lens = lens[sample]
     Ks_s, Vs_s = [], []
     for i in range(n):
         one = cfg.with_(n_layers=1)
@@ -40,6 +36,17 @@ def one_iteration_case(cfg, seed, sample, forced=None, kv_scale=0.5, threshold=N
         Vs_s.append(Vd[0][sample].cpu())
         del Kd, Vd
     tokens = torch.randint(0, cfg.vocab, (Bsz,), generator=torch.Generator().manual_seed(seed), dtype=torch.int32)
+    return run, w_cpu, lens, tokens, Ks_s, Vs_s
+
+
+def one_iteration_case(cfg, seed, sample, forced=None, kv_scale=0.5, threshold=None, expect_early=None):
+    """Synthetic cache contents (no prefill), ONE decode iteration on the GPU over the whole batch; the oracle runs
+    the sampled sequences with the GPU's batch exit layer imposed through forced exits of the remaining ones."""
+    tol = tol_of(cfg)
+    lam = cfg.threshold if threshold is None else threshold
+    n, Bsz = cfg.n_layers, cfg.batch
+    run, w_cpu, lens, tokens, Ks_s, Vs_s = setup_case(cfg, seed, sample, kv_scale)
+    sub_lens = lens[sample]
     g_tok, g_exit, g_L, g_conf, g_hid = run.step(tokens, lens.long(), lam, forced=forced)
     assert g_L == int(g_exit.max()), "batch exit layer must be the largest per-sequence exit layer"
     if expect_early is not None:
@@ -88,12 +95,13 @@ def oracle_with_imposed_L(m, cache, tokens, pos, lam, forced, L, trace):
     conf_log = torch.full((n, Bs), float("nan"), dtype=F64)
     trace["h"] = []
     for i in range(1, L + 1):
+        h_prev = h
         h = O.layer_forward(m, i, h, cache, pos)
         trace["h"].append(h.clone())
         if O.has_exit_head(m, i):
             rows = [b for b in range(Bs) if not status[b]]
             if rows:
-                c, _ = O.exit_check(m, i, h, rows)
+                c, _ = O.exit_check(m, i, h, rows, h_prev)
                 conf = {b: float(c[r]) for r, b in enumerate(rows)}
                 for b in rows:
                     conf_log[i - 1, b] = conf[b]
@@ -105,9 +113,60 @@ def oracle_with_imposed_L(m, cache, tokens, pos, lam, forced, L, trace):
     return O.transform_to_tokens(m, h), torch.tensor(exit_layer, dtype=torch.int32), L
 
 
+def per_sequence_case(cfg, seed, sample, forced, kv_scale=0.5):
+    """Per-sequence exit at a configuration's shape: with this rule no sequence depends on its batch mates, so the
+    oracle simply runs the sampled sequences as a batch of their own."""
+    tol = tol_of(cfg)
+    n = cfg.n_layers
+    run, w_cpu, lens, tokens, Ks_s, Vs_s = setup_case(cfg, seed, sample, kv_scale)
+    sub_lens = lens[sample]
+    g_tok, g_exit, g_L, g_conf, g_hid = run.step(tokens, lens.long(), cfg.threshold, forced=forced, heads=2)
+    if cfg.exit_every == 1:   # a check after every layer but the last: forced layers come back as given
+        assert torch.equal(g_exit, torch.clamp(forced, max=n)), "forced exit layers must come back as given"
+    assert g_L == int(g_exit.max())
+    m = O.model_from_config(cfg, w_cpu)
+    oc = O.DenseKV.from_tensors(Ks_s, Vs_s, sub_lens, cfg.dtype)
+    tr = {}
+    o_tok, o_exit, o_L = O.decode_iteration_freeze(m, oc, tokens[sample], sub_lens.long(), cfg.threshold,
+                                                   forced_exit_layer=forced[sample], trace=tr)
+    assert torch.equal(o_exit, g_exit[sample])
+    assert_close_scaled(g_hid[sample], tr["h_exit"], tol, "each sequence's own exit hidden state", dim=-1)
+    z = O.head_logits(m, tr["h_exit"])
+    for r, b in enumerate(sample):
+        if int(g_tok[b]) != int(o_tok[r]):
+            top = torch.topk(z[r], 2).values
+            assert float(top[0] - top[1]) <= tol * float(z[r].abs().max()), f"token of sequence {b}"
+    for i in range(1, n + 1):
+        for r, b in enumerate(sample):
+            k, v = run.kv_at(i, b, int(lens[b]))
+            assert_close_scaled(k, oc.K[i - 1][r, int(lens[b])], tol, f"K layer {i} sequence {b}")
+            assert_close_scaled(v, oc.V[i - 1][r, int(lens[b])], tol, f"V layer {i} sequence {b}")
+    return g_L
+
+
+def test_per_sequence_exit_at_7b_width_batch32_and_batch256():
+    """Sequences leaving one by one at the 7B width: batch 32 (streaming projection kernel) and batch 256 with
+    ragged contexts and shuffled blocks (tiled kernel); sampled sequences cover an early, a middle and a late exit."""
+    cfg = W.reduced(W.CONFIGS[1], n_layers=5)
+    forced = torch.tensor([1 + (b * 7) % 5 for b in range(cfg.batch)], dtype=torch.int32)
+    forced[0], forced[13], forced[31] = 1, 3, 5
+    assert per_sequence_case(cfg, seed=7, sample=[0, 13, 31], forced=forced) == 5
+    cfg = W.reduced(W.CONFIGS[2], n_layers=4)
+    forced = torch.tensor([1 + (b * 5) % 3 for b in range(cfg.batch)], dtype=torch.int32)      # everybody by layer 3
+    forced[0], forced[100], forced[255] = 1, 2, 3
+    assert per_sequence_case(cfg, seed=8, sample=[0, 100, 255], forced=forced) == 3
+
+
 def test_config1_llama7b_width_batch32_depth4():
     cfg = W.reduced(W.CONFIGS[1], n_layers=4, logit_scale=4.0)       # logit scale raised so exits happen by layer 3
     one_iteration_case(cfg, seed=1, sample=[0, 13, 31])
+
+
+@pytest.mark.parametrize("conf_mode,threshold", [(2, 0.85), (3, 0.6)])
+def test_config1_width_headless_measures(conf_mode, threshold):
+    """Hidden-state similarity and classifier checks at the 7B width (no LM head inside the loop)."""
+    cfg = W.reduced(W.CONFIGS[1], n_layers=6, conf_mode=conf_mode, threshold=threshold)
+    one_iteration_case(cfg, seed=9, sample=[0, 13, 31])
 
 
 def test_config2_batch256_ragged_shuffled_depth3():
