@@ -90,6 +90,8 @@ struct Workspace {
   int32_t* tile_cnt;  // [(d/32) * Mpad/32] arrival counters of the accumulate epilogue (directly behind rowsq)
   size_t zero_count;  // floats from rowsq on that must be zero when an iteration starts
   bf16_t* fill_x;     // [n][Mpad][d]
+  float* split_scratch;     // [d/32][1024] meeting place of the QKV tiles that two workgroups share (zeroed with rowsq)
+  int32_t* split_counters;  // [d/32]
   float* dots;        // [n][Mpad] per-layer row dot products of the head-less confidence measures (zeroed with rowsq)
   float* hprev;       // bf16: [d][Mpad], fp32: [B][d]: hidden state before the current layer (similarity measure)
   float* msr;         // fp32: [3][B] sums of the head-less confidence measures
@@ -118,10 +120,13 @@ Workspace carve(const ee_model_desc& D, int B, void* base) {
     w.xT = w.xH ? w.xH + d * Mpad : nullptr;
     w.aoT = c.take<bf16_t>(d * Mpad);
     w.actT = c.take<bf16_t>(f * Mpad);
-    w.zero_count = (2 * n + 2) * Mpad + (d / 32) * (Mpad / 32) + n * Mpad;
+    const size_t split_words = Mpad == 32 ? (d / 32) * 1025 : 0;   // only batches of one tile split QKV tiles
+    w.zero_count = (2 * n + 2) * Mpad + (d / 32) * (Mpad / 32) + n * Mpad + split_words;
     w.rowsq = c.take<float>(w.zero_count);
     w.tile_cnt = reinterpret_cast<int32_t*>(w.rowsq ? w.rowsq + (2 * n + 2) * Mpad : nullptr);
     w.dots = w.rowsq ? w.rowsq + (2 * n + 2) * Mpad + (d / 32) * (Mpad / 32) : nullptr;
+    w.split_scratch = (w.rowsq && split_words) ? w.dots + n * Mpad : nullptr;
+    w.split_counters = reinterpret_cast<int32_t*>(w.split_scratch ? w.split_scratch + (d / 32) * 1024 : nullptr);
     w.fill_x = c.take<bf16_t>(n * Mpad * d);
     w.hprev = c.take<float>(d * Mpad);
   } else {
@@ -446,6 +451,11 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       {
         ProfScope ps(EE_K_QKV, i, st);
         GemmShape gq{L.w_qkv, w.xT, d, B, 0, 3 * d / 32, D.head_dim / 2, 1};
+        if (w.split_scratch && d / 16 >= 8) {   // V tiles (the last third) halved along the contraction
+          gq.split_tiles = d / 32;
+          gq.split_scratch = w.split_scratch;
+          gq.split_counters = w.split_counters;
+        }
         QkvEpi qe = make_qkv_epi(D, *cache, *batch, w, i, w.q);
         qe.skip = left;
         launch_gemm_qkv_bf16(gq, qe, run_layers, st);

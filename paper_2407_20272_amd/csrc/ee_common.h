@@ -206,6 +206,11 @@ struct GemmShape {
   int n_tiles;      // tiles to compute
   int pair_stride;  // row order of the packed matrix
   int ksplit;       // workgroups along K (> 1 only with the accumulate epilogue)
+  // QKV projection with one batch tile: the last split_tiles tiles are each computed by two workgroups (half the
+  // contraction each, dispatched first) that meet in split_scratch; see gemm_mfma.hip.  0 = off.
+  int split_tiles;
+  float* split_scratch;      // [split_tiles][1024] floats, zero before the launch, left at zero
+  int32_t* split_counters;   // [split_tiles], zero before the launch, left at zero
 };
 void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st);
 void launch_gemm_acc_bf16(const GemmShape& g, const AccEpi& e, Pred pred, hipStream_t st);

@@ -58,7 +58,7 @@ __device__ inline bool fill_needed(const QkvEpi& e, int M, int layer, Lds& s) {
 // the upper row group): the two rows that an epilogue needs together always sit in the same thread.
 template <class Epi>
 __device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, const GemmShape& g, const Epi& e, Lds& s,
-                                   int wave, int lane) {
+                                   int wave, int lane, bool half_tile = false) {
   __syncthreads();
 #pragma unroll
   for (int a = 0; a < 16; ++a) s.red[wave][a][lane] = acc[a];
@@ -140,6 +140,30 @@ __device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, con
       }
     }
   } else {
+    if constexpr (std::is_same<Epi, QkvEpi>::value) {
+      if (half_tile) {
+        // This workgroup summed half of the contraction; its partner the other half.  Both add their halves into
+        // a zeroed scratch tile with device-scope atomics, wait until the adds are performed and bump the tile's
+        // counter; the second to arrive takes the sums back out (leaving zeros) and finishes the tile.  Two
+        // addends, so the result does not depend on who comes first.
+        const int tl = nt - (g.tile_begin + g.n_tiles - g.split_tiles);
+        float* sc = g.split_scratch + (size_t)tl * 1024 + threadIdx.x;
+        unsafeAtomicAdd(sc, vlo[0]);
+        unsafeAtomicAdd(sc + 256, vhi[0]);
+        unsafeAtomicAdd(sc + 512, vlo[1]);
+        unsafeAtomicAdd(sc + 768, vhi[1]);
+        __builtin_amdgcn_s_waitcnt(0);
+        __syncthreads();
+        if (threadIdx.x == 0) s.flag = atomicAdd(g.split_counters + tl, 1);
+        __syncthreads();
+        if (s.flag == 0) return;
+        vlo[0] = atomicExch(sc, 0.0f);
+        vhi[0] = atomicExch(sc + 256, 0.0f);
+        vlo[1] = atomicExch(sc + 512, 0.0f);
+        vhi[1] = atomicExch(sc + 768, 0.0f);
+        if (threadIdx.x == 0) g.split_counters[tl] = 0;
+      }
+    }
     if (m < g.M) {
 #pragma unroll
       for (int ai = 0; ai < 2; ++ai) {
@@ -218,10 +242,16 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nt = g.tile_begin + blockIdx.x;
+  // Tiles that two workgroups share come first in the grid (two consecutive block indices per tile, each half of
+  // the contraction): they are done, and their meeting in scratch memory is over, while the whole tiles still
+  // stream.  With 384 tiles on 256 compute units this turns two rounds of workgroups into one and a half.
+  const int bx = blockIdx.x;
+  const bool half_tile = bx < 2 * g.split_tiles;
+  const int nt = half_tile ? g.tile_begin + g.n_tiles - g.split_tiles + (bx >> 1) : g.tile_begin + bx - 2 * g.split_tiles;
+  const int nslices = half_tile ? 2 : 1;
   const int k_steps = g.K >> 4;
-  const int chunks = gridDim.y * NW;
-  const int c = blockIdx.y * NW + wave;
+  const int chunks = gridDim.y * nslices * NW;
+  const int c = (blockIdx.y * nslices + (half_tile ? (bx & 1) : 0)) * NW + wave;
   const int ks0 = (int)((long)k_steps * c / chunks);
   const int ks1 = (int)((long)k_steps * (c + 1) / chunks);
   const int m_tiles = (g.M + 31) >> 5;
@@ -261,7 +291,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
       frag_mma(A, acc);
     }
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) tile_finish(acc[mt], nt, mt0 + mt, g, e, s, wave, lane);
+    for (int mt = 0; mt < MT; ++mt) tile_finish(acc[mt], nt, mt0 + mt, g, e, s, wave, lane, half_tile);
   }
 }
 
@@ -536,7 +566,7 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
     hipLaunchKernelGGL((gemm_tiled_kernel<4, 1, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
     return;
   }
-  dim3 grid(g.n_tiles, g.ksplit, nz);
+  dim3 grid(g.n_tiles + g.split_tiles, g.ksplit, nz);   // split tiles take two workgroups each (one batch tile only)
   switch (pick_mt(g.M, 4)) {
     case 4:
       hipLaunchKernelGGL((gemm_mfma_kernel<4, 2, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
