@@ -109,6 +109,12 @@ typedef struct ee_batch {
   const int32_t* block_tables; /* dev [B][max_blocks]: physical block of each logical block              */
   int32_t max_blocks;          /* row pitch of block_tables                                              */
   int32_t max_context;         /* host-side upper bound of context_lens[b] + 1 (sizes the attention grid) */
+  const int32_t* row_table;    /* dev [B] or NULL.  NULL: row b of the batch uses row b of block_tables.  Else
+                                  row b uses row row_table[b]: several rows may then share one sequence's block
+                                  table at consecutive positions p, p+1, .. (a chunk of a prompt pushed through
+                                  in one call: every row caches its K/V before any row attends, and row b
+                                  attends positions 0..context_lens[b], so the chunk is causal).  Only with
+                                  EE_EXIT_NONE, and with ee_paged_attention_decode.                          */
 } ee_batch;
 
 const char* ee_last_error(void);

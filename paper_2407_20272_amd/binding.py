@@ -45,7 +45,8 @@ class ee_kv_cache(C.Structure):
 
 class ee_batch(C.Structure):
     _fields_ = [("batch", C.c_int32), ("tokens", C.c_void_p), ("context_lens", C.c_void_p),
-                ("block_tables", C.c_void_p), ("max_blocks", C.c_int32), ("max_context", C.c_int32)]
+                ("block_tables", C.c_void_p), ("max_blocks", C.c_int32), ("max_context", C.c_int32),
+                ("row_table", C.c_void_p)]
 
 
 class EEError(RuntimeError):
@@ -209,11 +210,12 @@ class PagedKV:
 
 
 def make_batch(tokens: Optional[torch.Tensor], context_lens: torch.Tensor, block_tables: torch.Tensor,
-               max_context: int) -> ee_batch:
+               max_context: int, row_table: Optional[torch.Tensor] = None) -> ee_batch:
     B = int(context_lens.shape[0])
     b = ee_batch(B, _ptr(_i32(tokens)) if tokens is not None else None, _ptr(_i32(context_lens)),
-                 _ptr(_i32(block_tables)), int(block_tables.shape[1]) if block_tables.dim() == 2 else 0, max_context)
-    b._keep = (tokens, context_lens, block_tables)   # the record only holds raw pointers: keep the tensors alive
+                 _ptr(_i32(block_tables)), int(block_tables.shape[1]) if block_tables.dim() == 2 else 0, max_context,
+                 _ptr(_i32(row_table)) if row_table is not None else None)
+    b._keep = (tokens, context_lens, block_tables, row_table)   # the record only holds raw pointers: keep the tensors alive
     return b
 
 

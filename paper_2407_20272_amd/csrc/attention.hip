@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int sub = lane % LPT;              // which EPL-wide slice of the head this lane holds
   const int grp = lane / LPT;              // which token of a load this lane sees
-  const int32_t* table = a.block_tables + (size_t)b * a.max_blocks;
+  const int32_t* table = a.block_tables + (size_t)(a.row_table ? a.row_table[b] : b) * a.max_blocks;
 
   extern __shared__ int32_t tbl[];
   if (pred_skip(pred)) return;

@@ -230,6 +230,7 @@ QkvEpi make_qkv_epi(const ee_model_desc& D, const ee_kv_cache& C, const ee_batch
   e.v_pool = reinterpret_cast<char*>(C.v_pool) + lb;
   e.context_lens = Bt.context_lens;
   e.block_tables = Bt.block_tables;
+  e.row_table = Bt.row_table;
   e.fill_from = nullptr;
   e.fill_from_stride = 0;
   e.layer = layer;
@@ -396,6 +397,8 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   if ((rc = check_workspace(D, B, workspace, workspace_bytes))) return rc;
   // Confidence measures that need no LM head (Section 2.1): 2 = similarity of consecutive hidden states,
   // 3 = dedicated classifier.  Both are one dot product per row, taken while the next operand is prepared.
+  if (batch->row_table && use_exit_heads != EE_EXIT_NONE)
+    EE_FAIL(EE_ERR_INVALID_ARG, "row_table (several rows per sequence) only goes with EE_EXIT_NONE");
   if (use_exit_heads < 0 || use_exit_heads > EE_EXIT_PER_SEQUENCE)
     EE_FAIL(EE_ERR_INVALID_ARG, "use_exit_heads must be EE_EXIT_NONE, EE_EXIT_BATCH or EE_EXIT_PER_SEQUENCE");
   const bool dotmode = use_exit_heads && D.conf_mode >= 2;
@@ -437,7 +440,8 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     const ee_layer_weights& L = model->layers[i - 1];
     const size_t pool_off = pool_layer_elems(D, *cache) * elem_bytes(D) * (size_t)(i - 1);
     AttnArgs at{w.q, reinterpret_cast<char*>(cache->k_pool) + pool_off, reinterpret_cast<char*>(cache->v_pool) + pool_off,
-                batch->context_lens, batch->block_tables, batch->max_blocks, B, D.n_heads, D.head_dim, nullptr, 0, left};
+                batch->context_lens, batch->block_tables, batch->max_blocks, B, D.n_heads, D.head_dim, nullptr, 0, left,
+                batch->row_table};
     const bool head_here = use_exit_heads && has_head(D, i);
     if (bf) {
       if (i == 1) {
@@ -702,7 +706,7 @@ int ee_paged_attention_decode(const ee_model_desc* desc, const ee_kv_cache* cach
   const size_t off = pool_layer_elems(*desc, *cache) * elem_bytes(*desc) * (size_t)(layer - 1);
   AttnArgs at{q, reinterpret_cast<char*>(cache->k_pool) + off, reinterpret_cast<char*>(cache->v_pool) + off,
               batch->context_lens, batch->block_tables, batch->max_blocks, batch->batch, desc->n_heads, desc->head_dim,
-              out, 0, nullptr};
+              out, 0, nullptr, batch->row_table};
   const Pred always{nullptr, 0};
   if ((rc = launch_attention(at, desc->dtype, always, reinterpret_cast<hipStream_t>(stream)))) return rc;
   EE_HIP(hipGetLastError());

@@ -69,6 +69,7 @@ struct QkvEpi {                 // rotary embedding + paged cache write (+ q out
   void* v_pool;
   const int32_t* context_lens;  // [M]
   const int32_t* block_tables;  // [M][max_blocks]
+  const int32_t* row_table;     // nullptr, or [M]: row m uses row row_table[m] of block_tables
   const int32_t* fill_from;     // nullptr, or [M]: only rows with fill_from[m] < layer are written (KV filling)
   int fill_from_stride;         // 1 = per row, 0 = one value for the whole batch
   int layer;
@@ -248,6 +249,7 @@ struct AttnArgs {
   void* out;                    // fp32 plain [B][H*dh], or XT bf16 [Mpad][H*dh]
   int out_xt;                   // 1: XT bf16
   const int32_t* skip;          // nullptr, or [B]: sequences with skip[b] != 0 are not attended (they have left)
+  const int32_t* row_table;     // nullptr, or [B]: row b uses row row_table[b] of block_tables
 };
 int launch_attention(const AttnArgs& a, int dtype, Pred pred, hipStream_t st);
 

@@ -46,7 +46,7 @@ __device__ inline void epi_qkv(const QkvEpi& e, int m, int f_lo, float lo, float
     }
     return;
   }
-  const int blk = e.block_tables[(size_t)m * e.max_blocks + (p >> 4)];
+  const int blk = e.block_tables[(size_t)(e.row_table ? e.row_table[m] : m) * e.max_blocks + (p >> 4)];
   const size_t at = (((size_t)blk * e.n_heads + head) * 16 + (p & 15)) * dh + j;
   T* pool = reinterpret_cast<T*>(which == 1 ? e.k_pool : e.v_pool);
   store_elem(pool + at, lo);

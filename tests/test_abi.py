@@ -100,6 +100,8 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert "w_cls" in B.ee_last_error()
     m2 = B.ee_model(desc(conf_mode=2), 1, 1, 1, layers)
     assert L.ee_exit_check(C.byref(m2), 1, 1, 2, 0.5, None, 1, 1, 1, 1, 1, None, None, 256, 1 << 30, None) == B.EE_ERR_UNSUPPORTED
+    # several rows per sequence (prompt chunks) only without exit checks
+    assert call(batch=B.ee_batch(2, 1, 1, 1, 2, 17, 1)) == B.EE_ERR_INVALID_ARG and "row_table" in B.ee_last_error()
     # the other entry points validate the same way
     assert L.ee_exit_check(C.byref(model), 9, 1, 2, 0.5, None, 1, 1, 1, 1, 1, None, None, 256, 1 << 30, None) == B.EE_ERR_INVALID_ARG
     assert L.ee_exit_check(C.byref(model), 1, None, 2, 0.5, None, 1, 1, 1, 1, 1, None, None, 256, 1 << 30, None) == B.EE_ERR_INVALID_ARG
