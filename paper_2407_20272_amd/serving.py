@@ -148,8 +148,9 @@ class Engine:
         filling = [r for r in self.active if r.consumed < len(r.prompt)]
         if filling:
             tokens, pos, row_table, reqs, last_row = [], [], [], [], {}
+            share = max(self.chunk, self.max_rows // len(filling))   # few prompts in flight: longer chunks each
             for r in filling:
-                take = min(self.chunk, len(r.prompt) - r.consumed, self.max_rows - len(tokens))
+                take = min(share, len(r.prompt) - r.consumed, self.max_rows - len(tokens))
                 if take <= 0:
                     break
                 reqs.append(r)
