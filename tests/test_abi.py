@@ -110,6 +110,9 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert L.ee_kv_fill(C.byref(model), C.byref(cache), C.byref(batch), 1, 1, 256, 8, None) == B.EE_ERR_WORKSPACE
     assert L.ee_paged_attention_decode(C.byref(d), C.byref(cache), 0, 1, C.byref(batch), 1, None, 0, None) == B.EE_ERR_INVALID_ARG
     assert L.ee_paged_attention_decode(C.byref(d), C.byref(cache), 1, None, C.byref(batch), 1, None, 0, None) == B.EE_ERR_INVALID_ARG
+    wide = B.ee_batch(2, 1, 1, 1, 20000, 17)                                          # block table wider than the LDS copy
+    assert L.ee_paged_attention_decode(C.byref(d), C.byref(cache), 1, 1, C.byref(wide), 1, None, 0, None) == B.EE_ERR_UNSUPPORTED
+    assert "max_blocks" in B.ee_last_error()
     assert L.ee_pack_weight(1, 33, 16, 0, 0, 1, None) == B.EE_ERR_SHAPE
     assert L.ee_pack_weight(1, 64, 16, 1, 24, 1, None) == B.EE_ERR_SHAPE
     assert L.ee_pack_weight(1, 64, 16, 9, 0, 1, None) == B.EE_ERR_INVALID_ARG

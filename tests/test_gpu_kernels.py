@@ -56,6 +56,31 @@ def test_attention_ragged_lengths(dtype, dh):
     run_attention(cfg, [0, 1, 14, 15, 16, 17, 31, 32, 63, 64, 65, 100, 257, 5], seed=11)
 
 
+def test_attention_rows_sharing_one_block_table():
+    """Several batch rows at consecutive positions of ONE sequence (row_table): each attends positions 0..its own."""
+    cfg = cfg_of("bf16", 128, 2).with_(batch=1, shuffled_blocks=True)
+    L = 70                                                      # the sequence holds positions 0..L
+    lens1 = torch.tensor([L], dtype=torch.int32)
+    Ks, Vs = W.make_dense_kv(cfg, lens1 + 1, L + 1, seed=14, device="cuda")
+    bt, nb = W.make_block_tables(lens1, 1, 16, True, 14, spare_blocks=1)
+    cache = B.PagedKV(cfg, nb)
+    for i in range(cfg.n_layers):
+        cache.k[i] = W.dense_to_paged(Ks[i], bt, nb, 16)
+        cache.v[i] = W.dense_to_paged(Vs[i], bt, nb, 16)
+    pos = torch.tensor([0, 15, 16, 17, 40, 69, 70], dtype=torch.int32)          # rows of the one sequence
+    R = len(pos)
+    q = torch.randn(R, cfg.n_heads, cfg.head_dim, generator=torch.Generator().manual_seed(14)) * 1.5
+    out = torch.zeros(R, cfg.n_heads, cfg.head_dim, device="cuda")
+    batch = B.make_batch(None, pos.cuda(), bt.cuda(), L + 1, torch.zeros(R, dtype=torch.int32).cuda())
+    B.ee_paged_attention_decode(B.make_desc(cfg), cache, 2, q.cuda(), batch, out)
+    torch.cuda.synchronize()
+    Kc, Vc = Ks[1].cpu(), Vs[1].cpu()
+    for r in range(R):
+        n = int(pos[r]) + 1
+        want = O.attention_decode(q[r].to(F64), Kc[0, :n], Vc[0, :n])
+        assert_close_scaled(out[r].cpu(), want, tol_of(cfg), f"row {r} at position {n - 1}")
+
+
 def test_attention_single_sequence_and_sequential_blocks():
     run_attention(cfg_of("bf16", 128, 2), [300], seed=12, shuffled=False)
     run_attention(cfg_of("fp32", 64, 4), [47], seed=13, shuffled=False)
