@@ -205,3 +205,11 @@ def test_per_sequence_forced_exits(cfg):
     forced[3, 0] = 1                               # one sequence leaves at once, the rest later
     stats = lockstep(cfg, seed=42, steps=4, forced_seq=forced, heads=2)
     assert stats["L"] == [int(forced[s].max()) for s in range(4)]
+
+
+@pytest.mark.parametrize("heads", [1, 2])
+def test_batch_of_one_and_prompts_ending_on_block_boundaries(heads):
+    """Degenerate sizes: a single sequence, and prompts whose next position opens a new 16-token block."""
+    lockstep(small_bf16(batch=1, prompt_len=16, min_prompt_len=16, threshold=0.4), seed=61, steps=3, heads=heads)
+    lockstep(small_bf16(batch=3, prompt_len=15, min_prompt_len=15, threshold=0.4), seed=62, steps=3, heads=heads)
+    lockstep(TINY.with_(batch=1, prompt_len=31, min_prompt_len=31, decode_steps=3), seed=63, steps=3, heads=heads)
