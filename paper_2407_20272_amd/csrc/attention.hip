@@ -243,10 +243,199 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Several batch rows of ONE sequence per workgroup (a chunk of a prompt pushed through the decode step: rows
+// that share a block table).  A workgroup owns R consecutive batch rows of one head; rows of the same sequence
+// form a run, and the run's K/V blocks are streamed once and multiplied against every row of the run, each row
+// masking the positions after its own.  A workgroup whose rows span several sequences walks its runs one after
+// the other.  Per row the arithmetic is that of the single-row kernel above; only the K/V traffic is shared.
+// ---------------------------------------------------------------------------------------------------------
+template <class T, int DH, int R, bool OUT_XT>
+__global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a, Pred pred) {
+  constexpr int EPL = Elems<T>::N;
+  constexpr int LPT = DH / EPL;
+  constexpr int TPL = 64 / LPT;
+  constexpr int LPB = 16 / TPL;
+  extern __shared__ int32_t tbl[];
+  if (pred_skip(pred)) return;
+
+  const int head = blockIdx.x, row0 = blockIdx.y * R;
+  const int nrows = min(R, a.B - row0);
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int sub = lane % LPT, grp = lane / LPT;
+
+  int seq[R], npos[R];
+  float q[R][EPL], m_run[R], l_run[R], o[R][EPL];
+  const float sc = 1.4426950408889634f / sqrtf((float)DH);
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const bool valid = r < nrows;
+    seq[r] = valid ? a.row_table[row0 + r] : -1;
+    npos[r] = valid ? min(a.context_lens[row0 + r] + 1, a.max_blocks * 16) : 0;
+    const float* qp = a.q + ((size_t)(valid ? row0 + r : row0) * a.n_heads + head) * DH + sub * EPL;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) {
+      q[r][i] = qp[i] * sc;
+      o[r][i] = 0.0f;
+    }
+    m_run[r] = NEG_BIG;
+    l_run[r] = 0.0f;
+  }
+
+  const size_t head_off = (size_t)head * 16 * DH;
+  const size_t block_elems = (size_t)a.n_heads * 16 * DH;
+  const T* kbase = reinterpret_cast<const T*>(a.k_pool) + head_off + (size_t)grp * DH + sub * EPL;
+  const T* vbase = reinterpret_cast<const T*>(a.v_pool) + head_off + (size_t)grp * DH + sub * EPL;
+  struct Blk {
+    uint4 k[LPB], v[LPB];
+  };
+
+  int r_begin = 0;
+  while (r_begin < nrows) {
+    // the run: rows r_begin .. r_end-1 of one sequence (uniform over the workgroup)
+    int r_end = r_begin + 1, run_ctx = 0, run_seq = -1;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      if (r == r_begin) run_seq = seq[r];
+#pragma unroll
+    for (int r = 1; r < R; ++r)
+      if (r == r_end && r < nrows && seq[r] == run_seq) ++r_end;
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+      if (r >= r_begin && r < r_end) run_ctx = max(run_ctx, npos[r]);
+    const int n_blocks = (run_ctx + 15) >> 4;
+    const int32_t* table = a.block_tables + (size_t)run_seq * a.max_blocks;
+    __syncthreads();   // the previous run's table is no longer read
+    for (int i = threadIdx.x; i < n_blocks; i += blockDim.x) tbl[i] = table[i];
+    __syncthreads();
+
+    auto fetch = [&](Blk& x, int lb) {
+      const size_t off = (size_t)tbl[lb] * block_elems;
+#pragma unroll
+      for (int i = 0; i < LPB; ++i) {
+        x.k[i] = load_stream(kbase + off + (size_t)i * TPL * DH);
+        x.v[i] = load_stream(vbase + off + (size_t)i * TPL * DH);
+      }
+    };
+    auto consume = [&](const Blk& x, int lb) {
+      float kf[LPB][EPL], vf[LPB][EPL];
+#pragma unroll
+      for (int i = 0; i < LPB; ++i) {
+        Elems<T>::unpack(x.k[i], kf[i]);
+        Elems<T>::unpack(x.v[i], vf[i]);
+      }
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        if (r < r_begin || r >= r_end) continue;   // uniform: rows of other runs keep their state
+        float s[LPB];
+        float m_new = m_run[r];
+#pragma unroll
+        for (int i = 0; i < LPB; ++i) {
+          float d = 0.0f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) d = fmaf(q[r][e], kf[i][e], d);
+          d = group_sum<LPT>(d);
+          const int tok = lb * 16 + i * TPL + grp;
+          s[i] = tok < npos[r] ? d : NEG_BIG;
+          m_new = fmaxf(m_new, s[i]);
+        }
+        const float alpha = __builtin_amdgcn_exp2f(m_run[r] - m_new);
+        l_run[r] *= alpha;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) o[r][e] *= alpha;
+#pragma unroll
+        for (int i = 0; i < LPB; ++i) {
+          const int tok = lb * 16 + i * TPL + grp;
+          const float p = tok < npos[r] ? __builtin_amdgcn_exp2f(s[i] - m_new) : 0.0f;
+          l_run[r] += p;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) o[r][e] = fmaf(p, vf[i][e], o[r][e]);
+        }
+        m_run[r] = m_new;
+      }
+    };
+
+    // one block in flight behind the one being multiplied (the multiplies of R rows hide the load)
+    Blk A, B;
+    int lb = wave;
+    if (lb < n_blocks) fetch(A, lb);
+    for (; lb + NW < n_blocks; lb += 2 * NW) {
+      fetch(B, lb + NW);
+      consume(A, lb);
+      if (lb + 2 * NW < n_blocks) fetch(A, lb + 2 * NW);
+      consume(B, lb + NW);
+    }
+    if (lb < n_blocks) consume(A, lb);
+    r_begin = r_end;
+  }
+
+  // merge the lane groups of each wavefront, then the wavefronts, row by row
+  __shared__ float sm[NW][R], sl[NW][R], so[NW][R][DH];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+#pragma unroll
+    for (int x = LPT; x < 64; x <<= 1) {
+      const float m_o = __shfl_xor(m_run[r], x);
+      const float l_o = __shfl_xor(l_run[r], x);
+      const float m_new = fmaxf(m_run[r], m_o);
+      const float wa = __builtin_amdgcn_exp2f(m_run[r] - m_new), wb = __builtin_amdgcn_exp2f(m_o - m_new);
+      l_run[r] = l_run[r] * wa + l_o * wb;
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) {
+        const float o_o = __shfl_xor(o[r][e], x);
+        o[r][e] = o[r][e] * wa + o_o * wb;
+      }
+      m_run[r] = m_new;
+    }
+    if (grp == 0) {
+#pragma unroll
+      for (int e = 0; e < EPL; ++e) so[wave][r][sub * EPL + e] = o[r][e];
+      if (sub == 0) {
+        sm[wave][r] = m_run[r];
+        sl[wave][r] = l_run[r];
+      }
+    }
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < nrows * DH; t += blockDim.x) {
+    const int r = t / DH, c = t - r * DH;
+    float M = sm[0][r];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, sm[w][r]);
+    float L = 0.0f, acc = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float wgt = __builtin_amdgcn_exp2f(sm[w][r] - M);
+      L += sl[w][r] * wgt;
+      acc += so[w][r][c] * wgt;
+    }
+    const float res = acc / L;
+    const int col = head * DH + c;
+    if constexpr (OUT_XT) {
+      reinterpret_cast<bf16_t*>(a.out)[xt_index(row0 + r, col, a.n_heads * DH)] = (bf16_t)res;
+    } else {
+      reinterpret_cast<float*>(a.out)[(size_t)(row0 + r) * a.n_heads * DH + col] = res;
+    }
+  }
+}
+
+// Four rows per workgroup measured best at the 7B shape (eight: 300 registers, one wavefront per SIMD, slower).
+constexpr int ROWS_PER_GROUP = 4;
+
 template <class T, int DH>
 void launch_t(const AttnArgs& a, Pred pred, hipStream_t st) {
-  dim3 grid(a.n_heads, a.B), block(256);
+  dim3 block(256);
   const size_t lds = (size_t)a.max_blocks * sizeof(int32_t);
+  if (a.row_table) {   // rows share sequences: stream every sequence's K/V once per group of rows
+    dim3 grid(a.n_heads, (a.B + ROWS_PER_GROUP - 1) / ROWS_PER_GROUP);
+    if (a.out_xt)
+      hipLaunchKernelGGL((attn_rows_kernel<T, DH, ROWS_PER_GROUP, true>), grid, block, lds, st, a, pred);
+    else
+      hipLaunchKernelGGL((attn_rows_kernel<T, DH, ROWS_PER_GROUP, false>), grid, block, lds, st, a, pred);
+    return;
+  }
+  dim3 grid(a.n_heads, a.B);
   if (a.out_xt)
     hipLaunchKernelGGL((attn_decode_kernel<T, DH, true>), grid, block, lds, st, a, pred);
   else
