@@ -70,9 +70,11 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; invalidates the result)")
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--modes", default="ee,full,never",
+    ap.add_argument("--modes", default="ee,full,never,ee+ps,sim",
                     help="ee: the config's softmax-response heads; full: no heads; never: heads that never fire; "
-                         "sim / cls: hidden-state-similarity / dedicated-classifier checks (no LM head in the loop)")
+                         "sim / cls: hidden-state-similarity / dedicated-classifier checks (no LM head in the loop); "
+                         "a +ps suffix lets each sequence leave at its own layer (extension of Algorithm 1).  "
+                         "The headline value is always mode ee")
     ap.add_argument("--per-sequence", action="store_true",
                     help="modes ee, sim and cls let each sequence leave at its own layer (extension of Algorithm 1) "
                          "instead of the whole batch leaving together")
@@ -177,6 +179,8 @@ def main():
               "cls": args.cls_threshold or CLS_THRESHOLD.get(args.config, 0.9)}
 
     def iteration(mode):
+        per_seq = args.per_sequence or mode.endswith("+ps")
+        mode = mode.split("+")[0]
         thr = thr_of[mode]
         f = None
         if forced_all is not None and mode != "full" and mode != "never":
@@ -184,7 +188,7 @@ def main():
             step_no.add_(1)
             f = forced_cur
         how = B.EE_EXIT_NONE if mode == "full" else (
-            B.EE_EXIT_PER_SEQUENCE if args.per_sequence and mode != "never" else B.EE_EXIT_BATCH)
+            B.EE_EXIT_PER_SEQUENCE if per_seq and mode != "never" else B.EE_EXIT_BATCH)
         B.ee_decode_iteration(variants.get(mode, model), cache, batch, thr, f, how, out_tok, out_exit, out_L, None, None, ws)
         L_hist.scatter_add_(0, out_L.long(), one1)
         E_hist.scatter_add_(0, out_exit.long(), oneB)
@@ -248,7 +252,7 @@ def main():
                     # early exit; the final LM pass (recorded at layer n) only when the loop reached layer n
                     executed = (Lp[it] < n) if cls == "kv_fill" else (layer == 0 or layer <= Lp[it])
                     # measures without an exit head: the one LM-head pass for the tokens (recorded at layer n) always runs
-                    if mode in ("sim", "cls") and layer == n and cls in ("head", "norm", "combine"):
+                    if mode.split("+")[0] in ("sim", "cls") and layer == n and cls in ("head", "norm", "combine"):
                         executed = True
                     if executed:
                         agg[cls][0] += 1
