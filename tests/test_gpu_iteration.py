@@ -213,3 +213,11 @@ def test_batch_of_one_and_prompts_ending_on_block_boundaries(heads):
     lockstep(small_bf16(batch=1, prompt_len=16, min_prompt_len=16, threshold=0.4), seed=61, steps=3, heads=heads)
     lockstep(small_bf16(batch=3, prompt_len=15, min_prompt_len=15, threshold=0.4), seed=62, steps=3, heads=heads)
     lockstep(TINY.with_(batch=1, prompt_len=31, min_prompt_len=31, decode_steps=3), seed=63, steps=3, heads=heads)
+
+
+def test_sixty_four_layers_the_most_the_library_takes():
+    """EE_MAX_LAYERS layers: the per-layer tables of the KV-filling launch are full; exits spread over the depth."""
+    cfg = small_bf16(n_layers=64, d_model=128, n_heads=1, head_dim=128, d_ffn=128, vocab=256, batch=3, prompt_len=6,
+                     min_prompt_len=6, weight_std=0.03, logit_scale=0.05, threshold=0.5)
+    stats = lockstep(cfg, seed=71, steps=2, check_untouched=False)
+    assert all(1 <= L <= 64 for L in stats["L"])

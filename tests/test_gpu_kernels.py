@@ -102,6 +102,11 @@ def test_attention_long_ragged_batch():
     run_attention(cfg, lens, seed=15, sample=[0, 1, 2, 47])
 
 
+def test_attention_very_long_context():
+    """20000 cached tokens (1251 blocks of the table in LDS), one short sequence beside it."""
+    run_attention(cfg_of("bf16", 128, 2), [20000, 7], seed=15)
+
+
 def test_attention_uniform_values_give_their_mean():
     """All keys equal -> uniform weights -> output = mean of V (a closed form, independent of the oracle)."""
     cfg = cfg_of("fp32", 64, 2).with_(batch=1)
