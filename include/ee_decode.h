@@ -148,10 +148,11 @@ size_t ee_workspace_bytes(const ee_model_desc* desc, int32_t max_batch, int32_t 
  *   use_exit_heads    EE_EXIT_NONE (0): full-layer baseline, no exit check is made, output_layer = n.
  *                     EE_EXIT_BATCH (1): Algorithm 1 as above.
  *                     EE_EXIT_PER_SEQUENCE (2): an extension of Algorithm 1 in which each sequence leaves on its
- *                     own: once its status is true, later layers neither cache K/V for it nor attend for it nor
- *                     change its hidden state; the loop still ends at the first layer after which every status
- *                     is true (output_layer = the largest exit layer); K/V of layers above a sequence's OWN exit
- *                     layer are filled from its own exit hidden state, and its token comes from that state.
+ *                     own: once its status is true, later layers neither attend for it nor change its hidden
+ *                     state; the loop still ends at the first layer after which every status is true
+ *                     (output_layer = the largest exit layer); K/V of all layers above a sequence's OWN exit
+ *                     layer are filled from its own exit hidden state (Section 3.2 applied per sequence), and
+ *                     its token comes from that state.
  *   out_tokens        dev [B] int32: greedy token (lowest index on ties).
  *   out_exit_layer    dev [B] int32: first layer whose check accepted the sequence, n_layers if none.
  *   out_batch_exit_layer dev [1] int32: output_layer.

@@ -412,8 +412,11 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   const bool bf = D.dtype == EE_BF16;
   IterState s{w.status, out_exit_layer, w.n_exited, w.done, out_batch_exit_layer};
   // Per-sequence exit (an extension of Algorithm 1): a sequence whose status is set has left.  Layers still run
-  // over the whole batch, but for such a sequence they cache no K/V, attend nothing and leave its hidden state as
-  // it is, so at the end every sequence's column of the residual stream is its own exit hidden state.
+  // over the whole batch, but for such a sequence they attend nothing and leave its hidden state as it is, so at
+  // the end every sequence's column of the residual stream is its own exit hidden state.  The QKV projection of a
+  // later layer i still caches K/V for it: its operand row is RMSNorm(own exit hidden state; layer i's gain), so
+  // what it caches IS the KV filling of layer i for that sequence (Section 3.2) and only the layers above the
+  // batch exit layer are left to the filling launch, as in Algorithm 1.
   const int32_t* left = use_exit_heads == EE_EXIT_PER_SEQUENCE ? w.status : nullptr;
   const Pred run_layers{w.done, 0};  // kernels of the layer loop: only while the batch has not left
   const Pred run_fill{w.done, 1};    // KV filling: only after it has
@@ -461,7 +464,6 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
           gq.split_counters = w.split_counters;
         }
         QkvEpi qe = make_qkv_epi(D, *cache, *batch, w, i, w.q);
-        qe.skip = left;
         launch_gemm_qkv_bf16(gq, qe, run_layers, st);
       }
       {
@@ -514,7 +516,6 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
         launch_rmsnorm_f32(w.h, reinterpret_cast<const float*>(L.g_attn), w.x, B, d, D.rms_eps, run_layers, st);
         SimpleShape gq{reinterpret_cast<const float*>(L.w_qkv), w.x, d, B, 0, 3 * d, D.head_dim / 2};
         QkvEpi qe = make_qkv_epi(D, *cache, *batch, w, i, w.q);
-        qe.skip = left;
         launch_simple_qkv(gq, qe, run_layers, st);
       }
       {
@@ -580,16 +581,10 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     }
   }
 
-  // Algorithm 1, KV cache filling for layers output_layer+1..n (runs only if the batch left early).
-  // Per-sequence exit: every sequence fills the layers above its own exit layer from its own hidden state,
-  // whether or not the whole batch left; layers nobody needs return at once.
-  if (use_exit_heads == EE_EXIT_PER_SEQUENCE) {
-    if (bf)
-      enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, out_exit_layer, 1, rs(0), (size_t)2 * Mpad, out_batch_exit_layer,
-                        always, st);
-    else
-      enqueue_fill_f32(*model, *cache, *batch, w, w.h, out_exit_layer, 1, always, st);
-  } else if (use_exit_heads) {
+  // Algorithm 1, KV cache filling for layers output_layer+1..n (runs only if the batch left early).  With
+  // per-sequence exit the layers between a sequence's own exit layer and output_layer were filled by those
+  // layers' own QKV projections (see above); every column of the residual stream is that sequence's exit state.
+  if (use_exit_heads) {
     if (bf)
       enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, out_batch_exit_layer, 0, rs(0), (size_t)2 * Mpad,
                         out_batch_exit_layer, run_fill, st);
@@ -597,8 +592,6 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       enqueue_fill_f32(*model, *cache, *batch, w, w.h, out_batch_exit_layer, 0, run_fill, st);
   }
 
-  // Algorithm 1, transform_to_tokens.  When the batch left at an exit head, that head's arg max over the same
-  // hidden state already is the token; the LM head is only streamed again when the loop ran to the last layer.
   // With a head-less confidence measure no exit head has produced a token: the LM head then always runs, on the
   // hidden state at output_layer (still in place: later layers were skipped), normalised with that layer's sums.
   {

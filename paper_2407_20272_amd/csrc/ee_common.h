@@ -78,7 +78,6 @@ struct QkvEpi {                 // rotary embedding + paged cache write (+ q out
   const float2* rope;           // [M][dh/2] (cos, sin) of the rotary angles at context_lens[m] (rope_theta > 0)
   const float* rowsq;           // nullptr, or [M] sum of squares of the hidden row: value *= rsqrt(rowsq/d + eps)
   float eps;
-  const int32_t* skip;          // nullptr, or [M]: rows with skip[m] != 0 write nothing (sequences that have left)
 };
 struct AccEpi {                 // h += value
   float* h;

@@ -20,7 +20,6 @@ __device__ inline void store_elem(bf16_t* p, float v) { *p = (bf16_t)v; }
 template <class T>
 __device__ inline void epi_qkv(const QkvEpi& e, int m, int f_lo, float lo, float hi) {
   if (e.fill_from && !(e.fill_from[(size_t)m * e.fill_from_stride] < e.layer)) return;
-  if (e.skip && e.skip[m] != 0) return;
   const float r = row_rinv(e.rowsq, m, e.d_model, e.eps);
   lo *= r;
   hi *= r;
