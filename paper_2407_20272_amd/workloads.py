@@ -16,7 +16,7 @@ from __future__ import annotations
 import dataclasses
 import hashlib
 import math
-from typing import Dict, List, Optional
+from typing import Dict, List
 
 import torch
 
