@@ -92,6 +92,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   const int t0 = (int)threadIdx.x < a.max_blocks ? table[threadIdx.x] : 0;
   const int len = a.context_lens[b];
   const int left = a.skip ? a.skip[b] : 0;
+  const int out_row = a.out_pos ? a.out_pos[b] : b;
   float q[EPL];
   {
     const float* qp = a.q + ((size_t)b * a.n_heads + head) * DH + sub * EPL;
@@ -236,9 +237,9 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
     const float r = acc / L;
     const int col = head * DH + threadIdx.x;
     if constexpr (OUT_XT) {
-      reinterpret_cast<bf16_t*>(a.out)[xt_index(b, col, a.n_heads * DH)] = (bf16_t)r;
+      reinterpret_cast<bf16_t*>(a.out)[xt_index(out_row, col, a.n_heads * DH)] = (bf16_t)r;
     } else {
-      reinterpret_cast<float*>(a.out)[(size_t)b * a.n_heads * DH + col] = r;
+      reinterpret_cast<float*>(a.out)[(size_t)out_row * a.n_heads * DH + col] = r;
     }
   }
 }
@@ -448,6 +449,7 @@ int launch_attention(const AttnArgs& a, int dtype, Pred pred, hipStream_t st) {
   if (a.B == 0) return EE_OK;
   if (a.max_blocks < 1 || a.max_blocks > TABLE_LDS_MAX)
     EE_FAIL(EE_ERR_UNSUPPORTED, "attention: max_blocks %d outside 1..%d", a.max_blocks, TABLE_LDS_MAX);
+  if (a.out_pos && a.row_table) EE_FAIL(EE_ERR_UNSUPPORTED, "attention: out_pos does not go with row_table");
   if (dtype == EE_FP32) {
     if (a.head_dim == 64) launch_t<float, 64>(a, pred, st);
     else if (a.head_dim == 128) launch_t<float, 128>(a, pred, st);

@@ -95,6 +95,7 @@ struct Workspace {
   float* dots;        // [n][Mpad] per-layer row dot products of the head-less confidence measures (zeroed with rowsq)
   float* hprev;       // bf16: [d][Mpad], fp32: [B][d]: hidden state before the current layer (similarity measure)
   float* msr;         // fp32: [3][B] sums of the head-less confidence measures
+  RowMap rowmap;      // bf16: [Mpad] + [Mpad] + [1] row map of the sequences still active (per-sequence exit)
   // fp32 path
   float *h, *x, *ao, *act, *logits;
   size_t bytes;
@@ -129,6 +130,9 @@ Workspace carve(const ee_model_desc& D, int B, void* base) {
     w.split_counters = reinterpret_cast<int32_t*>(w.split_scratch ? w.split_scratch + (d / 32) * 1024 : nullptr);
     w.fill_x = c.take<bf16_t>(n * Mpad * d);
     w.hprev = c.take<float>(d * Mpad);
+    w.rowmap.perm = c.take<int32_t>(Mpad);
+    w.rowmap.cpos = c.take<int32_t>(Mpad);
+    w.rowmap.n_active = c.take<int32_t>(1);
   } else {
     w.partials = c.take<float4>(Bp);
     w.h = c.take<float>(Bp * d);
@@ -206,6 +210,12 @@ int check_workspace(const ee_model_desc& D, int B, void* ws, size_t ws_bytes) {
 
 bool has_head(const ee_model_desc& D, int i) { return i < D.n_layers && i % D.exit_every == 0; }
 
+// Row compaction needs every projection that takes a compacted operand to run in the tiled kernel.
+bool bf16_compactable(const ee_model_desc& D, int B) {
+  return D.dtype == EE_BF16 && gemm_bf16_is_tiled(B, D.d_model / 32) && gemm_bf16_is_tiled(B, 2 * D.d_ffn / 32) &&
+         gemm_bf16_is_tiled(B, D.vocab / 32);
+}
+
 // Workgroups along the contraction for the accumulate epilogue: enough to cover the chip twice, no more (each
 // extra slice costs one more round of float atomics per output and shortens every wavefront's stream).
 int acc_ksplit(int n_tiles, int K) {
@@ -247,14 +257,15 @@ QkvEpi make_qkv_epi(const ee_model_desc& D, const ee_kv_cache& C, const ee_batch
 // --- exit head: statistics of (scale * logits) for every row of the hidden state ------------------------
 // prepped: the normalised operand is already in w.xH (written together with the next layer's operand).
 void enqueue_head_bf16(const ee_model& M, const Workspace& w, int B, int Mpad, float scale, const float* rowsq_slot,
-                       int layer, bool prepped, Pred pred, hipStream_t st) {
+                       int layer, bool prepped, const RowMap& rm, Pred pred, hipStream_t st) {
   const ee_model_desc& D = M.desc;
   if (!prepped) {
     ProfScope ps(EE_K_NORM, layer, st);
     launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(M.g_final), w.xH, rowsq_slot, D.rms_eps, Mpad, D.d_model, pred, st);
   }
   GemmShape g{M.w_lm, w.xH, D.d_model, B, 0, D.vocab / 32, 16, 1};
-  LmEpi e{w.partials, nullptr, D.vocab / 32, D.vocab, scale, nullptr, D.rms_eps, D.d_model};
+  g.n_rows_dev = rm.n_active;   // compacted operand (prepped by the caller through the same map)
+  LmEpi e{w.partials, nullptr, D.vocab / 32, D.vocab, scale, nullptr, D.rms_eps, D.d_model, rm.perm};
   ProfScope ps(EE_K_HEAD, layer, st);
   launch_gemm_lm_bf16(g, e, pred, st);
 }
@@ -418,6 +429,12 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   // what it caches IS the KV filling of layer i for that sequence (Section 3.2) and only the layers above the
   // batch exit layer are left to the filling launch, as in Algorithm 1.
   const int32_t* left = use_exit_heads == EE_EXIT_PER_SEQUENCE ? w.status : nullptr;
+  // At batch sizes where the projections run in the tiled kernel (whose cost grows with the rows), the layers'
+  // operands are compacted as well: attention writes the result of an active sequence to its position in the row
+  // map, the output, FFN and exit-head projections run over the first n_active rows only and scatter into the
+  // residual columns.  The QKV projection keeps all rows in place (it does the KV filling of those that left).
+  const bool compact = left && bf16_compactable(D, B);
+  const RowMap rmap = compact ? w.rowmap : RowMap{};
   const Pred run_layers{w.done, 0};  // kernels of the layer loop: only while the batch has not left
   const Pred run_fill{w.done, 1};    // KV filling: only after it has
   const Pred always{nullptr, 0};
@@ -432,6 +449,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     if (bf) {
       launch_embed_bf16(reinterpret_cast<const bf16_t*>(model->embed), batch->tokens, w.hT, B, Mpad, d, st);
       launch_rowsq(w.hT, rs(0), Mpad, d, always, st);
+      if (compact) launch_compact(w.status, B, rmap, nullptr, 0, Mpad, always, st);   // nobody has left: identity
     } else {
       launch_embed_f32(reinterpret_cast<const float*>(model->embed), batch->tokens, w.h, B, d, st);
       if (simmode) launch_copy_f32(w.h, w.hprev, (size_t)B * d, st);   // h_0, the "previous" state of layer 1
@@ -444,7 +462,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     const size_t pool_off = pool_layer_elems(D, *cache) * elem_bytes(D) * (size_t)(i - 1);
     AttnArgs at{w.q, reinterpret_cast<char*>(cache->k_pool) + pool_off, reinterpret_cast<char*>(cache->v_pool) + pool_off,
                 batch->context_lens, batch->block_tables, batch->max_blocks, B, D.n_heads, D.head_dim, nullptr, 0, left,
-                batch->row_table};
+                batch->row_table, rmap.cpos};
     const bool head_here = use_exit_heads && has_head(D, i);
     if (bf) {
       if (i == 1) {
@@ -475,28 +493,40 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       {
         ProfScope ps(EE_K_OPROJ, i, st);   // also leaves the row sums of squares the FFN norm needs
         GemmShape go{L.w_o, w.aoT, d, B, 0, d / 32, 16, acc_ksplit(d / 32, d)};
-        launch_gemm_acc_bf16(go, AccEpi{w.hT, Mpad, d, rs(2 * i - 1), w.tile_cnt, left}, run_layers, st);
+        go.n_rows_dev = rmap.n_active;
+        launch_gemm_acc_bf16(go, AccEpi{w.hT, Mpad, d, rs(2 * i - 1), w.tile_cnt, compact ? nullptr : left, rmap.perm},
+                             run_layers, st);
       }
       {
         ProfScope ps(EE_K_NORM, i, st);
-        launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_ffn), w.xT, rs(2 * i - 1), D.rms_eps, Mpad, d, run_layers, st);
+        const bf16_t* g_ffn = reinterpret_cast<const bf16_t*>(L.g_ffn);
+        if (compact)
+          launch_prep_x_compact(w.hT, g_ffn, nullptr, w.xT, rs(2 * i - 1), rmap, D.rms_eps, Mpad, d, run_layers, st);
+        else
+          launch_prep_x(w.hT, g_ffn, w.xT, rs(2 * i - 1), D.rms_eps, Mpad, d, run_layers, st);
       }
       {
         ProfScope ps(EE_K_GATEUP, i, st);
         GemmShape gg{L.w_gate_up, w.xT, d, B, 0, 2 * f / 32, f, 1};
+        gg.n_rows_dev = rmap.n_active;
         launch_gemm_gateup_bf16(gg, GateUpEpi{w.actT, f, nullptr, D.rms_eps, d}, run_layers, st);
       }
       {
         ProfScope ps(EE_K_DOWN, i, st);    // row sums for the exit head and for the next layer's attention norm
         GemmShape gd{L.w_down, w.actT, f, B, 0, d / 32, 16, acc_ksplit(d / 32, f)};
-        launch_gemm_acc_bf16(gd, AccEpi{w.hT, Mpad, d, rs(2 * i), w.tile_cnt, left}, run_layers, st);
+        gd.n_rows_dev = rmap.n_active;
+        launch_gemm_acc_bf16(gd, AccEpi{w.hT, Mpad, d, rs(2 * i), w.tile_cnt, compact ? nullptr : left, rmap.perm},
+                             run_layers, st);
       }
       if (i < n) {   // operand of the next layer's attention (and of this layer's exit head, in the same launch)
         ProfScope ps(EE_K_NORM, i, st);
         const bf16_t* g_next = reinterpret_cast<const bf16_t*>(model->layers[i].g_attn);
         if (head_here && !dotmode) {
-          launch_prep_x_pair(w.hT, reinterpret_cast<const bf16_t*>(model->g_final), g_next, w.xH, rs(2 * i), D.rms_eps, Mpad, d,
-                             run_layers, st);
+          const bf16_t* g_head = reinterpret_cast<const bf16_t*>(model->g_final);
+          if (compact)   // the head's operand compacted, the next layer's in place
+            launch_prep_x_compact(w.hT, g_head, g_next, w.xH, rs(2 * i), rmap, D.rms_eps, Mpad, d, run_layers, st);
+          else
+            launch_prep_x_pair(w.hT, g_head, g_next, w.xH, rs(2 * i), D.rms_eps, Mpad, d, run_layers, st);
         } else if (simmode) {
           // h_{i-1} . h_i where a check follows; the snapshot moves on after every layer
           float* dots = head_here ? w.dots + (size_t)(i - 1) * Mpad : nullptr;
@@ -568,16 +598,21 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       da.conf_out = out_conf ? out_conf + (size_t)(i - 1) * B : nullptr;
       ProfScope ps(EE_K_COMBINE, i, st);
       launch_decide(da, run_layers, st);
+      if (compact) launch_compact(w.status, B, rmap, w.rowsq, 2 * i, Mpad, run_layers, st);
     } else if (head_here) {
       const float scale = D.logit_scale * (float)i;
       if (bf)
-        enqueue_head_bf16(*model, w, B, Mpad, scale, rs(2 * i), i, true, run_layers, st);
+        enqueue_head_bf16(*model, w, B, Mpad, scale, rs(2 * i), i, true, rmap, run_layers, st);
       else
         enqueue_head_f32(*model, w, w.h, B, scale, i, run_layers, st);
       CombineArgs ca{w.partials, bf ? D.vocab / 32 : 1, B, i, scale, thresholds[i - 1], D.conf_mode, forced_exit_layer, s,
-                     out_tokens, out_conf ? out_conf + (size_t)(i - 1) * B : nullptr};
+                     out_tokens, out_conf ? out_conf + (size_t)(i - 1) * B : nullptr, left};
       ProfScope ps(EE_K_COMBINE, i, st);
       launch_combine(ca, run_layers, st);
+      if (compact) launch_compact(w.status, B, rmap, w.rowsq, 2 * i, Mpad, run_layers, st);
+    } else if (compact && i < n) {
+      // no check after this layer: the map stands, the sums of the rows that left still move on
+      launch_compact(w.status, B, rmap, w.rowsq, 2 * i, Mpad, run_layers, st);
     }
   }
 
@@ -602,9 +637,9 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
         launch_prep_x_dot(w.hT, reinterpret_cast<const bf16_t*>(model->g_final), w.xH, rs(0), out_batch_exit_layer,
                           (size_t)2 * Mpad, D.rms_eps, Mpad, d, RowDot{}, always, st);
       }
-      enqueue_head_bf16(*model, w, B, Mpad, 0.0f, nullptr, n, true, always, st);
+      enqueue_head_bf16(*model, w, B, Mpad, 0.0f, nullptr, n, true, RowMap{}, always, st);
     } else if (bf) {
-      enqueue_head_bf16(*model, w, B, Mpad, 0.0f, rs(2 * n), n, false, run_layers, st);
+      enqueue_head_bf16(*model, w, B, Mpad, 0.0f, rs(2 * n), n, false, RowMap{}, run_layers, st);
     } else {
       enqueue_head_f32(*model, w, w.h, B, 0.0f, n, final_pred, st);
     }
@@ -649,7 +684,7 @@ int ee_exit_check(const ee_model* model, int32_t layer, const float* hidden, int
                      w.rowsq, (size_t)Mpad, st);
     launch_hidden_to_ht(hidden, w.hT, batch, Mpad, D.d_model, st);
     launch_rowsq(w.hT, w.rowsq, Mpad, D.d_model, always, st);
-    enqueue_head_bf16(*model, w, batch, Mpad, scale, w.rowsq, layer, false, always, st);
+    enqueue_head_bf16(*model, w, batch, Mpad, scale, w.rowsq, layer, false, RowMap{}, always, st);
   } else {
     enqueue_head_f32(*model, w, hidden, batch, scale, layer, always, st);
   }

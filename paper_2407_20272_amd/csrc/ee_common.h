@@ -62,6 +62,15 @@ struct IterState {
   int32_t* batch_exit_layer;  // [1] output_layer of Algorithm 1
 };
 
+// Compaction of the rows that are still active (per-sequence exit at batch sizes the tiled projection kernel
+// serves): position p < *n_active of a compacted operand holds batch row perm[p]; cpos is the inverse map.
+// The map is rebuilt after every exit check and is constant inside a layer.
+struct RowMap {
+  int32_t* perm;      // [Mpad]; nullptr = no compaction (every row, in place)
+  int32_t* cpos;      // [Mpad] batch row -> position, -1 for a sequence that has left
+  int32_t* n_active;  // [1]
+};
+
 // Epilogue parameter blocks ---------------------------------------------------------------------------
 struct QkvEpi {                 // rotary embedding + paged cache write (+ q output)
   float* q;                     // [M][d] fp32 or nullptr (KV filling)
@@ -86,6 +95,7 @@ struct AccEpi {                 // h += value
   float* rowsq;                 // bf16 path: nullptr, or [Mpad] zeroed: receives sum_k h[m][k]^2 of the finished rows
   int32_t* tile_counters;       // bf16 path with rowsq: [n_tiles * m_tiles] zeroed arrival counters (left at zero)
   const int32_t* skip;          // nullptr, or [M]: rows with skip[m] != 0 keep their hidden state (sequences that have left)
+  const int32_t* perm;          // nullptr, or [M]: operand row m is batch row perm[m] (compacted operand, tiled kernel only)
 };
 struct GateUpEpi {              // act = silu(gate) * up
   void* act;                    // XT bf16 [Mpad][f] (bf16 path) or plain float [M][f]
@@ -103,6 +113,7 @@ struct LmEpi {                  // per-tile softmax statistics of the scaled log
   const float* rowsq;
   float eps;
   int d_model;
+  const int32_t* perm;          // nullptr, or [M]: operand row m is batch row perm[m] (compacted operand, tiled kernel only)
 };
 
 // ---------------------------------------------------------------------------------------------------
@@ -135,6 +146,15 @@ void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float*
 // Two normalisations of the same rows in one launch: slab 0 of xT_pair with gain_a, slab 1 (Mpad * d elements on) with gain_b.
 void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT_pair, const float* rowsq,
                         float eps, int Mpad, int d, Pred pred, hipStream_t st);
+// Compacted operands: one slab (gain_b == nullptr) or the pair above, where slab 0 is gathered through the row map
+// (position p holds RMSNorm of batch row perm[p], zeros from *n_active on) and slab 1 stays in place, every row.
+void launch_prep_x_compact(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT, const float* rowsq,
+                           const RowMap& rm, float eps, int Mpad, int d, Pred pred, hipStream_t st);
+// Rebuilds the row map from the status words (active rows keep their order).  carry_to, if set, is the table of
+// row sums of squares ([slots][Mpad]): a row that has left gets the sums of slot `slot` copied into the next two
+// slots, which the compacted projections of the next layer leave untouched for it.
+void launch_compact(const int32_t* status, int B, const RowMap& rm, float* rowsq_table, int slot, int Mpad, Pred pred,
+                    hipStream_t st);
 // rowsq_layer_stride > 0: the sums are at rowsq + slot_ptr[0] * rowsq_layer_stride.
 void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
                           size_t rowsq_layer_stride, const int32_t* slot_ptr, float eps, const int32_t* fill_from,
@@ -171,6 +191,7 @@ struct CombineArgs {
   IterState s;
   int32_t* argmax_out;  // [B] or nullptr
   float* conf_out;      // [B] or nullptr
+  const int32_t* left;  // nullptr, or [B]: rows with left[m] != 0 are not touched (per-sequence exit: token and state stay)
 };
 void launch_combine(const CombineArgs& a, Pred pred, hipStream_t st);
 // Exit decision from a measure that is one dot product per row (conf_mode 2: cosine of consecutive hidden
@@ -211,7 +232,13 @@ struct GemmShape {
   int split_tiles;
   float* split_scratch;      // [split_tiles][1024] floats, zero before the launch, left at zero
   int32_t* split_counters;   // [split_tiles], zero before the launch, left at zero
+  // Tiled kernel only: nullptr, or the device-side number of valid operand rows (<= M).  Row chunks beyond it
+  // return at once, rows beyond it are not written.
+  const int32_t* n_rows_dev;
 };
+// Whether a projection of M rows onto n_tiles packed tiles runs in the tiled kernel (the one that takes
+// n_rows_dev and the epilogues' perm).
+bool gemm_bf16_is_tiled(int M, int n_tiles);
 void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st);
 void launch_gemm_acc_bf16(const GemmShape& g, const AccEpi& e, Pred pred, hipStream_t st);
 void launch_gemm_gateup_bf16(const GemmShape& g, const GateUpEpi& e, Pred pred, hipStream_t st);
@@ -249,6 +276,7 @@ struct AttnArgs {
   int out_xt;                   // 1: XT bf16
   const int32_t* skip;          // nullptr, or [B]: sequences with skip[b] != 0 are not attended (they have left)
   const int32_t* row_table;     // nullptr, or [B]: row b uses row row_table[b] of block_tables
+  const int32_t* out_pos;       // nullptr, or [B]: the result of sequence b goes to row out_pos[b] of out (compacted operand)
 };
 int launch_attention(const AttnArgs& a, int dtype, Pred pred, hipStream_t st);
 

@@ -345,6 +345,9 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
   const int chunks = m_tiles / MT;
   const int ksplit = gridDim.y / chunks;
   const int chunk = blockIdx.y / ksplit, ksl = blockIdx.y % ksplit;
+  // compacted operand: only the first *n_rows_dev rows hold sequences that are still active
+  const int M_eff = g.n_rows_dev ? g.n_rows_dev[0] : g.M;
+  if (chunk * MT * 32 >= M_eff) return;
   const int nt0 = g.tile_begin + (blockIdx.x * NW + wave) * NTW;   // this wavefront's NTW consecutive output tiles
   const int k_steps = g.K >> 4;
   const int ks0 = (int)((long)k_steps * ksl / ksplit);
@@ -451,7 +454,10 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
         o.idx = __shfl_xor(st.idx, 32);
         st = stat_merge(st, o, e.scale);
         const int m = (chunk * MT + mt) * 32 + ml;
-        if (half == 0 && m < g.M) e.partials[(size_t)m * e.n_parts + (nt - g.tile_begin)] = stat_pack(st);
+        if (half == 0 && m < M_eff) {
+          const int row = e.perm ? e.perm[m] : m;
+          e.partials[(size_t)row * e.n_parts + (nt - g.tile_begin)] = stat_pack(st);
+        }
       }
   } else if constexpr (std::is_same<Epi, AccEpi>::value) {
 #pragma unroll
@@ -459,12 +465,13 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int m = (chunk * MT + mt) * 32 + ml;
-        if (m < g.M && !(e.skip && e.skip[m] != 0)) {
+        const int row = (e.perm && m < M_eff) ? e.perm[m] : m;
+        if (m < M_eff && !(e.skip && e.skip[row] != 0)) {
 #pragma unroll
           for (int a = 0; a < 8; ++a) {
             const int f_lo = packed_row_lo(nt0 + t, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
-            unsafeAtomicAdd(e.h + ht_index(m, f_lo, e.Mpad), acc[t][mt][a]);
-            unsafeAtomicAdd(e.h + ht_index(m, f_lo + g.pair_stride, e.Mpad), acc[t][mt][a + 8]);
+            unsafeAtomicAdd(e.h + ht_index(row, f_lo, e.Mpad), acc[t][mt][a]);
+            unsafeAtomicAdd(e.h + ht_index(row, f_lo + g.pair_stride, e.Mpad), acc[t][mt][a + 8]);
           }
         }
       }
@@ -483,14 +490,15 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
         for (int mt = 0; mt < MT; ++mt) {
           const int m = (chunk * MT + mt) * 32 + ml;
           float ss = 0.0f;
-          if (m < g.M) {
+          if (m < M_eff) {
+            const int row = e.perm ? e.perm[m] : m;
 #pragma unroll
             for (int t = 0; t < NTW; ++t)
 #pragma unroll
               for (int a = 0; a < 8; ++a) {
                 const int f_lo = packed_row_lo(nt0 + t, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
-                const float v0 = __hip_atomic_load(e.h + ht_index(m, f_lo, e.Mpad), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const float v1 = __hip_atomic_load(e.h + ht_index(m, f_lo + g.pair_stride, e.Mpad), __ATOMIC_RELAXED,
+                const float v0 = __hip_atomic_load(e.h + ht_index(row, f_lo, e.Mpad), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float v1 = __hip_atomic_load(e.h + ht_index(row, f_lo + g.pair_stride, e.Mpad), __ATOMIC_RELAXED,
                                                    __HIP_MEMORY_SCOPE_AGENT);
                 ss = fmaf(v0, v0, ss);
                 ss = fmaf(v1, v1, ss);
@@ -507,7 +515,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
 #pragma unroll
           for (int w = 0; w < NW; ++w) tot += s.part[w][0][mt][mm] + s.part[w][1][mt][mm];
           const int m = (chunk * MT + mt) * 32 + mm;
-          if (m < g.M) unsafeAtomicAdd(e.rowsq + m, tot);
+          if (m < M_eff) unsafeAtomicAdd(e.rowsq + (e.perm ? e.perm[m] : m), tot);
         }
         if (threadIdx.x == 0) e.tile_counters[cidx] = 0;
       }
@@ -518,7 +526,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int m = (chunk * MT + mt) * 32 + ml;
-        if (m < g.M) {
+        if (m < M_eff) {
 #pragma unroll
           for (int a = 0; a < 8; ++a) {
             const int f_lo = packed_row_lo(nt0 + t, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
@@ -541,6 +549,8 @@ int pick_mt(int M, int cap) {
   return 1;
 }
 
+bool tiled(int M, int n_tiles) { return pick_mt(M, 4) >= 4 && n_tiles % NW == 0; }
+
 template <class Epi, bool FILL>
 void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int nz, hipStream_t st) {
   dim3 block(256);
@@ -548,7 +558,7 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
   // Batch chunks of 4 tiles (128 rows) measured faster than 8 at batch 256 and 512: twice the workgroups, each
   // with half the accumulators, keeps more loads in flight; the second chunk's weight reads mostly hit the caches.
   const int mt_tiled = pick_mt(g.M, 4);
-  if (mt_tiled >= 4 && g.n_tiles % NW == 0) {
+  if (tiled(g.M, g.n_tiles)) {
     // tiled kernel: the workgroup's output tiles share the activation operand through LDS
     const int chunks = m_tiles / mt_tiled;
     // One output tile per wavefront.  Two per wavefront (NTW = 2: each LDS operand read feeds two MFMAs, half the
@@ -580,6 +590,8 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
 }
 
 }  // namespace
+
+bool gemm_bf16_is_tiled(int M, int n_tiles) { return tiled(M, n_tiles); }
 
 void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st) {
   FillCtl fc{};

@@ -102,11 +102,19 @@ __global__ __launch_bounds__(256) void rowsq_kernel(const float* hT, float* rows
 __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable gains, const bf16_t* gain0, bf16_t* xT,
                                                      size_t slab_elems, const float* rowsq, size_t rowsq_layer_stride,
                                                      const int32_t* slot_ptr, float eps, const int32_t* fill_from,
-                                                     int fill_from_stride, int B, int Mpad, int d, RowDot rd, Pred pred) {
+                                                     int fill_from_stride, int B, int Mpad, int d, RowDot rd,
+                                                     RowMap rm, Pred pred) {
   if (pred_skip(pred)) return;
   const int z = blockIdx.z;
   const int ml = threadIdx.x & 31, cl = threadIdx.x >> 5;
   const int m = blockIdx.y * 32 + ml;
+  // slab 0 of a launch with a row map is compacted: position m holds batch row perm[m], zeros from *n_active on
+  // (never combined with the second job below)
+  const bool compacted = rm.perm != nullptr && z == 0;
+  const int n_valid = compacted ? rm.n_active[0] : Mpad;
+  if ((int)blockIdx.y * 32 >= n_valid) return;
+  const bool valid = m < n_valid;
+  const int row = (compacted && valid) ? rm.perm[m] : m;
   if (fill_from) {
     // KV filling: slab z is layer z+1; skip slabs no sequence needs
     const int layer = z + 1;
@@ -127,12 +135,12 @@ __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable 
   // Hidden state of the batch exit layer L (KV filling and the final token inside a decode iteration): its sums
   // were left by the down projection of layer L in slot 2L of the per-iteration table; *slot_ptr = L
   if (rowsq_layer_stride) rowsq += (size_t)slot_ptr[0] * rowsq_layer_stride;
-  const float rq = rowsq[m];
+  const float rq = rowsq[row];
   float hv[8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) hv[i] = hT[ht_index(m, k0 + i, Mpad)];
+  for (int i = 0; i < 8; ++i) hv[i] = valid ? hT[ht_index(row, k0 + i, Mpad)] : 0.0f;
   const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gain + k0);
-  const float r = rsqrtf(rq / (float)d + eps);
+  const float r = valid ? rsqrtf(rq / (float)d + eps) : 0.0f;
   bf16x8 out;
 #pragma unroll
   for (int i = 0; i < 8; ++i) out[i] = (bf16_t)(hv[i] * r * (float)gv[i]);
@@ -256,6 +264,7 @@ __device__ inline void decide_row(const IterState& s, int m, int B, int layer, f
 __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, Pred pred) {
   if (pred_skip(pred)) return;
   const int m = blockIdx.x;
+  if (a.left && a.left[m] != 0) return;   // left at an earlier layer: its token and exit layer stand
   HeadStat s = stat_empty();
   for (int i = threadIdx.x; i < a.n_parts; i += blockDim.x)
     s = stat_merge(s, stat_unpack(a.partials[(size_t)m * a.n_parts + i]), a.scale);
@@ -274,6 +283,40 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, Pred pred) 
   float conf = 1.0f / s.sum;                                          // largest softmax probability
   if (a.conf_mode == 1) conf = (1.0f - expf(a.scale * (s.z2 - s.zmax))) / s.sum;  // top-1 minus top-2
   decide_row(a.s, m, a.B, a.layer, conf, a.threshold, a.forced_exit_layer, a.conf_out);
+}
+
+// Row map of the sequences that are still active, in batch order (one workgroup walks the batch 256 rows at a
+// time); rows that have left get their sums of squares carried into the next layer's two slots.
+__global__ __launch_bounds__(256) void compact_kernel(const int32_t* status, int B, RowMap rm, float* rowsq_table,
+                                                      int slot, int Mpad, Pred pred) {
+  if (pred_skip(pred)) return;
+  __shared__ int wave_total[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int base = 0;
+  for (int m0 = 0; m0 < B; m0 += 256) {
+    const int m = m0 + (int)threadIdx.x;
+    const bool in = m < B;
+    const bool active = in && status[m] == 0;
+    const unsigned long long bal = __ballot(active);
+    if (lane == 0) wave_total[wave] = __popcll(bal);
+    __syncthreads();
+    int off = base + __popcll(bal & ((1ull << lane) - 1ull));
+    for (int w = 0; w < wave; ++w) off += wave_total[w];
+    if (active) {
+      rm.perm[off] = m;
+      rm.cpos[m] = off;
+    } else if (in) {
+      rm.cpos[m] = -1;
+      if (rowsq_table) {
+        const float v = rowsq_table[(size_t)slot * Mpad + m];
+        rowsq_table[(size_t)(slot + 1) * Mpad + m] = v;
+        rowsq_table[(size_t)(slot + 2) * Mpad + m] = v;
+      }
+    }
+    base += wave_total[0] + wave_total[1] + wave_total[2] + wave_total[3];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) rm.n_active[0] = base;
 }
 
 // One thread per row: confidence from one dot product (hidden states similarity, dedicated classifier).
@@ -331,13 +374,13 @@ void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float*
                    Pred pred, hipStream_t st) {
   GainTable none{};
   hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 1), dim3(256), 0, st, hT, none, gain, xT, (size_t)0, rowsq, (size_t)0,
-                     (const int32_t*)nullptr, eps, (const int32_t*)nullptr, 0, 0, Mpad, d, RowDot{}, pred);
+                     (const int32_t*)nullptr, eps, (const int32_t*)nullptr, 0, 0, Mpad, d, RowDot{}, RowMap{}, pred);
 }
 void launch_prep_x_dot(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, const int32_t* slot_ptr,
                        size_t slot_stride, float eps, int Mpad, int d, const RowDot& rd, Pred pred, hipStream_t st) {
   GainTable none{};
   hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 1), dim3(256), 0, st, hT, none, gain, xT, (size_t)0, rowsq,
-                     slot_ptr ? slot_stride : (size_t)0, slot_ptr, eps, (const int32_t*)nullptr, 0, 0, Mpad, d, rd, pred);
+                     slot_ptr ? slot_stride : (size_t)0, slot_ptr, eps, (const int32_t*)nullptr, 0, 0, Mpad, d, rd, RowMap{}, pred);
 }
 void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT_pair, const float* rowsq,
                         float eps, int Mpad, int d, Pred pred, hipStream_t st) {
@@ -346,14 +389,27 @@ void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gai
   two.g[1] = gain_b;
   hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 2), dim3(256), 0, st, hT, two, (const bf16_t*)nullptr, xT_pair,
                      (size_t)Mpad * d, rowsq, (size_t)0, (const int32_t*)nullptr, eps, (const int32_t*)nullptr, 0, 0, Mpad, d,
-                     RowDot{}, pred);
+                     RowDot{}, RowMap{}, pred);
+}
+void launch_prep_x_compact(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT, const float* rowsq,
+                           const RowMap& rm, float eps, int Mpad, int d, Pred pred, hipStream_t st) {
+  GainTable two{};
+  two.g[0] = gain_a;
+  two.g[1] = gain_b;
+  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, gain_b ? 2 : 1), dim3(256), 0, st, hT, two, (const bf16_t*)nullptr,
+                     xT, (size_t)Mpad * d, rowsq, (size_t)0, (const int32_t*)nullptr, eps, (const int32_t*)nullptr, 0, 0, Mpad,
+                     d, RowDot{}, rm, pred);
+}
+void launch_compact(const int32_t* status, int B, const RowMap& rm, float* rowsq_table, int slot, int Mpad, Pred pred,
+                    hipStream_t st) {
+  hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(256), 0, st, status, B, rm, rowsq_table, slot, Mpad, pred);
 }
 void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
                           size_t rowsq_layer_stride, const int32_t* slot_ptr, float eps, const int32_t* fill_from,
                           int fill_from_stride, int B, int Mpad, int d, Pred pred, hipStream_t st) {
   hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, n_layers), dim3(256), 0, st, hT, gains,
                      (const bf16_t*)nullptr, xT_slabs, (size_t)Mpad * d, rowsq, rowsq_layer_stride, slot_ptr, eps, fill_from,
-                     fill_from_stride, B, Mpad, d, RowDot{}, pred);
+                     fill_from_stride, B, Mpad, d, RowDot{}, RowMap{}, pred);
 }
 void launch_rmsnorm_f32(const float* h, const float* gain, float* x, int B, int d, float eps, Pred pred, hipStream_t st) {
   hipLaunchKernelGGL(rmsnorm_f32_kernel, dim3(B), dim3(256), 0, st, h, gain, x, d, eps, pred);

@@ -207,6 +207,42 @@ def test_per_sequence_forced_exits(cfg):
     assert stats["L"] == [int(forced[s].max()) for s in range(4)]
 
 
+def compactable_bf16(**kw):
+    """Widths at which every projection runs in the tiled kernel once the batch is a multiple of 128 rows: the
+    per-sequence rule then compacts the rows that are still active."""
+    return small_bf16(n_layers=6, d_ffn=384, prompt_len=10, min_prompt_len=3, shuffled_blocks=True, **kw)
+
+
+@pytest.mark.parametrize("batch", [128, 256, 384])
+@pytest.mark.parametrize("conf_mode,threshold", [(0, 0.5), (2, 0.78)])
+def test_bf16_per_sequence_exit_compacted_rows_lockstep(conf_mode, threshold, batch):
+    cfg = compactable_bf16(batch=batch, conf_mode=conf_mode, threshold=threshold)
+    stats = lockstep(cfg, seed=43, steps=3, heads=2)
+    total = stats["decisions"] + stats["tokens"]
+    assert stats["near_threshold"] + stats["near_tie"] <= max(2, total // 20), stats
+
+
+@pytest.mark.parametrize("exit_every", [1, 2])
+def test_per_sequence_compaction_across_chunk_boundaries(exit_every):
+    """Forced exits that take the number of active rows through 129, 128, 127, 1 and 0 (the projections work on
+    128-row chunks), with the last sequence staying to the end or leaving one layer before it (KV filling of the
+    last layer), and with checks after every second layer only (the row sums of sequences that have left move on
+    through layers without a check)."""
+    cfg = compactable_bf16(batch=256, exit_every=exit_every)
+    n, Bsz = cfg.n_layers, cfg.batch
+    forced = torch.full((3, Bsz), 4, dtype=torch.int32)
+    forced[:, :127] = 1
+    forced[:, 127] = 2
+    forced[:, 128] = 3
+    forced[0, 255] = n           # one sequence runs every layer
+    forced[1, 255] = n - 1       # ... or leaves before the last layer, which is then filled
+    forced[2] = torch.randint(1, n + 1, (Bsz,), generator=torch.Generator().manual_seed(5), dtype=torch.int32)
+    stats = lockstep(cfg, seed=44, steps=3, forced_seq=forced, heads=2)
+    want = [n, n - 1 if exit_every == 1 else n, int(forced[2].max())]
+    if exit_every == 1:
+        assert stats["L"] == want
+
+
 @pytest.mark.parametrize("heads", [1, 2])
 def test_batch_of_one_and_prompts_ending_on_block_boundaries(heads):
     """Degenerate sizes: a single sequence, and prompts whose next position opens a new 16-token block."""
