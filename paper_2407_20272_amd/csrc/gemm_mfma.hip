@@ -304,6 +304,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
 // drain into two LDS stages).  Every wavefront finishes its own tiles, so the epilogue runs from registers.
 // ---------------------------------------------------------------------------------------------------------
 constexpr int UT = 4;
+__device__ u32x4 k_zero_tile[64];   // one operand tile of zeros, never written (activation rows past the contraction range; not const: it must live in the same address space as the operands)
 
 template <int MT>
 struct TiledLds {
@@ -381,15 +382,19 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
 #pragma unroll
     for (int j = 0; j < XR; ++j) {
       const int t = wave + NW * j, u = t / MT, mt = t % MT;
+      // past the end: a tile of zeros, chosen by address (a select on the loaded value would sit right behind
+      // the load and make the wavefront wait for everything it has in flight)
       const bool ok = kbase + u < ks1;
-      const int kk = ok ? kbase + u : ks1 - 1;
-      const u32x4 v = xp[mt * x_tile_stride + (size_t)kk * 64];
-      xr[j] = ok ? v : u32x4{0, 0, 0, 0};
+      const u32x4* src = ok ? xp + mt * x_tile_stride + (size_t)(kbase + u) * 64 : k_zero_tile + lane;
+      xr[j] = *src;
     }
   };
   // One group: drain its activation registers into LDS stage XS, start the loads of group grp+2 into the
   // registers just freed and an idle weight set, multiply group grp.
   auto step = [&](int grp, const u32x4 (&wcur)[NTW][UT], u32x4 (&wnext2)[NTW][UT], u32x4 (&xs)[XR], int XS) {
+    // keeps the LDS stores below from being hoisted into the previous group, ahead of its loads: there they would
+    // wait for loads that were only just issued
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < XR; ++j) {
       const int t = wave + NW * j;
