@@ -210,9 +210,10 @@ int check_workspace(const ee_model_desc& D, int B, void* ws, size_t ws_bytes) {
 
 bool has_head(const ee_model_desc& D, int i) { return i < D.n_layers && i % D.exit_every == 0; }
 
-// Row compaction needs every projection that takes a compacted operand to run in the tiled kernel.
+// Row compaction needs every projection that takes a compacted operand to run in the tiled kernel, and pays
+// from two 128-row chunks on (a chunk is what the kernel can skip).
 bool bf16_compactable(const ee_model_desc& D, int B) {
-  return D.dtype == EE_BF16 && gemm_bf16_is_tiled(B, D.d_model / 32) && gemm_bf16_is_tiled(B, 2 * D.d_ffn / 32) &&
+  return D.dtype == EE_BF16 && B > 128 && gemm_bf16_is_tiled(B, D.d_model / 32) && gemm_bf16_is_tiled(B, 2 * D.d_ffn / 32) &&
          gemm_bf16_is_tiled(B, D.vocab / 32);
 }
 

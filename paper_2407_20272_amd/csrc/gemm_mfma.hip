@@ -343,8 +343,8 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m_tiles = (g.M + 31) >> 5;
-  const int chunks = m_tiles / MT;
-  const int ksplit = gridDim.y / chunks;
+  const int chunks = (m_tiles + MT - 1) / MT;   // the last chunk may be short: its missing tiles re-read its last
+  const int ksplit = gridDim.y / chunks;        // valid one, and their rows are never written
   const int chunk = blockIdx.y / ksplit, ksl = blockIdx.y % ksplit;
   // compacted operand: only the first *n_rows_dev rows hold sequences that are still active
   const int M_eff = g.n_rows_dev ? g.n_rows_dev[0] : g.M;
@@ -357,6 +357,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
   const size_t w_tile_stride = (size_t)k_steps * 64;
   const u32x4* wp = reinterpret_cast<const u32x4*>(g.w) + (size_t)nt0 * k_steps * 64 + lane;
   const u32x4* xp = reinterpret_cast<const u32x4*>(g.x) + (size_t)(chunk * MT) * x_tile_stride + lane;
+  const int mt_last = min(MT, m_tiles - chunk * MT) - 1;   // last batch tile of this chunk that exists
 
   f32x16 acc[NTW][MT];
 #pragma unroll
@@ -385,7 +386,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
       // past the end: a tile of zeros, chosen by address (a select on the loaded value would sit right behind
       // the load and make the wavefront wait for everything it has in flight)
       const bool ok = kbase + u < ks1;
-      const u32x4* src = ok ? xp + mt * x_tile_stride + (size_t)(kbase + u) * 64 : k_zero_tile + lane;
+      const u32x4* src = ok ? xp + min(mt, mt_last) * x_tile_stride + (size_t)(kbase + u) * 64 : k_zero_tile + lane;
       xr[j] = *src;
     }
   };
@@ -554,7 +555,9 @@ int pick_mt(int M, int cap) {
   return 1;
 }
 
-bool tiled(int M, int n_tiles) { return pick_mt(M, 4) >= 4 && n_tiles % NW == 0; }
+// From three batch tiles on, the tiled kernel (128-row chunks, the last one padded) beats re-streaming the weights
+// once per pass of the streaming kernel.
+bool tiled(int M, int n_tiles) { return (M + 31) / 32 >= 3 && n_tiles % NW == 0; }
 
 template <class Epi, bool FILL>
 void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int nz, hipStream_t st) {
@@ -562,10 +565,9 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
   const int m_tiles = (g.M + 31) / 32;
   // Batch chunks of 4 tiles (128 rows) measured faster than 8 at batch 256 and 512: twice the workgroups, each
   // with half the accumulators, keeps more loads in flight; the second chunk's weight reads mostly hit the caches.
-  const int mt_tiled = pick_mt(g.M, 4);
   if (tiled(g.M, g.n_tiles)) {
     // tiled kernel: the workgroup's output tiles share the activation operand through LDS
-    const int chunks = m_tiles / mt_tiled;
+    const int chunks = (m_tiles + 3) / 4;
     // One output tile per wavefront.  Two per wavefront (NTW = 2: each LDS operand read feeds two MFMAs, half the
     // workgroups) measured slower at batch 256 and 512: the kernel is limited by loads in flight per compute unit,
     // not by LDS bandwidth.
