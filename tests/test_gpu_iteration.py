@@ -222,6 +222,17 @@ def test_bf16_per_sequence_exit_compacted_rows_lockstep(conf_mode, threshold, ba
     assert stats["near_threshold"] + stats["near_tie"] <= max(2, total // 20), stats
 
 
+@pytest.mark.parametrize("batch", [96, 150, 200])
+@pytest.mark.parametrize("heads", [1, 2])
+def test_bf16_row_counts_with_a_short_last_chunk(batch, heads):
+    """Three, five and seven 32-row tiles: the tiled projection kernel pads its last 128-row chunk (and, under
+    the per-sequence rule above 128 rows, compacts the active rows as well)."""
+    cfg = compactable_bf16(batch=batch)
+    stats = lockstep(cfg, seed=45, steps=3, heads=heads)
+    total = stats["decisions"] + stats["tokens"]
+    assert stats["near_threshold"] + stats["near_tie"] <= max(2, total // 20), stats
+
+
 @pytest.mark.parametrize("exit_every", [1, 2])
 def test_per_sequence_compaction_across_chunk_boundaries(exit_every):
     """Forced exits that take the number of active rows through 129, 128, 127, 1 and 0 (the projections work on
