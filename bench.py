@@ -85,6 +85,8 @@ def main():
                          "(always used when prompt lengths are ragged)")
     ap.add_argument("--batch", type=int, default=0, help="override the batch size (exit-rate sweep members)")
     ap.add_argument("--context", type=int, default=0, help="override the context length (exit-rate sweep members)")
+    ap.add_argument("--forced-layer", type=int, default=0,
+                    help="force every sequence to leave at this layer (measures KV filling over the layers above it)")
     ap.add_argument("--forced-mean", type=float, default=0.0,
                     help="exit-rate sweep: force per-sequence exit layers from the truncated geometric distribution on "
                          "[8, n] with this mean instead of using the confidence")
@@ -151,8 +153,11 @@ def main():
         first.copy_(out_tok)
     torch.cuda.synchronize()
     forced_all = None
-    if args.forced_mean > 0:
+    if args.forced_layer > 0:   # everybody leaves at this layer: the batch exit layer is known, KV filling covers n - it
+        forced_all = torch.full((Wm + K + P + 4, Bsz), min(args.forced_layer, n), dtype=torch.int32, device="cuda")
+    elif args.forced_mean > 0:
         forced_all = W.make_forced_exit_layers(Bsz, Wm + K + P + 4, args.forced_mean, 8, n, seed=0).cuda()
+    if forced_all is not None:
         forced_cur = torch.zeros(Bsz, dtype=torch.int32, device="cuda")
         step_no = torch.zeros(1, dtype=torch.int64, device="cuda")
     setup_s = time.time() - t0
@@ -319,7 +324,7 @@ def main():
                    "vocab": cfg.vocab, "threshold": cfg.threshold, "logit_scale": cfg.logit_scale,
                    "exit_every": cfg.exit_every, "kv_block": cfg.block_size, "mode": head_mode,
                    "context_lens": [int(lens.min()), int(lens.max())], "kv": "synthetic" if synthetic_kv else "prefilled",
-                   "forced_exit_mean": args.forced_mean or None,
+                   "forced_exit_mean": args.forced_mean or None, "forced_exit_layer": args.forced_layer or None,
                    "launch": "eager" if args.no_graph else "hip_graph",
                    "exit_rule": "per_sequence" if args.per_sequence else "batch (Algorithm 1)"},
         "modes": results,

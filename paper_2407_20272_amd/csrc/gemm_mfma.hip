@@ -36,21 +36,26 @@ struct Lds {
   int flag;
 };
 
-// KV filling: does any sequence need layer `layer` filled?  (uniform over the workgroup)
-__device__ inline bool fill_needed(const QkvEpi& e, int M, int layer, Lds& s) {
-  if (threadIdx.x == 0) s.flag = 0;
+// KV filling: should this workgroup (layer slice `layer`) return at once?  Uniform over the workgroup.  With one
+// fill-from layer for the whole batch (Algorithm 1) the predicate word and that layer are fetched together: the
+// workgroup waits for one memory round trip, not three, before its first weight load.
+__device__ inline bool fill_skip(const Pred& pred, const QkvEpi& e, int M, int layer, int& lds_flag) {
+  if (e.fill_from_stride == 0) {
+    const int32_t from = e.fill_from[0];
+    const int32_t flag = pred.flag ? pred.flag[0] : 0;
+    if (pred.flag && ((flag != 0) != (pred.run_when != 0))) return true;
+    return !(from < layer);
+  }
+  if (pred_skip(pred)) return true;
+  if (threadIdx.x == 0) lds_flag = 0;
   __syncthreads();
   int need = 0;
-  if (e.fill_from_stride == 0) {
-    need = e.fill_from[0] < layer;
-  } else {
-    for (int m = threadIdx.x; m < M; m += blockDim.x) need |= e.fill_from[m] < layer;
-  }
-  if (need) s.flag = 1;
+  for (int m = threadIdx.x; m < M; m += blockDim.x) need |= e.fill_from[m] < layer;
+  if (need) lds_flag = 1;
   __syncthreads();
-  const bool any = s.flag != 0;
+  const bool any = lds_flag != 0;
   __syncthreads();
-  return any;
+  return !any;
 }
 
 // Meets the four wavefronts' partial 32x32 tiles in LDS and runs the epilogue on the finished sums.
@@ -164,13 +169,63 @@ __device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, con
         if (threadIdx.x == 0) g.split_counters[tl] = 0;
       }
     }
-    if (m < g.M) {
+    if constexpr (std::is_same<Epi, QkvEpi>::value) {
+      // The tile holds, for each of its 32 batch rows, 16 consecutive channels of one head and their 16 rotary
+      // partners (half a head further on).  Rotate in registers, stage the tile in LDS, then write whole 16-channel
+      // runs (one 16-byte store per thread) instead of single elements scattered over the cache blocks.
+      const int d = e.d_model, dh = e.head_dim, hdim = dh >> 1;
+      const int f0 = packed_row_lo(nt, 0, g.pair_stride);   // first channel of the tile (uniform)
+      const int which = f0 / d;                              // 0 q, 1 k, 2 v
+      const int head = (f0 - which * d) / dh;
+      const int j0 = f0 - which * d - head * dh;             // < dh/2, a multiple of 16
+      const int mcol = l2 & 31;
 #pragma unroll
       for (int ai = 0; ai < 2; ++ai) {
-        const int f_lo = packed_row_lo(nt, r16[ai], g.pair_stride);
-        if constexpr (std::is_same<Epi, QkvEpi>::value) {
-          epi_qkv<bf16_t>(e, m, f_lo, vlo[ai], vhi[ai]);
-        } else {
+        float lo = vlo[ai], hi = vhi[ai];
+        if (m < g.M) {
+          const float r = row_rinv(e.rowsq, m, e.d_model, e.eps);
+          lo *= r;
+          hi *= r;
+          if (which < 2 && e.rope_theta > 0.0f) {
+            const float2 cs = e.rope[(size_t)m * hdim + j0 + r16[ai]];
+            const float a = lo * cs.x - hi * cs.y;
+            const float b = hi * cs.x + lo * cs.y;
+            lo = a;
+            hi = b;
+          }
+        }
+        s.zt[r16[ai]][mcol] = lo;
+        s.zt[16 + r16[ai]][mcol] = hi;
+      }
+      __syncthreads();
+      if (which == 0) {
+        if (e.q) {   // thread -> (row, run, quarter of the run): four floats
+          const int mr = threadIdx.x >> 3, part = threadIdx.x & 7, run = part >> 2, c0 = run * 16 + (part & 3) * 4;
+          const int mm = mt_global * 32 + mr;
+          if (mm < g.M && !(e.fill_from && !(e.fill_from[(size_t)mm * e.fill_from_stride] < e.layer))) {
+            float4 v = make_float4(s.zt[c0][mr], s.zt[c0 + 1][mr], s.zt[c0 + 2][mr], s.zt[c0 + 3][mr]);
+            *reinterpret_cast<float4*>(e.q + (size_t)mm * d + head * dh + j0 + run * hdim + (part & 3) * 4) = v;
+          }
+        }
+      } else if (threadIdx.x < 128) {   // thread -> (row, run, half of the run): eight bf16
+        const int mr = threadIdx.x >> 2, part = threadIdx.x & 3, run = part >> 1, c0 = run * 16 + (part & 1) * 8;
+        const int mm = mt_global * 32 + mr;
+        if (mm < g.M && !(e.fill_from && !(e.fill_from[(size_t)mm * e.fill_from_stride] < e.layer))) {
+          const int p = e.context_lens[mm];
+          const int blk = e.block_tables[(size_t)(e.row_table ? e.row_table[mm] : mm) * e.max_blocks + (p >> 4)];
+          const size_t at = (((size_t)blk * e.n_heads + head) * 16 + (p & 15)) * dh + j0 + run * hdim + (part & 1) * 8;
+          bf16x8 v;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) v[i] = (bf16_t)s.zt[c0 + i][mr];
+          bf16_t* pool = reinterpret_cast<bf16_t*>(which == 1 ? e.k_pool : e.v_pool);
+          *reinterpret_cast<bf16x8*>(pool + at) = v;
+        }
+      }
+    } else {
+      if (m < g.M) {
+#pragma unroll
+        for (int ai = 0; ai < 2; ++ai) {
+          const int f_lo = packed_row_lo(nt, r16[ai], g.pair_stride);
           epi_gateup<bf16_t>(e, m, f_lo, vlo[ai], vhi[ai]);
         }
       }
@@ -227,12 +282,13 @@ __device__ inline void frag_mma(const Frag<MT, U>& f, f32x16 (&acc)[MT]) {
 
 template <int MT, int U, class Epi, bool FILL>
 __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred pred, FillCtl fc) {
-  if (pred_skip(pred)) return;
   __shared__ Lds s;
 
-  if constexpr (FILL) {
+  if constexpr (!FILL) {
+    if (pred_skip(pred)) return;
+  } else {
     const int layer = (int)gridDim.z - (int)blockIdx.z;   // deepest layer first: the slices that have work start first
-    if (!fill_needed(e, g.M, layer, s)) return;
+    if (fill_skip(pred, e, g.M, layer, s.flag)) return;
     g.w = fc.layers.w_qkv[layer - 1];
     g.x = fc.x_slabs + (size_t)(layer - 1) * fc.x_slab_elems;
     e.layer = layer;
@@ -315,24 +371,15 @@ struct TiledLds {
 
 template <int MT, int NTW, class Epi, bool FILL>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pred pred, FillCtl fc) {
-  if (pred_skip(pred)) return;
   __shared__ TiledLds<MT> s;
   constexpr int XR = UT * MT / NW;   // activation tiles each wavefront stages per group
   static_assert(UT * MT % NW == 0, "stage must split evenly over the wavefronts");
 
-  if constexpr (FILL) {
+  if constexpr (!FILL) {
+    if (pred_skip(pred)) return;
+  } else {
     const int layer = (int)gridDim.z - (int)blockIdx.z;   // deepest layer first: the slices that have work start first
-    if (threadIdx.x == 0) s.flag = 0;
-    __syncthreads();
-    int need = 0;
-    if (e.fill_from_stride == 0) {
-      need = e.fill_from[0] < layer;
-    } else {
-      for (int m = threadIdx.x; m < g.M; m += blockDim.x) need |= e.fill_from[m] < layer;
-    }
-    if (need) s.flag = 1;
-    __syncthreads();
-    if (!s.flag) return;
+    if (fill_skip(pred, e, g.M, layer, s.flag)) return;
     g.w = fc.layers.w_qkv[layer - 1];
     g.x = fc.x_slabs + (size_t)(layer - 1) * fc.x_slab_elems;
     e.layer = layer;

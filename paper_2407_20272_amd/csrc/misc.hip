@@ -118,16 +118,18 @@ __global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable 
   if (fill_from) {
     // KV filling: slab z is layer z+1; skip slabs no sequence needs
     const int layer = z + 1;
-    __shared__ int any_row;
-    if (threadIdx.x == 0) any_row = 0;
-    __syncthreads();
-    int need = 0;
-    if (fill_from_stride == 0) need = fill_from[0] < layer;
-    else
+    if (fill_from_stride == 0) {
+      if (!(fill_from[0] < layer)) return;
+    } else {
+      __shared__ int any_row;
+      if (threadIdx.x == 0) any_row = 0;
+      __syncthreads();
+      int need = 0;
       for (int r = threadIdx.x; r < B; r += blockDim.x) need |= fill_from[r] < layer;
-    if (need) any_row = 1;
-    __syncthreads();
-    if (!any_row) return;
+      if (need) any_row = 1;
+      __syncthreads();
+      if (!any_row) return;
+    }
   }
   const bf16_t* gain = gains.g[z] ? reinterpret_cast<const bf16_t*>(gains.g[z]) : gain0;
   const int c = blockIdx.x * 8 + cl;  // 8-channel chunk
