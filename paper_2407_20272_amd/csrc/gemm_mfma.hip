@@ -626,6 +626,17 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
       if (ksplit > k_steps / 64) ksplit = k_steps / 64;
       if (ksplit < 1) ksplit = 1;
     }
+    if constexpr (std::is_same<Epi, QkvEpi>::value && !FILL) {
+      // Few output tiles and one 128-row chunk leave most compute units idle (QKV at 7B width: 96 workgroups):
+      // 64-row chunks double the workgroups as long as they all still start at once (measured at 128 rows:
+      // 61 -> 45 us; with more workgroups than compute units the second weight pass costs more than it gains).
+      const int chunks2 = (m_tiles + 1) / 2;
+      if (!g.n_rows_dev && groups * chunks < 128 && groups * chunks2 <= 256) {
+        dim3 grid2(groups, chunks2, nz);
+        hipLaunchKernelGGL((gemm_tiled_kernel<2, 1, Epi, FILL>), grid2, block, 0, st, g, e, pred, fc);
+        return;
+      }
+    }
     dim3 grid(groups, chunks * ksplit, nz);
     hipLaunchKernelGGL((gemm_tiled_kernel<4, 1, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
     return;
