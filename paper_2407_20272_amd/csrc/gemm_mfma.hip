@@ -622,7 +622,9 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
     int ksplit = 1;
     if constexpr (std::is_same<Epi, AccEpi>::value) {
       const int k_steps = g.K / 16;
-      ksplit = 512 / (groups * chunks);
+      // one workgroup per compute unit (measured at 96-512 rows: better than two; further slices only add
+      // rounds of float atomics), slices of at least 64 contraction steps
+      ksplit = 256 / (groups * chunks);
       if (ksplit > k_steps / 64) ksplit = k_steps / 64;
       if (ksplit < 1) ksplit = 1;
     }
