@@ -235,6 +235,7 @@ struct GemmShape {
   // Tiled kernel only: nullptr, or the device-side number of valid operand rows (<= M).  Row chunks beyond it
   // return at once, rows beyond it are not written.
   const int32_t* n_rows_dev;
+  int grid_y;   // set by the launcher (tiled kernel): batch chunks x contraction slices per group of output tiles
 };
 // Whether a projection of M rows onto n_tiles packed tiles runs in the tiled kernel (the one that takes
 // n_rows_dev and the epilogues' perm).

@@ -391,12 +391,22 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int m_tiles = (g.M + 31) >> 5;
   const int chunks = (m_tiles + MT - 1) / MT;   // the last chunk may be short: its missing tiles re-read its last
-  const int ksplit = gridDim.y / chunks;        // valid one, and their rows are never written
-  const int chunk = blockIdx.y / ksplit, ksl = blockIdx.y % ksplit;
+                                                // valid one, and their rows are never written
+  // One-dimensional grid.  Workgroup ids that are congruent modulo 8 run on the same XCD and share its L2, so
+  // the workgroups that stream the SAME weight tiles (the batch chunks and contraction slices of one tile group)
+  // get consecutive ids of one residue class: they start together on one XCD, and all but the first read of a
+  // weight tile hit that L2 instead of going out to memory once per chunk.
+  const int ny = g.grid_y;                      // chunks * contraction slices
+  const int ksplit = ny / chunks;
+  const int slot = (int)blockIdx.x >> 3;
+  const int bx = (slot / ny) * 8 + ((int)blockIdx.x & 7);
+  const int by = slot % ny;
+  if (bx * NW * NTW >= g.n_tiles) return;       // the group count is padded to a multiple of 8
+  const int chunk = by / ksplit, ksl = by % ksplit;
   // compacted operand: only the first *n_rows_dev rows hold sequences that are still active
   const int M_eff = g.n_rows_dev ? g.n_rows_dev[0] : g.M;
   if (chunk * MT * 32 >= M_eff) return;
-  const int nt0 = g.tile_begin + (blockIdx.x * NW + wave) * NTW;   // this wavefront's NTW consecutive output tiles
+  const int nt0 = g.tile_begin + (bx * NW + wave) * NTW;   // this wavefront's NTW consecutive output tiles
   const int k_steps = g.K >> 4;
   const int ks0 = (int)((long)k_steps * ksl / ksplit);
   const int ks1 = (int)((long)k_steps * (ksl + 1) / ksplit);
@@ -534,7 +544,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
       // row sums the next RMSNorm needs
       __builtin_amdgcn_s_waitcnt(0);
       __syncthreads();
-      const int cidx = blockIdx.x * chunks + chunk;
+      const int cidx = bx * chunks + chunk;
       if (threadIdx.x == 0) s.flag = atomicAdd(e.tile_counters + cidx, 1);
       __syncthreads();
       const bool last = s.flag == ksplit - 1;
@@ -634,13 +644,17 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
       // 61 -> 45 us; with more workgroups than compute units the second weight pass costs more than it gains).
       const int chunks2 = (m_tiles + 1) / 2;
       if (!g.n_rows_dev && groups * chunks < 128 && groups * chunks2 <= 256) {
-        dim3 grid2(groups, chunks2, nz);
-        hipLaunchKernelGGL((gemm_tiled_kernel<2, 1, Epi, FILL>), grid2, block, 0, st, g, e, pred, fc);
+        GemmShape g2 = g;
+        g2.grid_y = chunks2;
+        dim3 grid2((groups + 7) / 8 * 8 * chunks2, 1, nz);
+        hipLaunchKernelGGL((gemm_tiled_kernel<2, 1, Epi, FILL>), grid2, block, 0, st, g2, e, pred, fc);
         return;
       }
     }
-    dim3 grid(groups, chunks * ksplit, nz);
-    hipLaunchKernelGGL((gemm_tiled_kernel<4, 1, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
+    GemmShape g4 = g;
+    g4.grid_y = chunks * ksplit;
+    dim3 grid((groups + 7) / 8 * 8 * chunks * ksplit, 1, nz);
+    hipLaunchKernelGGL((gemm_tiled_kernel<4, 1, Epi, FILL>), grid, block, 0, st, g4, e, pred, fc);
     return;
   }
   dim3 grid(g.n_tiles + g.split_tiles, g.ksplit, nz);   // split tiles take two workgroups each (one batch tile only)
