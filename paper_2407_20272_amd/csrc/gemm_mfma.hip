@@ -399,8 +399,17 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
   const int ny = g.grid_y;                      // chunks * contraction slices
   const int ksplit = ny / chunks;
   const int slot = (int)blockIdx.x >> 3;
-  const int bx = (slot / ny) * 8 + ((int)blockIdx.x & 7);
-  const int by = slot % ny;
+  int bx, by;
+  if (g.n_rows_dev) {
+    // compacted operand: most chunks may have nothing to do, and their workgroups return at once; chunk-major
+    // order keeps those behind the chunks that work instead of in between them
+    const int groups8 = (int)gridDim.x / (8 * ny);
+    by = slot / groups8;
+    bx = (slot % groups8) * 8 + ((int)blockIdx.x & 7);
+  } else {
+    bx = (slot / ny) * 8 + ((int)blockIdx.x & 7);
+    by = slot % ny;
+  }
   if (bx * NW * NTW >= g.n_tiles) return;       // the group count is padded to a multiple of 8
   const int chunk = by / ksplit, ksl = by % ksplit;
   // compacted operand: only the first *n_rows_dev rows hold sequences that are still active
