@@ -199,6 +199,14 @@ def test_config4_llama13b_ffn_width():
     one_iteration_case(cfg, seed=6, sample=[0, 31, 63], threshold=0.3)
 
 
+@pytest.mark.parametrize("batch", [96, 160])
+def test_13b_width_row_counts_of_the_tiled_projection_kernel(batch):
+    """13B widths (40, 120, 216 and 250 groups of output tiles: not multiples of 8, so the XCD-aware grid is
+    padded) at row counts whose last 128-row chunk is short."""
+    cfg = W.reduced(W.CONFIGS[4], n_layers=2, batch=batch, prompt_len=64, min_prompt_len=64, logit_scale=8.0)
+    one_iteration_case(cfg, seed=7, sample=[0, batch // 2, batch - 1], threshold=0.3)
+
+
 def test_config1_full_size_one_iteration_sampled():
     """The benchmark workload itself: 32 layers, batch 32, context 512, exit head after every layer, threshold 0.9
     (hidden state, exit layers, confidences, tokens and this position's K/V of all 32 layers for sampled sequences)."""
