@@ -510,12 +510,14 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
         // this lane's 16 logits of the row in ascending vocabulary order: rows r16(a), a = 0..7, then r16(a)+16
         float z[16];
         int zi[16];
+        const int mrow = (chunk * MT + mt) * 32 + ml;
+        const float rs = mrow < M_eff ? row_rinv(e.rowsq, e.perm ? e.perm[mrow] : mrow, e.d_model, e.eps) : 0.0f;
 #pragma unroll
         for (int a = 0; a < 8; ++a) {
           const int r16 = (a >> 2) * 8 + half * 4 + (a & 3);
-          z[a] = acc[t][mt][a];
+          z[a] = acc[t][mt][a] * rs;
           zi[a] = nt * 32 + r16;
-          z[a + 8] = acc[t][mt][a + 8];
+          z[a + 8] = acc[t][mt][a + 8] * rs;
           zi[a + 8] = nt * 32 + r16 + 16;
         }
         HeadStat st = stat_of<16>(z, zi, e.scale);
