@@ -214,7 +214,7 @@ def test_config1_full_size_one_iteration_sampled():
     assert 1 <= L <= 32
 
 
-@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("dtype", ["fp32", "bf16", "bf16_per_sequence_160"])
 def test_hip_graph_replay_matches_eager(dtype):
     """The launch configuration bench.py times: one iteration captured into a HIP graph and replayed, with eager work and
     synchronisations between replays; every replay must reproduce the eager iteration's outputs.  The fp32 path is
@@ -224,9 +224,13 @@ def test_hip_graph_replay_matches_eager(dtype):
     if dtype == "fp32":
         cfg = W.CONFIGS[0].with_(n_layers=5, batch=8, prompt_len=40, min_prompt_len=40, weight_std=0.05, logit_scale=1.0,
                                  threshold=0.4)
-    else:
+    elif dtype == "bf16":
         cfg = W.reduced(W.CONFIGS[1], n_layers=5, d_model=512, n_heads=4, d_ffn=1408, vocab=2048, batch=32, prompt_len=40,
                         min_prompt_len=40, weight_std=0.05, logit_scale=1.0, threshold=0.4)
+    else:   # per-sequence exit with the active rows compacted (device-side row map: nothing for the graph to bake in)
+        cfg = W.reduced(W.CONFIGS[1], n_layers=5, d_model=512, n_heads=4, d_ffn=1408, vocab=2048, batch=160, prompt_len=40,
+                        min_prompt_len=40, weight_std=0.05, logit_scale=1.0, threshold=0.4)
+    exit_rule = B.EE_EXIT_PER_SEQUENCE if dtype == "bf16_per_sequence_160" else B.EE_EXIT_BATCH
     w = W.make_weights(cfg, seed=8, gain_jitter=0.1)
     lens = W.make_context_lens(cfg, seed=8)
     steps = 4
@@ -239,8 +243,8 @@ def test_hip_graph_replay_matches_eager(dtype):
     batch = B.make_batch(tokens, ctx, run.bt_dev, int(lens.max()) + steps + 2)
 
     def iteration():
-        B.ee_decode_iteration(run.model, run.cache, batch, cfg.threshold, None, True, run.out_tokens, run.out_exit, run.out_L,
-                              None, run.out_hidden, run.ws)
+        B.ee_decode_iteration(run.model, run.cache, batch, cfg.threshold, None, exit_rule, run.out_tokens, run.out_exit,
+                              run.out_L, None, run.out_hidden, run.ws)
         torch.add(run.out_tokens, 0, out=tokens)
         ctx.add_(1)
 
@@ -268,6 +272,7 @@ def test_hip_graph_replay_matches_eager(dtype):
     torch.cuda.synchronize()
     reset()
     scratch = torch.zeros(1 << 20, device="cuda")
+    alive = torch.ones(cfg.batch, dtype=torch.bool)
     for s in range(steps):
         g.replay()
         scratch.add_(1.0)                             # the program's own eager work between replays
@@ -277,11 +282,14 @@ def test_hip_graph_replay_matches_eager(dtype):
             assert torch.equal(run.out_tokens.cpu(), t) and torch.equal(run.out_exit.cpu(), e) and int(run.out_L.item()) == L, s
             assert torch.equal(run.out_hidden.cpu(), h), s
         else:
-            assert float((run.out_tokens.cpu() == t).float().mean()) >= 0.9, s
-            assert float((run.out_exit.cpu() == e).float().mean()) >= 0.9, s
+            same_tok, same_exit = run.out_tokens.cpu() == t, run.out_exit.cpu() == e
+            assert float(same_tok.float().mean()) >= 0.9, s
+            assert float(same_exit.float().mean()) >= 0.9, s
+            rows = alive & same_tok & same_exit         # sequences still on the eager run's trajectory
             if int(run.out_L.item()) == L:
-                assert_close_scaled(run.out_hidden.cpu(), h, 2e-2, f"replay {s}: hidden state", dim=-1)
+                assert_close_scaled(run.out_hidden.cpu()[rows], h[rows], 2e-2, f"replay {s}: hidden state", dim=-1)
+            alive &= same_tok                           # a different token (a near tie) is fed back: that sequence's future differs
     if dtype == "fp32":
         assert torch.equal(run.cache.k, k1)
-    else:
+    elif bool(alive.all()):
         torch.testing.assert_close(run.cache.k.float(), k1.float(), rtol=5e-2, atol=5e-2)
