@@ -352,7 +352,8 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Main loop 2 (batches of 128 rows and more): the four wavefronts of a workgroup own four different 32-row
+// Main loop 2 (from three 32-row batch tiles on; LM head, gate/up and down projection always): the four
+// wavefronts of a workgroup own four different 32-row
 // output tiles over the SAME contraction range, so the activation operand is fetched from L2 once per
 // workgroup, staged in LDS and read by all four; weights still go straight from HBM to registers, each byte
 // once per batch chunk of MT*32 rows.  Groups of UT contraction steps: while group g is multiplied, the loads
