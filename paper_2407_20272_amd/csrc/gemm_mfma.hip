@@ -303,11 +303,29 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
   // stream.  With 384 tiles on 256 compute units this turns two rounds of workgroups into one and a half.
   const int bx = blockIdx.x;
   const bool half_tile = bx < 2 * g.split_tiles;
-  const int nt = half_tile ? g.tile_begin + g.n_tiles - g.split_tiles + (bx >> 1) : g.tile_begin + bx - 2 * g.split_tiles;
+  int tl = half_tile ? bx >> 1 : bx - 2 * g.split_tiles;   // tile within its class (halved / whole)
+  int khalf = bx & 1;
+  if constexpr (std::is_same<Epi, QkvEpi>::value) {
+    // Four consecutive tiles hold the 128 channels of one head (or two heads of 64): each writes 32-byte runs of
+    // the same cache lines of the paged cache (64-byte runs of q).  Workgroup ids congruent modulo 8 run on the
+    // same XCD behind the same L2, so the four tiles of a head get ids 8 apart: their partial lines meet in that
+    // L2 before they go to memory.  Only whole groups are rearranged (32 whole tiles = 8 heads x 4 tiles; 64 half
+    // tiles = 8 heads x 4 tiles x 2 halves, both halves of a tile on one XCD as well).
+    if (half_tile) {
+      if (bx < ((2 * g.split_tiles) & ~63)) {
+        const int q = (bx >> 3) & 7;
+        tl = (((bx >> 6) << 3) + (bx & 7)) * 4 + (q >> 1);
+        khalf = q & 1;
+      }
+    } else if (tl < ((g.n_tiles - g.split_tiles) & ~31)) {
+      tl = (tl & ~31) + ((tl & 7) << 2) + ((tl >> 3) & 3);
+    }
+  }
+  const int nt = half_tile ? g.tile_begin + g.n_tiles - g.split_tiles + tl : g.tile_begin + tl;
   const int nslices = half_tile ? 2 : 1;
   const int k_steps = g.K >> 4;
   const int chunks = gridDim.y * nslices * NW;
-  const int c = (blockIdx.y * nslices + (half_tile ? (bx & 1) : 0)) * NW + wave;
+  const int c = (blockIdx.y * nslices + (half_tile ? khalf : 0)) * NW + wave;
   const int ks0 = (int)((long)k_steps * c / chunks);
   const int ks1 = (int)((long)k_steps * (c + 1) / chunks);
   const int m_tiles = (g.M + 31) >> 5;
