@@ -183,6 +183,12 @@ def main():
               "sim": args.sim_threshold or SIM_THRESHOLD.get(args.config, 0.99),
               "cls": args.cls_threshold or CLS_THRESHOLD.get(args.config, 0.9)}
 
+    # Confidences of the instrumented pass only (None while the timed steps run): counts the decisions that sit
+    # within NEAR_TOL of their threshold, i.e. the ones float rounding could flip against another implementation.
+    NEAR_TOL = 1e-3
+    conf_all = torch.empty(n, Bsz, dtype=torch.float32, device="cuda")
+    conf_buf = None
+
     def iteration(mode):
         per_seq = args.per_sequence or mode.endswith("+ps")
         mode = mode.split("+")[0]
@@ -194,7 +200,7 @@ def main():
             f = forced_cur
         how = B.EE_EXIT_NONE if mode == "full" else (
             B.EE_EXIT_PER_SEQUENCE if per_seq and mode != "never" else B.EE_EXIT_BATCH)
-        B.ee_decode_iteration(variants.get(mode, model), cache, batch, thr, f, how, out_tok, out_exit, out_L, None, None, ws)
+        B.ee_decode_iteration(variants.get(mode, model), cache, batch, thr, f, how, out_tok, out_exit, out_L, conf_buf, None, ws)
         L_hist.scatter_add_(0, out_L.long(), one1)
         E_hist.scatter_add_(0, out_exit.long(), oneB)
         torch.add(out_tok, 0, out=tokens)          # next iteration consumes the tokens just produced
@@ -240,11 +246,18 @@ def main():
             ctx_before = ctx.clone()
             B.ee_profile_enable(True)
             Lp = []
+            near = torch.zeros(2, dtype=torch.int64, device="cuda")
+            conf_buf = conf_all if (mode.split("+")[0] not in ("full",) and forced_all is None) else None
             for s_ in range(P):
                 iteration(mode)
                 L_last[s_].copy_(out_L[0])
+                if conf_buf is not None:
+                    near[0] += ((conf_all - thr_of[mode.split("+")[0]]).abs() < NEAR_TOL).sum()
+                    near[1] += (~torch.isnan(conf_all)).sum()
+            conf_buf = None
             torch.cuda.synchronize()
             B.ee_profile_enable(False)
+            results[mode]["near_threshold"] = {"tol": NEAR_TOL, "count": int(near[0]), "decisions": int(near[1]), "steps": P}
             recs = B.ee_profile_read()
             Lp = L_last[:P].cpu().tolist()
             mean_ctx1 = float(ctx_before.float().mean()) + 1 + (P - 1) / 2.0
