@@ -8,6 +8,8 @@
 // Lanes that share a token add their partial dot products with a butterfly; every group of lanes keeps its own
 // running softmax (max, sum, weighted V) over the tokens it sees, and the groups, then the wavefronts, are merged
 // once at the end.  No score is ever written to memory.
+#include <type_traits>
+
 #include "ee_common.h"
 #include "ee_epilogue.h"
 
@@ -421,6 +423,216 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a, Pred pred) {
   }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Sixteen batch rows of a prompt chunk per workgroup on the matrix cores (bf16 cache).  A workgroup owns 16
+// consecutive batch rows of one head; rows of one sequence form a run whose K/V blocks are streamed ONCE, 32
+// tokens per wavefront step, and multiplied against all 16 rows with v_mfma_f32_16x16x32_bf16:
+//   scores^T [token][row] = K [token][dh] . q^T [dh][row]      (K straight from the cache as the A operand)
+//   out^T    [dh][row]   += V^T [dh][token] . p^T [token][row]  (V transposed through a per-wavefront LDS tile)
+// With the transposed products a lane holds everything of ONE row (row = lane % 16): its 8 scores of the step,
+// its running maximum and its slice of the output, so the online softmax needs two shuffles per step and the
+// probabilities go from the score registers into the next product without leaving the lane (the contraction
+// slots of the second product are simply numbered in the order the first one delivers the tokens).
+// q and the probabilities stay float in effect: each is split into a bf16 head and a bf16 remainder and
+// multiplied twice.  Rows outside the current run, and positions after a row's own, are masked.
+// ---------------------------------------------------------------------------------------------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int CHUNK_ROWS = 16;
+constexpr int VPITCH = 34;   // bf16 per transposed V row in LDS: 32 tokens + 2 (keeps the 8 writes of a lane group on separate banks)
+
+template <int DH, bool OUT_XT>
+__global__ __launch_bounds__(256) void attn_chunk_kernel(AttnArgs a, Pred pred) {
+  constexpr int CH = DH / 32;   // 32-channel contraction steps of q . K
+  constexpr int DT = DH / 16;   // 16-channel tiles of the output
+  constexpr int VS_BYTES = NW * DH * VPITCH * 2;
+  constexpr int SO_BYTES = NW * CHUNK_ROWS * DH * 4;
+  extern __shared__ int32_t tbl[];
+  __shared__ __align__(16) unsigned char smem[VS_BYTES > SO_BYTES ? VS_BYTES : SO_BYTES];
+  __shared__ int s_seq[CHUNK_ROWS], s_npos[CHUNK_ROWS];
+  __shared__ float sm[NW][CHUNK_ROWS], sl[NW][CHUNK_ROWS];
+  if (pred_skip(pred)) return;
+
+  const int head = blockIdx.x, row0 = blockIdx.y * CHUNK_ROWS;
+  const int nrows = min(CHUNK_ROWS, a.B - row0);
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int i16 = lane & 15, g = lane >> 4;
+  const int my_row = row0 + i16;
+  const bool row_ok = i16 < nrows;
+  const int my_seq = row_ok ? a.row_table[my_row] : -1;
+  const int my_npos = row_ok ? min(a.context_lens[my_row] + 1, a.max_blocks * 16) : 0;
+  if (threadIdx.x < CHUNK_ROWS) {
+    s_seq[i16] = my_seq;
+    s_npos[i16] = my_npos;
+  }
+
+  // q of this lane's row, channels c*32 + g*8 .. +8 of every contraction step, scaled, as bf16 head + remainder
+  const float sc = 1.4426950408889634f / sqrtf((float)DH);
+  bf16x8_t qh[CH], ql[CH];
+  {
+    const float* qp = a.q + ((size_t)(row_ok ? my_row : row0) * a.n_heads + head) * DH + g * 8;
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      const float4 lo = *reinterpret_cast<const float4*>(qp + c * 32);
+      const float4 hi = *reinterpret_cast<const float4*>(qp + c * 32 + 4);
+      const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = row_ok ? v[e] * sc : 0.0f;
+        const __bf16 h = (__bf16)x;
+        qh[c][e] = h;
+        ql[c][e] = (__bf16)(x - (float)h);
+      }
+    }
+  }
+
+  float m_run = NEG_BIG, l_run = 0.0f;
+  f32x4_t o[DT];
+#pragma unroll
+  for (int d = 0; d < DT; ++d) o[d] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+  const size_t block_elems = (size_t)a.n_heads * 16 * DH;
+  const size_t lane_off = (size_t)head * 16 * DH + (size_t)i16 * DH + g * 8;   // token i16 of a block, channels g*8..
+  const bf16_t* kbase = reinterpret_cast<const bf16_t*>(a.k_pool) + lane_off;
+  const bf16_t* vbase = reinterpret_cast<const bf16_t*>(a.v_pool) + lane_off;
+  __bf16 (*vw)[VPITCH] = reinterpret_cast<__bf16 (*)[VPITCH]>(smem + (size_t)wave * DH * VPITCH * 2);
+
+  __syncthreads();
+  int r_begin = 0;
+  while (r_begin < nrows) {
+    // the run: rows r_begin .. r_end-1 of one sequence (uniform over the workgroup)
+    const int run_seq = __builtin_amdgcn_readfirstlane(s_seq[r_begin]);
+    int r_end = r_begin + 1;
+    while (r_end < nrows && __builtin_amdgcn_readfirstlane(s_seq[r_end]) == run_seq) ++r_end;
+    int run_ctx = 0;
+    for (int r = r_begin; r < r_end; ++r) run_ctx = max(run_ctx, __builtin_amdgcn_readfirstlane(s_npos[r]));
+    const int n_blocks = (run_ctx + 15) >> 4;
+    const int n_steps = (n_blocks + 1) >> 1;
+    const int32_t* table = a.block_tables + (size_t)run_seq * a.max_blocks;
+    __syncthreads();   // the previous run's table is no longer read
+    for (int x = threadIdx.x; x < n_blocks; x += blockDim.x) tbl[x] = table[x];
+    __syncthreads();
+    const int npos_eff = (i16 >= r_begin && i16 < r_end) ? my_npos : 0;
+
+    for (int s = wave; s < n_steps; s += NW) {
+      // two 16-token blocks; an odd block count reads the last block twice (its second copy is masked)
+      const int lb1 = min(2 * s + 1, n_blocks - 1);
+      const size_t off[2] = {(size_t)__builtin_amdgcn_readfirstlane(tbl[2 * s]) * block_elems,
+                             (size_t)__builtin_amdgcn_readfirstlane(tbl[lb1]) * block_elems};
+      u32x4_t kt[2][CH], vt[2][CH];
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+          kt[t][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(kbase + off[t] + c * 32));
+          vt[t][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(vbase + off[t] + c * 32));
+        }
+      // scores^T of the 32 tokens: lane (i16, g) gets tokens 4g..4g+3 of each block for row i16
+      f32x4_t st[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        st[t] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+          const bf16x8_t kk = __builtin_bit_cast(bf16x8_t, kt[t][c]);
+          st[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, qh[c], st[t], 0, 0, 0);
+          st[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kk, ql[c], st[t], 0, 0, 0);
+        }
+      }
+      float sv[8];
+      float mx = m_run;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int tok = s * 32 + t * 16 + 4 * g + r;
+          sv[t * 4 + r] = tok < npos_eff ? st[t][r] : NEG_BIG;
+          mx = fmaxf(mx, sv[t * 4 + r]);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float alpha = __builtin_amdgcn_exp2f(m_run - mx);
+      m_run = mx;
+      l_run *= alpha;
+#pragma unroll
+      for (int d = 0; d < DT; ++d) o[d] *= alpha;
+      bf16x8_t ph, pl;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int tok = s * 32 + t * 16 + 4 * g + r;
+          const float p = tok < npos_eff ? __builtin_amdgcn_exp2f(sv[t * 4 + r] - mx) : 0.0f;
+          l_run += p;
+          const __bf16 h = (__bf16)p;
+          ph[t * 4 + r] = h;
+          pl[t * 4 + r] = (__bf16)(p - (float)h);
+        }
+      // V of the 32 tokens, transposed into this wavefront's LDS tile: vw[channel][token]
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+          const bf16x8_t vv = __builtin_bit_cast(bf16x8_t, vt[t][c]);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) vw[c * 32 + g * 8 + e][t * 16 + i16] = vv[e];
+        }
+      // out^T += V^T . p^T; contraction slot e of lane group g is token 4g+e of the first block (e < 4) or
+      // token 4g+e-4 of the second: the order in which ph / pl hold the probabilities
+#pragma unroll
+      for (int d = 0; d < DT; ++d) {
+        const __bf16* rowp = &vw[16 * d + i16][0];
+        bf16x8_t va;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          va[e] = rowp[4 * g + e];
+          va[4 + e] = rowp[16 + 4 * g + e];
+        }
+        o[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, ph, o[d], 0, 0, 0);
+        o[d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pl, o[d], 0, 0, 0);
+      }
+    }
+    r_begin = r_end;
+  }
+
+  // the four lane groups of a row hold partial sums of the same maximum; then merge the wavefronts row by row
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  __syncthreads();   // every wavefront is done with its V tile: the space now holds the partial outputs
+  float (*so)[CHUNK_ROWS][DH] = reinterpret_cast<float (*)[CHUNK_ROWS][DH]>(smem);
+#pragma unroll
+  for (int d = 0; d < DT; ++d)
+    *reinterpret_cast<float4*>(&so[wave][i16][16 * d + 4 * g]) = make_float4(o[d][0], o[d][1], o[d][2], o[d][3]);
+  if (g == 0) {
+    sm[wave][i16] = m_run;
+    sl[wave][i16] = l_run;
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < nrows * DH; t += blockDim.x) {
+    const int r = t / DH, c = t - r * DH;
+    float M = sm[0][r];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) M = fmaxf(M, sm[w][r]);
+    float L = 0.0f, acc = 0.0f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float wgt = __builtin_amdgcn_exp2f(sm[w][r] - M);
+      L += sl[w][r] * wgt;
+      acc += so[w][r][c] * wgt;
+    }
+    const float res = acc / L;
+    const int col = head * DH + c;
+    if constexpr (OUT_XT) {
+      reinterpret_cast<bf16_t*>(a.out)[xt_index(row0 + r, col, a.n_heads * DH)] = (bf16_t)res;
+    } else {
+      reinterpret_cast<float*>(a.out)[(size_t)(row0 + r) * a.n_heads * DH + col] = res;
+    }
+  }
+}
+
 // Four rows per workgroup measured best at the 7B shape (eight: 300 registers, one wavefront per SIMD, slower).
 constexpr int ROWS_PER_GROUP = 4;
 
@@ -429,6 +641,14 @@ void launch_t(const AttnArgs& a, Pred pred, hipStream_t st) {
   dim3 block(256);
   const size_t lds = (size_t)a.max_blocks * sizeof(int32_t);
   if (a.row_table) {   // rows share sequences: stream every sequence's K/V once per group of rows
+    if constexpr (std::is_same<T, bf16_t>::value) {
+      dim3 grid16(a.n_heads, (a.B + CHUNK_ROWS - 1) / CHUNK_ROWS);
+      if (a.out_xt)
+        hipLaunchKernelGGL((attn_chunk_kernel<DH, true>), grid16, block, lds, st, a, pred);
+      else
+        hipLaunchKernelGGL((attn_chunk_kernel<DH, false>), grid16, block, lds, st, a, pred);
+      return;
+    }
     dim3 grid(a.n_heads, (a.B + ROWS_PER_GROUP - 1) / ROWS_PER_GROUP);
     if (a.out_xt)
       hipLaunchKernelGGL((attn_rows_kernel<T, DH, ROWS_PER_GROUP, true>), grid, block, lds, st, a, pred);

@@ -81,6 +81,34 @@ def test_attention_rows_sharing_one_block_table():
         assert_close_scaled(out[r].cpu(), want, tol_of(cfg), f"row {r} at position {n - 1}")
 
 
+@pytest.mark.parametrize("dh", [64, 128])
+def test_attention_rows_of_several_sequences_across_row_groups(dh):
+    """Rows of three sequences in one call (row_table), runs of 20, 5 and 17 rows: the 16-row groups of the
+    matrix-core kernel straddle the runs, the last group is ragged, block counts are odd and even."""
+    cfg = cfg_of("bf16", dh, 2).with_(batch=3, shuffled_blocks=True)
+    lens = torch.tensor([69, 4, 199], dtype=torch.int32)        # last cached position of each sequence
+    Lmax = int(lens.max()) + 1
+    Ks, Vs = W.make_dense_kv(cfg, lens + 1, Lmax, seed=15, device="cuda")
+    bt, nb = W.make_block_tables(lens, 1, 16, True, 15, spare_blocks=2)
+    cache = B.PagedKV(cfg, nb)
+    for i in range(cfg.n_layers):
+        cache.k[i] = W.dense_to_paged(Ks[i], bt, nb, 16)
+        cache.v[i] = W.dense_to_paged(Vs[i], bt, nb, 16)
+    rows = [(0, p) for p in range(50, 70)] + [(1, p) for p in range(0, 5)] + [(2, p) for p in range(183, 200)]
+    R = len(rows)
+    pos = torch.tensor([p for _, p in rows], dtype=torch.int32)
+    seq = torch.tensor([s_ for s_, _ in rows], dtype=torch.int32)
+    q = torch.randn(R, cfg.n_heads, cfg.head_dim, generator=torch.Generator().manual_seed(15)) * 1.5
+    out = torch.zeros(R, cfg.n_heads, cfg.head_dim, device="cuda")
+    batch = B.make_batch(None, pos.cuda(), bt.cuda(), Lmax, seq.cuda())
+    B.ee_paged_attention_decode(B.make_desc(cfg), cache, 1, q.cuda(), batch, out)
+    torch.cuda.synchronize()
+    Kc, Vc = Ks[0].cpu(), Vs[0].cpu()
+    for r, (s_, p_) in enumerate(rows):
+        want = O.attention_decode(q[r].to(F64), Kc[s_, :p_ + 1], Vc[s_, :p_ + 1])
+        assert_close_scaled(out[r].cpu(), want, tol_of(cfg), f"row {r}: sequence {s_} at position {p_}")
+
+
 def test_attention_single_sequence_and_sequential_blocks():
     run_attention(cfg_of("bf16", 128, 2), [300], seed=12, shuffled=False)
     run_attention(cfg_of("fp32", 64, 4), [47], seed=13, shuffled=False)
