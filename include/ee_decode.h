@@ -19,8 +19,11 @@
  *   - Return value: EE_OK, or a negative error code.  Arguments are validated on
  *     the host before anything is launched; on error nothing has been enqueued.
  *     ee_last_error() returns a thread-local message for the last failing call.
- *     Data errors that only the device can see (a block id >= num_blocks, a token
- *     id >= vocab) are the caller's contract.
+ *     Data errors that only the device can see (a block id outside 0..num_blocks-1,
+ *     a position outside the block table, a token id outside 0..vocab-1) are the
+ *     caller's contract: the result for such a sequence is unspecified.  The kernels
+ *     keep such an access inside the caller's buffers all the same (the id is read as
+ *     0, the cache write is dropped), so bad data cannot fault the device.
  *   - dtype EE_FP32: weights, activations and KV cache are float; matrices are plain
  *     row-major [out_features][in_features].
  *     dtype EE_BF16: weights, embedding, gains and KV cache are bfloat16; matrices

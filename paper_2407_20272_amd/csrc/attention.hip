@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   // Everything the first K/V load needs is requested before any of it is waited for: the context length, the
   // start of the block-table row (its width is known without the length) and q: one memory round trip, not
   // three in a row.
-  const int t0 = (int)threadIdx.x < a.max_blocks ? table[threadIdx.x] : 0;
+  const int t0 = (int)threadIdx.x < a.max_blocks ? safe_block(table[threadIdx.x], a.num_blocks) : 0;
   const int len = a.context_lens[b];
   const int left = a.skip ? a.skip[b] : 0;
   const int out_row = a.out_pos ? a.out_pos[b] : b;
@@ -109,7 +109,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   // The sequence's block table goes to LDS once (max_blocks entries of dynamic LDS).  The block loop must not
   // read it from memory: the wait for such a read would also wait for every K/V load issued before it.
   if ((int)threadIdx.x < a.max_blocks) tbl[threadIdx.x] = t0;
-  for (int i = threadIdx.x + blockDim.x; i < n_blocks; i += blockDim.x) tbl[i] = table[i];
+  for (int i = threadIdx.x + blockDim.x; i < n_blocks; i += blockDim.x) tbl[i] = safe_block(table[i], a.num_blocks);
 
   // q slice, pre-scaled so that exp2 can be used: softmax(x) = 2^(x*log2 e)
   {
@@ -310,7 +310,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a, Pred pred) {
     const int n_blocks = (run_ctx + 15) >> 4;
     const int32_t* table = a.block_tables + (size_t)run_seq * a.max_blocks;
     __syncthreads();   // the previous run's table is no longer read
-    for (int i = threadIdx.x; i < n_blocks; i += blockDim.x) tbl[i] = table[i];
+    for (int i = threadIdx.x; i < n_blocks; i += blockDim.x) tbl[i] = safe_block(table[i], a.num_blocks);
     __syncthreads();
 
     auto fetch = [&](Blk& x, int lb) {
@@ -513,7 +513,7 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(AttnArgs a, Pred pred) 
     const int n_steps = (n_blocks + 1) >> 1;
     const int32_t* table = a.block_tables + (size_t)run_seq * a.max_blocks;
     __syncthreads();   // the previous run's table is no longer read
-    for (int x = threadIdx.x; x < n_blocks; x += blockDim.x) tbl[x] = table[x];
+    for (int x = threadIdx.x; x < n_blocks; x += blockDim.x) tbl[x] = safe_block(table[x], a.num_blocks);
     __syncthreads();
     const int npos_eff = (i16 >= r_begin && i16 < r_end) ? my_npos : 0;
 

@@ -252,6 +252,7 @@ QkvEpi make_qkv_epi(const ee_model_desc& D, const ee_kv_cache& C, const ee_batch
   e.rope_theta = D.rope_theta;
   e.rowsq = nullptr;
   e.eps = D.rms_eps;
+  e.num_blocks = C.num_blocks;
   return e;
 }
 
@@ -448,11 +449,11 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     launch_iter_init(s, B, n, out_conf, bf ? w.rowsq : nullptr, bf ? w.zero_count : 0, st);
     launch_rope_table(batch->context_lens, w.rope, B, D.head_dim, D.rope_theta, st);
     if (bf) {
-      launch_embed_bf16(reinterpret_cast<const bf16_t*>(model->embed), batch->tokens, w.hT, B, Mpad, d, st);
+      launch_embed_bf16(reinterpret_cast<const bf16_t*>(model->embed), batch->tokens, w.hT, B, Mpad, d, D.vocab, st);
       launch_rowsq(w.hT, rs(0), Mpad, d, always, st);
       if (compact) launch_compact(w.status, B, rmap, nullptr, 0, Mpad, always, st);   // nobody has left: identity
     } else {
-      launch_embed_f32(reinterpret_cast<const float*>(model->embed), batch->tokens, w.h, B, d, st);
+      launch_embed_f32(reinterpret_cast<const float*>(model->embed), batch->tokens, w.h, B, d, D.vocab, st);
       if (simmode) launch_copy_f32(w.h, w.hprev, (size_t)B * d, st);   // h_0, the "previous" state of layer 1
     }
   }
@@ -463,7 +464,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     const size_t pool_off = pool_layer_elems(D, *cache) * elem_bytes(D) * (size_t)(i - 1);
     AttnArgs at{w.q, reinterpret_cast<char*>(cache->k_pool) + pool_off, reinterpret_cast<char*>(cache->v_pool) + pool_off,
                 batch->context_lens, batch->block_tables, batch->max_blocks, B, D.n_heads, D.head_dim, nullptr, 0, left,
-                batch->row_table, rmap.cpos};
+                batch->row_table, rmap.cpos, cache->num_blocks};
     const bool head_here = use_exit_heads && has_head(D, i);
     if (bf) {
       if (i == 1) {
@@ -735,7 +736,7 @@ int ee_paged_attention_decode(const ee_model_desc* desc, const ee_kv_cache* cach
   const size_t off = pool_layer_elems(*desc, *cache) * elem_bytes(*desc) * (size_t)(layer - 1);
   AttnArgs at{q, reinterpret_cast<char*>(cache->k_pool) + off, reinterpret_cast<char*>(cache->v_pool) + off,
               batch->context_lens, batch->block_tables, batch->max_blocks, batch->batch, desc->n_heads, desc->head_dim,
-              out, 0, nullptr, batch->row_table};
+              out, 0, nullptr, batch->row_table, nullptr, cache->num_blocks};
   const Pred always{nullptr, 0};
   if ((rc = launch_attention(at, desc->dtype, always, reinterpret_cast<hipStream_t>(stream)))) return rc;
   EE_HIP(hipGetLastError());

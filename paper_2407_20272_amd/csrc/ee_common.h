@@ -87,6 +87,7 @@ struct QkvEpi {                 // rotary embedding + paged cache write (+ q out
   const float2* rope;           // [M][dh/2] (cos, sin) of the rotary angles at context_lens[m] (rope_theta > 0)
   const float* rowsq;           // nullptr, or [M] sum of squares of the hidden row: value *= rsqrt(rowsq/d + eps)
   float eps;
+  int num_blocks;               // blocks per layer of the pools: a slot whose block id or position is out of range is not written
 };
 struct AccEpi {                 // h += value
   float* h;
@@ -129,8 +130,8 @@ struct Pred {
 // misc.hip
 void launch_iter_init(const IterState& s, int B, int n_layers, float* conf_out, float* zero_buf, size_t zero_count,
                       hipStream_t st);
-void launch_embed_bf16(const bf16_t* E, const int32_t* tokens, float* hT, int B, int Mpad, int d, hipStream_t st);
-void launch_embed_f32(const float* E, const int32_t* tokens, float* h, int B, int d, hipStream_t st);
+void launch_embed_bf16(const bf16_t* E, const int32_t* tokens, float* hT, int B, int Mpad, int d, int vocab, hipStream_t st);
+void launch_embed_f32(const float* E, const int32_t* tokens, float* h, int B, int d, int vocab, hipStream_t st);
 void launch_hidden_to_ht(const float* plain, float* hT, int B, int Mpad, int d, hipStream_t st);
 void launch_ht_to_hidden(const float* hT, float* plain, int B, int Mpad, int d, hipStream_t st);
 void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t st);
@@ -266,6 +267,10 @@ void launch_simple_gateup(const SimpleShape& g, const GateUpEpi& e, Pred pred, h
 void launch_simple_lm(const SimpleShape& g, const LmEpi& e, Pred pred, hipStream_t st);
 
 // attention.hip
+// Block ids and positions come from device memory the caller filled in; the kernels never let them reach outside
+// the pools or the block table (the result for such a sequence is unspecified, the access is not).
+__host__ __device__ inline int safe_block(int blk, int num_blocks) { return (unsigned)blk < (unsigned)num_blocks ? blk : 0; }
+
 struct AttnArgs {
   const float* q;               // [B][H*dh] fp32, rotary applied
   const void* k_pool;           // layer base
@@ -278,6 +283,7 @@ struct AttnArgs {
   const int32_t* skip;          // nullptr, or [B]: sequences with skip[b] != 0 are not attended (they have left)
   const int32_t* row_table;     // nullptr, or [B]: row b uses row row_table[b] of block_tables
   const int32_t* out_pos;       // nullptr, or [B]: the result of sequence b goes to row out_pos[b] of out (compacted operand)
+  int num_blocks;               // blocks per layer of the pools: a block id outside 0..num_blocks-1 is read as block 0
 };
 int launch_attention(const AttnArgs& a, int dtype, Pred pred, hipStream_t st);
 

@@ -212,13 +212,14 @@ __device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, con
         const int mm = mt_global * 32 + mr;
         if (mm < g.M && !(e.fill_from && !(e.fill_from[(size_t)mm * e.fill_from_stride] < e.layer))) {
           const int p = e.context_lens[mm];
-          const int blk = e.block_tables[(size_t)(e.row_table ? e.row_table[mm] : mm) * e.max_blocks + (p >> 4)];
+          const bool p_ok = (unsigned)p < (unsigned)(e.max_blocks * 16);
+          const int blk = e.block_tables[(size_t)(e.row_table ? e.row_table[mm] : mm) * e.max_blocks + (p_ok ? p >> 4 : 0)];
           const size_t at = (((size_t)blk * e.n_heads + head) * 16 + (p & 15)) * dh + j0 + run * hdim + (part & 1) * 8;
           bf16x8 v;
 #pragma unroll
           for (int i = 0; i < 8; ++i) v[i] = (bf16_t)s.zt[c0 + i][mr];
           bf16_t* pool = reinterpret_cast<bf16_t*>(which == 1 ? e.k_pool : e.v_pool);
-          *reinterpret_cast<bf16x8*>(pool + at) = v;
+          if (p_ok && (unsigned)blk < (unsigned)e.num_blocks) *reinterpret_cast<bf16x8*>(pool + at) = v;
         }
       }
     } else {

@@ -26,18 +26,23 @@ __global__ void iter_init_kernel(IterState s, int B, int n_layers, float* conf_o
 }
 
 // hidden_states <- Embed(input_tokens): one row gather per sequence; padding rows of the last tile are zero.
-__global__ void embed_bf16_kernel(const bf16_t* E, const int32_t* tokens, float* hT, int B, int Mpad, int d) {
+// A token id outside 0..vocab-1 reads row 0 (the result is unspecified, the access stays inside the table).
+__global__ void embed_bf16_kernel(const bf16_t* E, const int32_t* tokens, float* hT, int B, int Mpad, int d, int vocab) {
   const int k = blockIdx.x * blockDim.y + threadIdx.y;
   const int m = blockIdx.y * 32 + threadIdx.x;
   if (k >= d || m >= Mpad) return;
   float v = 0.0f;
-  if (m < B) v = (float)E[(size_t)tokens[m] * d + k];
+  if (m < B) {
+    const int tok = tokens[m];
+    v = (float)E[(size_t)((unsigned)tok < (unsigned)vocab ? tok : 0) * d + k];
+  }
   hT[ht_index(m, k, Mpad)] = v;
 }
-__global__ void embed_f32_kernel(const float* E, const int32_t* tokens, float* h, int B, int d) {
+__global__ void embed_f32_kernel(const float* E, const int32_t* tokens, float* h, int B, int d, int vocab) {
   const int k = blockIdx.x * blockDim.x + threadIdx.x;
   const int m = blockIdx.y;
-  if (k < d) h[(size_t)m * d + k] = E[(size_t)tokens[m] * d + k];
+  const int tok = tokens[m];
+  if (k < d) h[(size_t)m * d + k] = E[(size_t)((unsigned)tok < (unsigned)vocab ? tok : 0) * d + k];
 }
 
 __global__ void hidden_to_ht_kernel(const float* plain, float* hT, int B, int Mpad, int d) {
@@ -346,11 +351,11 @@ void launch_iter_init(const IterState& s, int B, int n_layers, float* conf_out, 
   if (blocks > 1024) blocks = 1024;
   hipLaunchKernelGGL(iter_init_kernel, dim3(blocks), dim3(256), 0, st, s, B, n_layers, conf_out, zero_buf, zero_count);
 }
-void launch_embed_bf16(const bf16_t* E, const int32_t* tokens, float* hT, int B, int Mpad, int d, hipStream_t st) {
-  hipLaunchKernelGGL(embed_bf16_kernel, dim3((d + 7) / 8, Mpad / 32), dim3(32, 8), 0, st, E, tokens, hT, B, Mpad, d);
+void launch_embed_bf16(const bf16_t* E, const int32_t* tokens, float* hT, int B, int Mpad, int d, int vocab, hipStream_t st) {
+  hipLaunchKernelGGL(embed_bf16_kernel, dim3((d + 7) / 8, Mpad / 32), dim3(32, 8), 0, st, E, tokens, hT, B, Mpad, d, vocab);
 }
-void launch_embed_f32(const float* E, const int32_t* tokens, float* h, int B, int d, hipStream_t st) {
-  hipLaunchKernelGGL(embed_f32_kernel, dim3((d + 255) / 256, B), dim3(256), 0, st, E, tokens, h, B, d);
+void launch_embed_f32(const float* E, const int32_t* tokens, float* h, int B, int d, int vocab, hipStream_t st) {
+  hipLaunchKernelGGL(embed_f32_kernel, dim3((d + 255) / 256, B), dim3(256), 0, st, E, tokens, h, B, d, vocab);
 }
 void launch_hidden_to_ht(const float* plain, float* hT, int B, int Mpad, int d, hipStream_t st) {
   hipLaunchKernelGGL(hidden_to_ht_kernel, dim3((d + 7) / 8, Mpad / 32), dim3(32, 8), 0, st, plain, hT, B, Mpad, d);
