@@ -20,7 +20,8 @@
  *     the host before anything is launched; on error nothing has been enqueued.
  *     ee_last_error() returns a thread-local message for the last failing call.
  *     Data errors that only the device can see (a block id outside 0..num_blocks-1,
- *     a position outside the block table, a token id outside 0..vocab-1) are the
+ *     a position outside the block table, a row_table entry outside 0..B-1, a token
+ *     id outside 0..vocab-1) are the
  *     caller's contract: the result for such a sequence is unspecified.  The kernels
  *     keep such an access inside the caller's buffers all the same (the id is read as
  *     0, the cache write is dropped), so bad data cannot fault the device.
@@ -112,7 +113,8 @@ typedef struct ee_batch {
   int32_t batch;               /* B >= 0; B == 0 is a no-op that still returns EE_OK                     */
   const int32_t* tokens;       /* dev [B]: token each sequence consumes this iteration                   */
   const int32_t* context_lens; /* dev [B]: p_b = positions already cached; the new K/V go to position p_b */
-  const int32_t* block_tables; /* dev [B][max_blocks]: physical block of each logical block              */
+  const int32_t* block_tables; /* dev [B][max_blocks]: physical block of each logical block (with row_table:
+                                  one row per sequence, at least max(row_table) + 1 rows)                */
   int32_t max_blocks;          /* row pitch of block_tables                                              */
   int32_t max_context;         /* host-side upper bound of context_lens[b] + 1 (sizes the attention grid) */
   const int32_t* row_table;    /* dev [B] or NULL.  NULL: row b of the batch uses row b of block_tables.  Else

@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int sub = lane % LPT;              // which EPL-wide slice of the head this lane holds
   const int grp = lane / LPT;              // which token of a load this lane sees
-  const int32_t* table = a.block_tables + (size_t)(a.row_table ? a.row_table[b] : b) * a.max_blocks;
+  const int32_t* table = a.block_tables + (size_t)(a.row_table ? safe_row(a.row_table[b], a.B) : b) * a.max_blocks;
 
   extern __shared__ int32_t tbl[];
   if (pred_skip(pred)) return;
@@ -274,7 +274,7 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a, Pred pred) {
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const bool valid = r < nrows;
-    seq[r] = valid ? a.row_table[row0 + r] : -1;
+    seq[r] = valid ? safe_row(a.row_table[row0 + r], a.B) : -1;
     npos[r] = valid ? min(a.context_lens[row0 + r] + 1, a.max_blocks * 16) : 0;
     const float* qp = a.q + ((size_t)(valid ? row0 + r : row0) * a.n_heads + head) * DH + sub * EPL;
 #pragma unroll
@@ -462,7 +462,7 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(AttnArgs a, Pred pred) 
   const int i16 = lane & 15, g = lane >> 4;
   const int my_row = row0 + i16;
   const bool row_ok = i16 < nrows;
-  const int my_seq = row_ok ? a.row_table[my_row] : -1;
+  const int my_seq = row_ok ? safe_row(a.row_table[my_row], a.B) : -1;
   const int my_npos = row_ok ? min(a.context_lens[my_row] + 1, a.max_blocks * 16) : 0;
   if (threadIdx.x < CHUNK_ROWS) {
     s_seq[i16] = my_seq;

@@ -253,6 +253,7 @@ QkvEpi make_qkv_epi(const ee_model_desc& D, const ee_kv_cache& C, const ee_batch
   e.rowsq = nullptr;
   e.eps = D.rms_eps;
   e.num_blocks = C.num_blocks;
+  e.table_rows = Bt.batch;
   return e;
 }
 

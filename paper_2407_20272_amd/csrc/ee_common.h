@@ -88,6 +88,7 @@ struct QkvEpi {                 // rotary embedding + paged cache write (+ q out
   const float* rowsq;           // nullptr, or [M] sum of squares of the hidden row: value *= rsqrt(rowsq/d + eps)
   float eps;
   int num_blocks;               // blocks per layer of the pools: a slot whose block id or position is out of range is not written
+  int table_rows;               // rows of block_tables (the batch size): a row_table entry outside 0..table_rows-1 is read as 0
 };
 struct AccEpi {                 // h += value
   float* h;
@@ -270,6 +271,7 @@ void launch_simple_lm(const SimpleShape& g, const LmEpi& e, Pred pred, hipStream
 // Block ids and positions come from device memory the caller filled in; the kernels never let them reach outside
 // the pools or the block table (the result for such a sequence is unspecified, the access is not).
 __host__ __device__ inline int safe_block(int blk, int num_blocks) { return (unsigned)blk < (unsigned)num_blocks ? blk : 0; }
+__host__ __device__ inline int safe_row(int row, int n_rows) { return (unsigned)row < (unsigned)n_rows ? row : 0; }
 
 struct AttnArgs {
   const float* q;               // [B][H*dh] fp32, rotary applied

@@ -46,7 +46,7 @@ __device__ inline void epi_qkv(const QkvEpi& e, int m, int f_lo, float lo, float
     return;
   }
   const bool p_ok = (unsigned)p < (unsigned)(e.max_blocks * 16);
-  const int blk = e.block_tables[(size_t)(e.row_table ? e.row_table[m] : m) * e.max_blocks + (p_ok ? p >> 4 : 0)];
+  const int blk = e.block_tables[(size_t)(e.row_table ? safe_row(e.row_table[m], e.table_rows) : m) * e.max_blocks + (p_ok ? p >> 4 : 0)];
   if (!p_ok || (unsigned)blk >= (unsigned)e.num_blocks) return;   // never outside the pools
   const size_t at = (((size_t)blk * e.n_heads + head) * 16 + (p & 15)) * dh + j;
   T* pool = reinterpret_cast<T*>(which == 1 ? e.k_pool : e.v_pool);

@@ -213,7 +213,7 @@ __device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, con
         if (mm < g.M && !(e.fill_from && !(e.fill_from[(size_t)mm * e.fill_from_stride] < e.layer))) {
           const int p = e.context_lens[mm];
           const bool p_ok = (unsigned)p < (unsigned)(e.max_blocks * 16);
-          const int blk = e.block_tables[(size_t)(e.row_table ? e.row_table[mm] : mm) * e.max_blocks + (p_ok ? p >> 4 : 0)];
+          const int blk = e.block_tables[(size_t)(e.row_table ? safe_row(e.row_table[mm], e.table_rows) : mm) * e.max_blocks + (p_ok ? p >> 4 : 0)];
           const size_t at = (((size_t)blk * e.n_heads + head) * 16 + (p & 15)) * dh + j0 + run * hdim + (part & 1) * 8;
           bf16x8 v;
 #pragma unroll
