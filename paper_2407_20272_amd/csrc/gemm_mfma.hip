@@ -657,8 +657,8 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
     // tiled kernel: the workgroup's output tiles share the activation operand through LDS
     const int chunks = (m_tiles + 3) / 4;
     // One output tile per wavefront.  Two per wavefront (NTW = 2: each LDS operand read feeds two MFMAs, half the
-    // workgroups) measured slower at batch 256 and 512: the kernel is limited by loads in flight per compute unit,
-    // not by LDS bandwidth.
+    // workgroups) measured slower at batch 256 and 512 for every shape but the LM head: halving the LDS reads per
+    // MFMA does not pay by itself, so LDS bandwidth alone is not what limits the kernel.
     const int groups = g.n_tiles / NW;
     int ksplit = 1;
     if constexpr (std::is_same<Epi, AccEpi>::value) {
