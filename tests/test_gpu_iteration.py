@@ -53,6 +53,15 @@ def test_small_bf16_lockstep(batch):
     assert len(set(stats["L"])) >= 1
 
 
+def test_bf16_width_1280_partly_rearranged_tile_order():
+    """d_model 1280 (10 heads x 128): the QKV projection has 80 whole and 40 halved tiles, so the XCD-aware tile
+    order of the streaming kernel rearranges 64 of each and leaves the rest in place; KV filling runs too."""
+    cfg = small_bf16(d_model=1280, n_heads=10, head_dim=128, n_layers=3, batch=7, threshold=0.35, shuffled_blocks=True)
+    stats = lockstep(cfg, seed=61, steps=4)
+    total = stats["decisions"] + stats["tokens"]
+    assert stats["near_threshold"] + stats["near_tie"] <= max(2, total // 20), stats
+
+
 def test_small_bf16_head_dim_64_exit_every_2_mode1():
     cfg = small_bf16(n_heads=4, head_dim=64, n_layers=6, exit_every=2, conf_mode=1, batch=9, threshold=0.3)
     lockstep(cfg, seed=21, steps=4)

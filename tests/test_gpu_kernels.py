@@ -291,6 +291,13 @@ def test_kv_fill_uniform_layer_and_many_rows():
     run_kv_fill(cfg, 52, lens=[9, 10], fill_from=[4, 4])                           # nothing to fill
 
 
+def test_kv_fill_width_1280_partly_rearranged_tile_order():
+    """80 K/V tiles per layer: 64 take the XCD-aware order, 16 stay in place."""
+    cfg = cfg_of("bf16", 128, 10, n_layers=4)
+    run_kv_fill(cfg, 54, lens=[0, 17, 31, 64, 5], fill_from=[1, 0, 3, 2, 4])
+    run_kv_fill(cfg, 55, lens=list(range(20, 52)), fill_from=[1] * 32)
+
+
 def test_kv_fill_llama7b_width():
     cfg = W.reduced(L7B, n_layers=3, d_ffn=256, vocab=512)
     run_kv_fill(cfg, 53, lens=[512 + 3 * b for b in range(32)], fill_from=[1] * 32)
