@@ -98,9 +98,8 @@ typedef struct ee_model {
 /* Paged KV cache (the block-virtualised cache the paper inherits, Section 2.2 / 3.2).
  * k_pool and v_pool: dev [n_layers][num_blocks][n_heads][block_size][head_dim] in the model dtype.
  * block_size must be 16.  Position p of sequence b lives in block block_tables[b][p / 16] at offset p % 16.
- * Slots of a sequence's last block that lie after its last position are read (and weighted with zero) by the
- * attention kernels: they must hold finite values (allocate the pools zeroed; values left by an earlier owner
- * of the block are fine), since 0 * NaN is NaN. */
+ * Slots that hold no position of a sequence (the rest of its last block, blocks nobody owns) may contain
+ * anything, NaN included: the attention kernels never let them reach a result. */
 typedef struct ee_kv_cache {
   void* k_pool;
   void* v_pool;

@@ -69,6 +69,12 @@ __device__ inline uint4 load_stream(const T* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// Sixteen bytes of zeros (never written; not const, so that it lives in the same address space as the cache).
+// A lane whose token lies after the sequence's last position reads its V values from here instead of from the
+// cache: what an earlier owner of the block, or nobody, left in those slots is weighted with zero, and 0 * NaN
+// would still be NaN.  The choice is made on the ADDRESS; the load itself stays unconditional.
+__device__ uint4 k_zero16;
+
 constexpr int TABLE_LDS_MAX = 16384;   // block-table entries staged in LDS: contexts up to 262144 tokens
 
 template <class T, int DH, bool OUT_XT>
@@ -131,13 +137,14 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   struct Blk {
     uint4 k[LPB], v[LPB];
   };
+  const T* zero_src = reinterpret_cast<const T*>(&k_zero16);
   auto fetch = [&](Blk& x, int lb) {
     const int phys = tbl[lb];
     const size_t off = (size_t)phys * block_elems;
 #pragma unroll
     for (int i = 0; i < LPB; ++i) {
       x.k[i] = load_stream(kbase + off + (size_t)i * TPL * DH);
-      x.v[i] = load_stream(vbase + off + (size_t)i * TPL * DH);
+      x.v[i] = load_stream(lb * 16 + i * TPL + grp < n_ctx ? vbase + off + (size_t)i * TPL * DH : zero_src);
     }
   };
   auto consume = [&](const Blk& x, int lb) {
@@ -313,12 +320,13 @@ __global__ __launch_bounds__(256) void attn_rows_kernel(AttnArgs a, Pred pred) {
     for (int i = threadIdx.x; i < n_blocks; i += blockDim.x) tbl[i] = safe_block(table[i], a.num_blocks);
     __syncthreads();
 
+    const T* zero_src = reinterpret_cast<const T*>(&k_zero16);
     auto fetch = [&](Blk& x, int lb) {
       const size_t off = (size_t)tbl[lb] * block_elems;
 #pragma unroll
       for (int i = 0; i < LPB; ++i) {
         x.k[i] = load_stream(kbase + off + (size_t)i * TPL * DH);
-        x.v[i] = load_stream(vbase + off + (size_t)i * TPL * DH);
+        x.v[i] = load_stream(lb * 16 + i * TPL + grp < run_ctx ? vbase + off + (size_t)i * TPL * DH : zero_src);
       }
     };
     auto consume = [&](const Blk& x, int lb) {
@@ -528,7 +536,9 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(AttnArgs a, Pred pred) 
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
           kt[t][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(kbase + off[t] + c * 32));
-          vt[t][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(vbase + off[t] + c * 32));
+          // positions from the run's end on (also the second copy of a repeated last block) come from the zeros
+          vt[t][c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(
+              s * 32 + t * 16 + i16 < run_ctx ? vbase + off[t] + c * 32 : reinterpret_cast<const bf16_t*>(&k_zero16)));
         }
       // scores^T of the 32 tokens: lane (i16, g) gets tokens 4g..4g+3 of each block for row i16
       f32x4_t st[2];

@@ -24,7 +24,20 @@ def cfg_of(dtype, head_dim, n_heads, **kw):
 # ------------------------------------------------------------------------------------------------------
 # paged decode attention
 # ------------------------------------------------------------------------------------------------------
-def run_attention(cfg, lens, seed, shuffled=True, sample=None):
+def poison_unwritten_slots(cache, bt, n_pos):
+    """NaN in every cache slot that holds no position of any sequence (sequence b owns positions 0..n_pos[b]-1)."""
+    nb = cache.k.shape[1]
+    valid = torch.zeros(nb, 16, dtype=torch.bool)
+    for b in range(len(n_pos)):
+        for p_ in range(int(n_pos[b])):
+            blk, off = W.slot_of(bt, b, p_, 16)
+            valid[blk, off] = True
+    mask = (~valid).cuda()[None, :, None, :, None].expand_as(cache.k)
+    cache.k[mask] = float("nan")
+    cache.v[mask] = float("nan")
+
+
+def run_attention(cfg, lens, seed, shuffled=True, sample=None, poison=False):
     lens = torch.tensor(lens, dtype=torch.int32)
     cfg = cfg.with_(batch=len(lens), shuffled_blocks=shuffled)
     max_ctx = int(lens.max()) + 1
@@ -34,6 +47,8 @@ def run_attention(cfg, lens, seed, shuffled=True, sample=None):
     for i in range(cfg.n_layers):
         cache.k[i] = W.dense_to_paged(Ks[i], bt, nb, 16)
         cache.v[i] = W.dense_to_paged(Vs[i], bt, nb, 16)
+    if poison:
+        poison_unwritten_slots(cache, bt, lens + 1)
     g = torch.Generator().manual_seed(seed)
     q = torch.randn(cfg.batch, cfg.n_heads, cfg.head_dim, generator=g) * 1.5
     out = torch.zeros(cfg.batch, cfg.n_heads, cfg.head_dim, device="cuda")
@@ -54,6 +69,13 @@ def run_attention(cfg, lens, seed, shuffled=True, sample=None):
 def test_attention_ragged_lengths(dtype, dh):
     cfg = cfg_of(dtype, dh, 3)
     run_attention(cfg, [0, 1, 14, 15, 16, 17, 31, 32, 63, 64, 65, 100, 257, 5], seed=11)
+
+
+@pytest.mark.parametrize("dtype,dh", [("fp32", 64), ("bf16", 64), ("bf16", 128)])
+def test_attention_ignores_what_unwritten_slots_hold(dtype, dh):
+    """Slots after a sequence's last position (and blocks nobody owns) hold NaN: no result may change."""
+    cfg = cfg_of(dtype, dh, 2)
+    run_attention(cfg, [0, 1, 14, 15, 16, 17, 31, 32, 63, 64, 65, 100, 257, 5], seed=12, poison=True)
 
 
 def test_attention_rows_sharing_one_block_table():
@@ -94,6 +116,7 @@ def test_attention_rows_of_several_sequences_across_row_groups(dh):
     for i in range(cfg.n_layers):
         cache.k[i] = W.dense_to_paged(Ks[i], bt, nb, 16)
         cache.v[i] = W.dense_to_paged(Vs[i], bt, nb, 16)
+    poison_unwritten_slots(cache, bt, lens + 1)   # what lies after a sequence's last position must not matter
     rows = [(0, p) for p in range(50, 70)] + [(1, p) for p in range(0, 5)] + [(2, p) for p in range(183, 200)]
     R = len(rows)
     pos = torch.tensor([p for _, p in rows], dtype=torch.int32)
