@@ -459,6 +459,11 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     }
   }
 
+  // The exit decision of layer i (softmax-response measures, bf16, batches the streaming projection kernel serves)
+  // rides along with the QKV projection launch of layer i + 1: one launch less per checked layer.
+  const bool carry_combine = bf && !dotmode && !compact && gemm_qkv_carries_combine(B);
+  CombineArgs pending{};
+  bool have_pending = false;
   // Algorithm 1, batch inference loop.  Everything is enqueued; the done flag turns later layers into no-ops.
   for (int i = 1; i <= n; ++i) {
     const ee_layer_weights& L = model->layers[i - 1];
@@ -485,7 +490,8 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
           gq.split_counters = w.split_counters;
         }
         QkvEpi qe = make_qkv_epi(D, *cache, *batch, w, i, w.q);
-        launch_gemm_qkv_bf16(gq, qe, run_layers, st);
+        launch_gemm_qkv_bf16(gq, qe, run_layers, st, have_pending ? &pending : nullptr);
+        have_pending = false;
       }
       {
         ProfScope ps(EE_K_ATTN, i, st);
@@ -610,8 +616,13 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
         enqueue_head_f32(*model, w, w.h, B, scale, i, run_layers, st);
       CombineArgs ca{w.partials, bf ? D.vocab / 32 : 1, B, i, scale, thresholds[i - 1], D.conf_mode, forced_exit_layer, s,
                      out_tokens, out_conf ? out_conf + (size_t)(i - 1) * B : nullptr, left};
-      ProfScope ps(EE_K_COMBINE, i, st);
-      launch_combine(ca, run_layers, st);
+      if (carry_combine) {   // decided inside the next layer's QKV projection launch (i < n: there is one)
+        pending = ca;
+        have_pending = true;
+      } else {
+        ProfScope ps(EE_K_COMBINE, i, st);
+        launch_combine(ca, run_layers, st);
+      }
       if (compact) launch_compact(w.status, B, rmap, w.rowsq, 2 * i, Mpad, run_layers, st);
     } else if (compact && i < n) {
       // no check after this layer: the map stands, the sums of the rows that left still move on

@@ -196,6 +196,13 @@ struct CombineArgs {
   const int32_t* left;  // nullptr, or [B]: rows with left[m] != 0 are not touched (per-sequence exit: token and state stay)
 };
 void launch_combine(const CombineArgs& a, Pred pred, hipStream_t st);
+// The exit decision of layer i may ride along with the QKV projection launch of layer i+1 instead of taking a
+// launch of its own (see launch_gemm_qkv_bf16): n_wg leading workgroups of that launch, one per batch row
+// (padded to a multiple of 8), run combine_row.  n_wg == 0: none.
+struct CombineJob {
+  CombineArgs a;
+  int n_wg;
+};
 // Exit decision from a measure that is one dot product per row (conf_mode 2: cosine of consecutive hidden
 // states = dots / sqrt(sq_a * sq_b); conf_mode 3: logistic function of dots * rsqrt(sq_b / d + eps) + bias[0],
 // the classifier's unit applied to the hidden state at unit root mean square).
@@ -242,7 +249,13 @@ struct GemmShape {
 // Whether a projection of M rows onto n_tiles packed tiles runs in the tiled kernel (the one that takes
 // n_rows_dev and the epilogues' perm).
 bool gemm_bf16_is_tiled(int M, int n_tiles);
-void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st);
+// with_combine != nullptr (only where gemm_qkv_carries_combine(M) holds): the launch also takes the exit decision
+// of the previous layer.  The projection then runs SPECULATIVELY when that decision ends the iteration (its
+// predicate word may or may not show the new value yet): what it caches for its layer is what KV filling
+// (Section 3.2) caches there anyway, and KV filling runs afterwards over every layer above the batch exit layer.
+void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st,
+                          const CombineArgs* with_combine = nullptr);
+bool gemm_qkv_carries_combine(int M);
 void launch_gemm_acc_bf16(const GemmShape& g, const AccEpi& e, Pred pred, hipStream_t st);
 void launch_gemm_gateup_bf16(const GemmShape& g, const GateUpEpi& e, Pred pred, hipStream_t st);
 void launch_gemm_lm_bf16(const GemmShape& g, const LmEpi& e, Pred pred, hipStream_t st);

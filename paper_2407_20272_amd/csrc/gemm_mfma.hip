@@ -15,6 +15,7 @@
 
 #include "ee_common.h"
 #include "ee_epilogue.h"
+#include "ee_decide.h"
 
 namespace ee {
 namespace {
@@ -282,9 +283,23 @@ __device__ inline void frag_mma(const Frag<MT, U>& f, f32x16 (&acc)[MT]) {
 }
 
 template <int MT, int U, class Epi, bool FILL>
-__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred pred, FillCtl fc) {
+__global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred pred, FillCtl fc, CombineJob cj) {
   __shared__ Lds s;
 
+  int bx = blockIdx.x;
+  if constexpr (std::is_same<Epi, QkvEpi>::value && !FILL) {
+    // Leading workgroups: the exit decision of the previous layer, one row each.  That layer ran if the batch
+    // has not left, or left at that very layer (the word may already show a sibling's update of this launch;
+    // `done` set at an earlier layer comes with a smaller batch exit layer, both long visible).
+    if (cj.n_wg) {
+      if (bx < cj.n_wg) {
+        if (bx < cj.a.B && (*cj.a.s.done == 0 || *cj.a.s.batch_exit_layer >= cj.a.layer))
+          combine_row(cj.a, bx, reinterpret_cast<float4*>(&s.red[0][0][0]));
+        return;
+      }
+      bx -= cj.n_wg;
+    }
+  }
   if constexpr (!FILL) {
     if (pred_skip(pred)) return;
   } else {
@@ -302,7 +317,6 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
   // Tiles that two workgroups share come first in the grid (two consecutive block indices per tile, each half of
   // the contraction): they are done, and their meeting in scratch memory is over, while the whole tiles still
   // stream.  With 384 tiles on 256 compute units this turns two rounds of workgroups into one and a half.
-  const int bx = blockIdx.x;
   const bool half_tile = bx < 2 * g.split_tiles;
   int tl = half_tile ? bx >> 1 : bx - 2 * g.split_tiles;   // tile within its class (halved / whole)
   int khalf = bx & 1;
@@ -648,7 +662,8 @@ int pick_mt(int M, int cap) {
 bool tiled(int M, int n_tiles) { return (M + 31) / 32 >= 3 && n_tiles % NW == 0; }
 
 template <class Epi, bool FILL>
-void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int nz, hipStream_t st) {
+void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int nz, hipStream_t st,
+            const CombineJob& cj = CombineJob{}) {
   dim3 block(256);
   const int m_tiles = (g.M + 31) / 32;
   // Batch chunks of 4 tiles (128 rows) measured faster than 8 at batch 256 and 512: twice the workgroups, each
@@ -714,16 +729,17 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
       return;
     }
   }
-  dim3 grid(g.n_tiles + g.split_tiles, g.ksplit, nz);   // split tiles take two workgroups each (one batch tile only)
+  // split tiles take two workgroups each (one batch tile only); the workgroups of a combine job come first
+  dim3 grid(g.n_tiles + g.split_tiles + cj.n_wg, g.ksplit, nz);
   switch (pick_mt(g.M, 4)) {
     case 4:
-      hipLaunchKernelGGL((gemm_mfma_kernel<4, 2, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
+      hipLaunchKernelGGL((gemm_mfma_kernel<4, 2, Epi, FILL>), grid, block, 0, st, g, e, pred, fc, cj);
       break;
     case 2:
-      hipLaunchKernelGGL((gemm_mfma_kernel<2, 4, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
+      hipLaunchKernelGGL((gemm_mfma_kernel<2, 4, Epi, FILL>), grid, block, 0, st, g, e, pred, fc, cj);
       break;
     default:
-      hipLaunchKernelGGL((gemm_mfma_kernel<1, 8, Epi, FILL>), grid, block, 0, st, g, e, pred, fc);
+      hipLaunchKernelGGL((gemm_mfma_kernel<1, 8, Epi, FILL>), grid, block, 0, st, g, e, pred, fc, cj);
   }
 }
 
@@ -731,9 +747,16 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
 
 bool gemm_bf16_is_tiled(int M, int n_tiles) { return tiled(M, n_tiles); }
 
-void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st) {
+bool gemm_qkv_carries_combine(int M) { return (M + 31) / 32 <= 2; }   // the streaming kernel serves these batches
+
+void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st, const CombineArgs* with_combine) {
   FillCtl fc{};
-  launch<QkvEpi, false>(g, e, pred, fc, 1, st);
+  CombineJob cj{};
+  if (with_combine) {
+    cj.a = *with_combine;
+    cj.n_wg = (with_combine->B + 7) / 8 * 8;   // a multiple of 8: the tiles keep their XCDs
+  }
+  launch<QkvEpi, false>(g, e, pred, fc, 1, st, cj);
 }
 void launch_gemm_acc_bf16(const GemmShape& g, const AccEpi& e, Pred pred, hipStream_t st) {
   FillCtl fc{};

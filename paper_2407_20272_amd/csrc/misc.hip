@@ -1,6 +1,7 @@
 // Small kernels of the decode step: state reset, embedding gather, normalisation, exit-head decision.
 #include "ee_common.h"
 #include "ee_epilogue.h"
+#include "ee_decide.h"
 
 namespace ee {
 namespace {
@@ -248,48 +249,10 @@ __global__ __launch_bounds__(256) void head_stats_f32_kernel(const float* logits
 // apply the sticky status rule, count accepted sequences and raise the all-exited flag.  One workgroup per row.
 // layer == 0: final token selection only.
 // ---------------------------------------------------------------------------------------------------
-// Section 3.1 status rule for one sequence: an accepted sequence stays accepted (and is not re-checked);
-// otherwise the confidence (or the forced exit layer) decides; the last acceptance of the batch raises `done`.
-__device__ inline void decide_row(const IterState& s, int m, int B, int layer, float conf, float threshold,
-                                  const int32_t* forced_exit_layer, float* conf_out) {
-  if (s.status[m] != 0) {
-    if (conf_out) conf_out[m] = __builtin_nanf("");
-    return;
-  }
-  if (conf_out) conf_out[m] = conf;
-  const bool accepted = forced_exit_layer ? (layer >= forced_exit_layer[m]) : (conf > threshold);
-  if (!accepted) return;
-  s.status[m] = 1;
-  s.exit_layer[m] = layer;
-  const int before = atomicAdd(s.n_exited, 1);
-  if (before + 1 == B) {
-    *s.batch_exit_layer = layer;
-    *s.done = 1;
-  }
-}
-
 __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, Pred pred) {
   if (pred_skip(pred)) return;
-  const int m = blockIdx.x;
-  if (a.left && a.left[m] != 0) return;   // left at an earlier layer: its token and exit layer stand
-  HeadStat s = stat_empty();
-  for (int i = threadIdx.x; i < a.n_parts; i += blockDim.x)
-    s = stat_merge(s, stat_unpack(a.partials[(size_t)m * a.n_parts + i]), a.scale);
   __shared__ float4 red[256];
-  red[threadIdx.x] = stat_pack(s);
-  __syncthreads();
-  for (int w = 128; w > 0; w >>= 1) {
-    if (threadIdx.x < w)
-      red[threadIdx.x] = stat_pack(stat_merge(stat_unpack(red[threadIdx.x]), stat_unpack(red[threadIdx.x + w]), a.scale));
-    __syncthreads();
-  }
-  if (threadIdx.x != 0) return;
-  s = stat_unpack(red[0]);
-  if (a.argmax_out) a.argmax_out[m] = s.idx;
-  if (a.layer == 0) return;
-  float conf = 1.0f / s.sum;                                          // largest softmax probability
-  if (a.conf_mode == 1) conf = (1.0f - expf(a.scale * (s.z2 - s.zmax))) / s.sum;  // top-1 minus top-2
-  decide_row(a.s, m, a.B, a.layer, conf, a.threshold, a.forced_exit_layer, a.conf_out);
+  combine_row(a, blockIdx.x, red);
 }
 
 // Row map of the sequences that are still active, in batch order (one workgroup walks the batch 256 rows at a
