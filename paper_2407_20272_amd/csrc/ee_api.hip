@@ -462,8 +462,10 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   // The exit decision of layer i (softmax-response measures, bf16, batches the streaming projection kernel serves)
   // rides along with the QKV projection launch of layer i + 1: one launch less per checked layer.
   const bool carry_combine = bf && !dotmode && !compact && gemm_qkv_carries_combine(B);
+  const bool carry_decide = bf && dotmode && !compact && gemm_qkv_carries_combine(B);
   CombineArgs pending{};
-  bool have_pending = false;
+  DecideArgs pending_dot{};
+  bool have_pending = false, have_pending_dot = false;
   // Algorithm 1, batch inference loop.  Everything is enqueued; the done flag turns later layers into no-ops.
   for (int i = 1; i <= n; ++i) {
     const ee_layer_weights& L = model->layers[i - 1];
@@ -490,8 +492,9 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
           gq.split_counters = w.split_counters;
         }
         QkvEpi qe = make_qkv_epi(D, *cache, *batch, w, i, w.q);
-        launch_gemm_qkv_bf16(gq, qe, run_layers, st, have_pending ? &pending : nullptr);
-        have_pending = false;
+        launch_gemm_qkv_bf16(gq, qe, run_layers, st, have_pending ? &pending : nullptr,
+                             have_pending_dot ? &pending_dot : nullptr);
+        have_pending = have_pending_dot = false;
       }
       {
         ProfScope ps(EE_K_ATTN, i, st);
@@ -605,8 +608,13 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       da.forced_exit_layer = forced_exit_layer;
       da.s = s;
       da.conf_out = out_conf ? out_conf + (size_t)(i - 1) * B : nullptr;
-      ProfScope ps(EE_K_COMBINE, i, st);
-      launch_decide(da, run_layers, st);
+      if (carry_decide) {   // decided inside the next layer's QKV projection launch
+        pending_dot = da;
+        have_pending_dot = true;
+      } else {
+        ProfScope ps(EE_K_COMBINE, i, st);
+        launch_decide(da, run_layers, st);
+      }
       if (compact) launch_compact(w.status, B, rmap, w.rowsq, 2 * i, Mpad, run_layers, st);
     } else if (head_here) {
       const float scale = D.logit_scale * (float)i;

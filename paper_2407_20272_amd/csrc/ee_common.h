@@ -196,13 +196,6 @@ struct CombineArgs {
   const int32_t* left;  // nullptr, or [B]: rows with left[m] != 0 are not touched (per-sequence exit: token and state stay)
 };
 void launch_combine(const CombineArgs& a, Pred pred, hipStream_t st);
-// The exit decision of layer i may ride along with the QKV projection launch of layer i+1 instead of taking a
-// launch of its own (see launch_gemm_qkv_bf16): n_wg leading workgroups of that launch, one per batch row
-// (padded to a multiple of 8), run combine_row.  n_wg == 0: none.
-struct CombineJob {
-  CombineArgs a;
-  int n_wg;
-};
 // Exit decision from a measure that is one dot product per row (conf_mode 2: cosine of consecutive hidden
 // states = dots / sqrt(sq_a * sq_b); conf_mode 3: logistic function of dots * rsqrt(sq_b / d + eps) + bias[0],
 // the classifier's unit applied to the hidden state at unit root mean square).
@@ -222,6 +215,16 @@ struct DecideArgs {
   float* conf_out;
 };
 void launch_decide(const DecideArgs& a, Pred pred, hipStream_t st);
+// The exit decision of layer i may ride along with the QKV projection launch of layer i+1 instead of taking a
+// launch of its own (see launch_gemm_qkv_bf16): n_wg leading workgroups of that launch (a multiple of 8) take it.
+// kind 1: softmax-response measures, workgroup m < a.B runs combine_row for batch row m.
+// kind 2: one-dot-product measures, workgroup 0 runs decide_from_dot for every row.  n_wg == 0: none.
+struct CombineJob {
+  CombineArgs a;
+  DecideArgs d;
+  int kind;
+  int n_wg;
+};
 
 // pack.hip
 void launch_pack_weight(const bf16_t* w, int n_out, int n_in, int pair_stride, bf16_t* packed, hipStream_t st);
@@ -254,7 +257,7 @@ bool gemm_bf16_is_tiled(int M, int n_tiles);
 // predicate word may or may not show the new value yet): what it caches for its layer is what KV filling
 // (Section 3.2) caches there anyway, and KV filling runs afterwards over every layer above the batch exit layer.
 void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st,
-                          const CombineArgs* with_combine = nullptr);
+                          const CombineArgs* with_combine = nullptr, const DecideArgs* with_decide = nullptr);
 bool gemm_qkv_carries_combine(int M);
 void launch_gemm_acc_bf16(const GemmShape& g, const AccEpi& e, Pred pred, hipStream_t st);
 void launch_gemm_gateup_bf16(const GemmShape& g, const GateUpEpi& e, Pred pred, hipStream_t st);

@@ -50,4 +50,15 @@ __device__ inline void combine_row(const CombineArgs& a, int m, float4* red) {
   decide_row(a.s, m, a.B, a.layer, conf, a.threshold, a.forced_exit_layer, a.conf_out);
 }
 
+// Confidence of row m from one dot product (hidden states similarity, dedicated classifier) and the status rule.
+__device__ inline void decide_from_dot(const DecideArgs& a, int m) {
+  float conf;
+  if (a.conf_mode == 2) {
+    conf = a.dots[m] / (sqrtf(a.sq_a[m]) * sqrtf(a.sq_b[m]));
+  } else {
+    conf = 1.0f / (1.0f + expf(-(a.dots[m] * rsqrtf(a.sq_b[m] / (float)a.d + a.eps) + a.bias[0])));
+  }
+  decide_row(a.s, m, a.B, a.layer, conf, a.threshold, a.forced_exit_layer, a.conf_out);
+}
+
 }  // namespace ee

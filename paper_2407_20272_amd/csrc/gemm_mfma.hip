@@ -293,8 +293,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
     // `done` set at an earlier layer comes with a smaller batch exit layer, both long visible).
     if (cj.n_wg) {
       if (bx < cj.n_wg) {
-        if (bx < cj.a.B && (*cj.a.s.done == 0 || *cj.a.s.batch_exit_layer >= cj.a.layer))
-          combine_row(cj.a, bx, reinterpret_cast<float4*>(&s.red[0][0][0]));
+        if (cj.kind == 1) {
+          if (bx < cj.a.B && (*cj.a.s.done == 0 || *cj.a.s.batch_exit_layer >= cj.a.layer))
+            combine_row(cj.a, bx, reinterpret_cast<float4*>(&s.red[0][0][0]));
+        } else if (bx == 0 && (*cj.d.s.done == 0 || *cj.d.s.batch_exit_layer >= cj.d.layer)) {
+          for (int m = threadIdx.x; m < cj.d.B; m += blockDim.x) decide_from_dot(cj.d, m);
+        }
         return;
       }
       bx -= cj.n_wg;
@@ -749,12 +753,18 @@ bool gemm_bf16_is_tiled(int M, int n_tiles) { return tiled(M, n_tiles); }
 
 bool gemm_qkv_carries_combine(int M) { return (M + 31) / 32 <= 2; }   // the streaming kernel serves these batches
 
-void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st, const CombineArgs* with_combine) {
+void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st, const CombineArgs* with_combine,
+                          const DecideArgs* with_decide) {
   FillCtl fc{};
   CombineJob cj{};
   if (with_combine) {
     cj.a = *with_combine;
+    cj.kind = 1;
     cj.n_wg = (with_combine->B + 7) / 8 * 8;   // a multiple of 8: the tiles keep their XCDs
+  } else if (with_decide) {
+    cj.d = *with_decide;
+    cj.kind = 2;
+    cj.n_wg = 8;
   }
   launch<QkvEpi, false>(g, e, pred, fc, 1, st, cj);
 }

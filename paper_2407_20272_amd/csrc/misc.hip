@@ -294,13 +294,7 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a, Pred pred) {
   if (pred_skip(pred)) return;
   const int m = blockIdx.x * blockDim.x + threadIdx.x;
   if (m >= a.B) return;
-  float conf;
-  if (a.conf_mode == 2) {
-    conf = a.dots[m] / (sqrtf(a.sq_a[m]) * sqrtf(a.sq_b[m]));
-  } else {
-    conf = 1.0f / (1.0f + expf(-(a.dots[m] * rsqrtf(a.sq_b[m] / (float)a.d + a.eps) + a.bias[0])));
-  }
-  decide_row(a.s, m, a.B, a.layer, conf, a.threshold, a.forced_exit_layer, a.conf_out);
+  decide_from_dot(a, m);
 }
 
 }  // namespace
