@@ -54,6 +54,52 @@ __device__ inline void epi_qkv(const QkvEpi& e, int m, int f_lo, float lo, float
   store_elem(pool + at + half, hi);
 }
 
+// The same for four consecutive channels f_lo0..f_lo0+3 (f_lo0 a multiple of 4) of batch row m and their four
+// rotary partners, bf16 cache: one look-up of the slot, 8-byte stores into the cache, 16-byte stores into q.
+__device__ inline void epi_qkv4(const QkvEpi& e, int m, int f_lo0, float (&lo)[4], float (&hi)[4]) {
+  if (e.fill_from && !(e.fill_from[(size_t)m * e.fill_from_stride] < e.layer)) return;
+  const float r = row_rinv(e.rowsq, m, e.d_model, e.eps);
+  const int d = e.d_model, dh = e.head_dim, half = dh >> 1;
+  const int which = f_lo0 / d;  // 0 q, 1 k, 2 v
+  const int within = f_lo0 - which * d;
+  const int head = within / dh;
+  const int j = within - head * dh;  // < dh/2, a multiple of 4
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    lo[i] *= r;
+    hi[i] *= r;
+  }
+  if (which < 2 && e.rope_theta > 0.0f) {
+    const float4 c01 = *reinterpret_cast<const float4*>(e.rope + (size_t)m * half + j);       // (cos, sin) x 2
+    const float4 c23 = *reinterpret_cast<const float4*>(e.rope + (size_t)m * half + j + 2);
+    const float cs[4] = {c01.x, c01.z, c23.x, c23.z}, sn[4] = {c01.y, c01.w, c23.y, c23.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float a = lo[i] * cs[i] - hi[i] * sn[i];
+      const float b = hi[i] * cs[i] + lo[i] * sn[i];
+      lo[i] = a;
+      hi[i] = b;
+    }
+  }
+  if (which == 0) {
+    if (e.q) {
+      float* q = e.q + (size_t)m * d + head * dh + j;
+      *reinterpret_cast<float4*>(q) = make_float4(lo[0], lo[1], lo[2], lo[3]);
+      *reinterpret_cast<float4*>(q + half) = make_float4(hi[0], hi[1], hi[2], hi[3]);
+    }
+    return;
+  }
+  const int p = e.context_lens[m];
+  const bool p_ok = (unsigned)p < (unsigned)(e.max_blocks * 16);
+  const int blk = e.block_tables[(size_t)(e.row_table ? safe_row(e.row_table[m], e.table_rows) : m) * e.max_blocks + (p_ok ? p >> 4 : 0)];
+  if (!p_ok || (unsigned)blk >= (unsigned)e.num_blocks) return;   // never outside the pools
+  const size_t at = (((size_t)blk * e.n_heads + head) * 16 + (p & 15)) * dh + j;
+  bf16_t* pool = reinterpret_cast<bf16_t*>(which == 1 ? e.k_pool : e.v_pool);
+  typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+  *reinterpret_cast<bf16x4*>(pool + at) = bf16x4{(bf16_t)lo[0], (bf16_t)lo[1], (bf16_t)lo[2], (bf16_t)lo[3]};
+  *reinterpret_cast<bf16x4*>(pool + at + half) = bf16x4{(bf16_t)hi[0], (bf16_t)hi[1], (bf16_t)hi[2], (bf16_t)hi[3]};
+}
+
 __device__ inline void epi_acc(const AccEpi& e, int m, int f, float v) {
   if (e.skip && e.skip[m] != 0) return;
   float* p = e.Mpad ? e.h + ht_index(m, f, e.Mpad) : e.h + (size_t)m * e.n_out + f;
@@ -72,6 +118,19 @@ __device__ inline void epi_gateup(const GateUpEpi& e, int m, int f, float gate, 
   } else {
     reinterpret_cast<float*>(e.act)[(size_t)m * e.d_ffn + f] = a;
   }
+}
+
+// SwiGLU products of four consecutive features f0..f0+3 (f0 a multiple of 4), bf16 operand-tile order: one 8-byte store.
+__device__ inline void epi_gateup4(const GateUpEpi& e, int m, int f0, const float (&gate)[4], const float (&up)[4]) {
+  const float r = row_rinv(e.rowsq, m, e.d_model, e.eps);
+  typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+  bf16x4 out;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float g = gate[i] * r, u = up[i] * r;
+    out[i] = (bf16_t)(g / (1.0f + expf(-g)) * u);
+  }
+  *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16_t*>(e.act) + xt_index(m, f0, e.d_ffn)) = out;
 }
 
 // Running softmax statistics of one row: largest and second largest (unscaled) logit, index of the largest

@@ -639,13 +639,20 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
       for (int mt = 0; mt < MT; ++mt) {
         const int m = (chunk * MT + mt) * 32 + ml;
         if (m < M_eff) {
+          // this lane holds two runs of four consecutive output rows (and their partners 16 rows on) of its batch row
 #pragma unroll
-          for (int a = 0; a < 8; ++a) {
-            const int f_lo = packed_row_lo(nt0 + t, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
+          for (int run = 0; run < 2; ++run) {
+            const int f_lo0 = packed_row_lo(nt0 + t, run * 8 + half * 4, g.pair_stride);
+            float lo[4], hi[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              lo[i] = acc[t][mt][run * 4 + i];
+              hi[i] = acc[t][mt][run * 4 + i + 8];
+            }
             if constexpr (std::is_same<Epi, QkvEpi>::value) {
-              epi_qkv<bf16_t>(e, m, f_lo, acc[t][mt][a], acc[t][mt][a + 8]);
+              epi_qkv4(e, m, f_lo0, lo, hi);
             } else {
-              epi_gateup<bf16_t>(e, m, f_lo, acc[t][mt][a], acc[t][mt][a + 8]);
+              epi_gateup4(e, m, f_lo0, lo, hi);
             }
           }
         }
