@@ -621,24 +621,39 @@ __global__ __launch_bounds__(256) void attn_chunk_kernel(AttnArgs a, Pred pred) 
     sl[wave][i16] = l_run;
   }
   __syncthreads();
-  for (int t = threadIdx.x; t < nrows * DH; t += blockDim.x) {
-    const int r = t / DH, c = t - r * DH;
-    float M = sm[0][r];
+  // one thread per (row, 8 consecutive channels): 16-byte (bf16 operand order) or 2 x 16-byte (float) stores
+  {
+    constexpr int G8 = DH / 8;
+    const int r = threadIdx.x / G8, c0 = (threadIdx.x % G8) * 8;
+    if (r < nrows) {
+      float M = sm[0][r];
 #pragma unroll
-    for (int w = 1; w < NW; ++w) M = fmaxf(M, sm[w][r]);
-    float L = 0.0f, acc = 0.0f;
+      for (int w = 1; w < NW; ++w) M = fmaxf(M, sm[w][r]);
+      float L = 0.0f, acc[8];
 #pragma unroll
-    for (int w = 0; w < NW; ++w) {
-      const float wgt = __builtin_amdgcn_exp2f(sm[w][r] - M);
-      L += sl[w][r] * wgt;
-      acc += so[w][r][c] * wgt;
-    }
-    const float res = acc / L;
-    const int col = head * DH + c;
-    if constexpr (OUT_XT) {
-      reinterpret_cast<bf16_t*>(a.out)[xt_index(row0 + r, col, a.n_heads * DH)] = (bf16_t)res;
-    } else {
-      reinterpret_cast<float*>(a.out)[(size_t)(row0 + r) * a.n_heads * DH + col] = res;
+      for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+#pragma unroll
+      for (int w = 0; w < NW; ++w) {
+        const float wgt = __builtin_amdgcn_exp2f(sm[w][r] - M);
+        L += sl[w][r] * wgt;
+        const float4 lo = *reinterpret_cast<const float4*>(&so[w][r][c0]);
+        const float4 hi = *reinterpret_cast<const float4*>(&so[w][r][c0 + 4]);
+        const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] += v[e] * wgt;
+      }
+      const float inv = 1.0f / L;
+      const int col = head * DH + c0;
+      if constexpr (OUT_XT) {
+        bf16x8_t o8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o8[e] = (__bf16)(acc[e] * inv);
+        *reinterpret_cast<bf16x8_t*>(reinterpret_cast<bf16_t*>(a.out) + xt_index(row0 + r, col, a.n_heads * DH)) = o8;
+      } else {
+        float* op = reinterpret_cast<float*>(a.out) + (size_t)(row0 + r) * a.n_heads * DH + col;
+        *reinterpret_cast<float4*>(op) = make_float4(acc[0] * inv, acc[1] * inv, acc[2] * inv, acc[3] * inv);
+        *reinterpret_cast<float4*>(op + 4) = make_float4(acc[4] * inv, acc[5] * inv, acc[6] * inv, acc[7] * inv);
+      }
     }
   }
 }
