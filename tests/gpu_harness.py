@@ -108,7 +108,7 @@ def near_threshold(cfg, m, tr, i, b, lam_i) -> bool:
     return abs(float(tr["conf"][i - 1, b]) - lam_i) <= measure_tolerance(cfg, m, tr, i, b)
 
 
-class GpuRun:
+class HipRun:
     """Device-side state of one workload: model, paged cache, block tables, workspace, output buffers."""
 
     def __init__(self, cfg, weights_cpu: Dict, context_lens: torch.Tensor, extra_tokens: int, seed: int = 0,
@@ -197,7 +197,7 @@ def lockstep(cfg, seed: int, steps: int, thresholds=None, forced_seq=None, heads
     max_ctx = int(lens.max()) + steps
     ocache = O.DenseKV(n, Bsz, max_ctx, cfg.n_heads, cfg.head_dim, cfg.dtype)
     sentinel = 7.0
-    run = GpuRun(cfg, w, lens, steps, seed=seed, pool_fill=sentinel)
+    run = HipRun(cfg, w, lens, steps, seed=seed, pool_fill=sentinel)
     h_last = torch.zeros(Bsz, cfg.d_model, dtype=F64)
     tok_o = O.prefill(m, ocache, prompts, lens, last_hidden=h_last)
     tok_g = run.prefill(prompts, lens)
@@ -257,7 +257,7 @@ def lockstep(cfg, seed: int, steps: int, thresholds=None, forced_seq=None, heads
     return stats
 
 
-def compare_cache(cfg, run: GpuRun, ocache, lens, tol, what, only_pos=None):
+def compare_cache(cfg, run: HipRun, ocache, lens, tol, what, only_pos=None):
     """GPU pools (gathered through the block tables) against the oracle's dense cache, all layers."""
     ctx = int(lens.max())
     for i in range(cfg.n_layers):
@@ -269,7 +269,7 @@ def compare_cache(cfg, run: GpuRun, ocache, lens, tol, what, only_pos=None):
                 assert_close_scaled(got[b, sl], want[b, sl], tol, f"{what}: {name} cache layer {i + 1} sequence {b}")
 
 
-def assert_untouched(cfg, run: GpuRun, lens, sentinel):
+def assert_untouched(cfg, run: HipRun, lens, sentinel):
     """Every slot that no (sequence, position < len) owns still holds the sentinel: no stray paged write."""
     bs = cfg.block_size
     owned = torch.zeros(run.num_blocks, bs, dtype=torch.bool)

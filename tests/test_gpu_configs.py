@@ -11,7 +11,7 @@ import torch
 from oracle import ee_oracle as O
 from paper_2407_20272_amd import binding as B
 from paper_2407_20272_amd import workloads as W
-from gpu_harness import F64, GpuRun, assert_close_scaled, check_confidences, near_threshold, tol_of
+from gpu_harness import F64, HipRun, assert_close_scaled, check_confidences, near_threshold, tol_of
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
 
@@ -22,7 +22,7 @@ def setup_case(cfg, seed, sample, kv_scale=0.5):
     n, Bsz = cfg.n_layers, cfg.batch
     w = W.make_weights(cfg, seed=seed, device="cuda", gain_jitter=0.1)
     lens = W.make_context_lens(cfg, seed=seed)
-    run = GpuRun(cfg, None, lens, 1, seed=seed, spare_blocks=1, weights_dev=w)
+    run = HipRun(cfg, None, lens, 1, seed=seed, spare_blocks=1, weights_dev=w)
     w_cpu = W.weights_to(w, "cpu")
     del w
     max_ctx = int(lens.max()) + 1
@@ -234,7 +234,7 @@ def test_hip_graph_replay_matches_eager(dtype):
     w = W.make_weights(cfg, seed=8, gain_jitter=0.1)
     lens = W.make_context_lens(cfg, seed=8)
     steps = 4
-    run = GpuRun(cfg, w, lens, steps + 2, seed=8)
+    run = HipRun(cfg, w, lens, steps + 2, seed=8)
     Ks, Vs = W.make_dense_kv(cfg, lens, int(lens.max()), seed=8, scale=0.5)
     run.load_dense(Ks, Vs)
     k0, v0 = run.cache.k.clone(), run.cache.v.clone()

@@ -7,7 +7,7 @@ import pytest
 import torch
 
 from paper_2407_20272_amd import workloads as W
-from gpu_harness import GpuRun, lockstep
+from gpu_harness import HipRun, lockstep
 
 pytestmark = pytest.mark.gpu
 TINY, L7B = W.CONFIGS[0], W.CONFIGS[1]
@@ -74,7 +74,7 @@ def test_threshold_above_one_equals_full_layer_path():
         prompts, lens = W.make_prompts(cfg, seed=4), W.make_context_lens(cfg, seed=4)
         outs = []
         for heads in (True, False):
-            run = GpuRun(cfg, w, lens, 4, seed=4)
+            run = HipRun(cfg, w, lens, 4, seed=4)
             tok = run.prefill(prompts, lens)
             pos = lens.clone().long()
             toks = [tok]
@@ -115,7 +115,7 @@ def test_saturated_model_forced_exit_cache_equals_full_pass(dtype):
     prompts, lens = W.make_prompts(cfg, seed=6), W.make_context_lens(cfg, seed=6)
     res = []
     for forced_mode in (True, False):
-        run = GpuRun(cfg, w, lens, 3, seed=6)
+        run = HipRun(cfg, w, lens, 3, seed=6)
         tok = run.prefill(prompts, lens)
         pos = lens.clone().long()
         toks = []
@@ -137,7 +137,7 @@ def test_saturated_model_forced_exit_cache_equals_full_pass(dtype):
 def test_empty_batch_is_a_noop():
     cfg = TINY
     w = W.make_weights(cfg, seed=0)
-    run = GpuRun(cfg, w, torch.tensor([3], dtype=torch.int32), 1)
+    run = HipRun(cfg, w, torch.tensor([3], dtype=torch.int32), 1)
     tok, e, L, conf, hid = run.step(torch.zeros(0, dtype=torch.int32), torch.zeros(0, dtype=torch.long), 0.5,
                                     rows=[])
     assert tok.numel() == 0 and e.numel() == 0

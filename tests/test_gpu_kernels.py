@@ -8,7 +8,7 @@ import torch
 from oracle import ee_oracle as O
 from paper_2407_20272_amd import binding as B
 from paper_2407_20272_amd import workloads as W
-from gpu_harness import F64, GpuRun, assert_close_scaled, conf_tolerance, tol_of
+from gpu_harness import F64, HipRun, assert_close_scaled, conf_tolerance, tol_of
 
 pytestmark = pytest.mark.gpu
 TINY, L7B = W.CONFIGS[0], W.CONFIGS[1]
@@ -273,7 +273,7 @@ def run_kv_fill(cfg, seed, lens, fill_from):
     fill_from = torch.tensor(fill_from, dtype=torch.int32)
     w = W.make_weights(cfg, seed=seed, gain_jitter=0.2)
     m = O.model_from_config(cfg, w)
-    run = GpuRun(cfg, w, lens, 1, seed=seed, pool_fill=7.0)
+    run = HipRun(cfg, w, lens, 1, seed=seed, pool_fill=7.0)
     g = torch.Generator().manual_seed(seed)
     hidden = torch.randn(cfg.batch, cfg.d_model, generator=g) * 2.0
     batch = B.make_batch(None, lens.cuda(), run.bt_dev, int(lens.max()) + 1)
