@@ -62,6 +62,19 @@ def test_bf16_width_1280_partly_rearranged_tile_order():
     assert stats["near_threshold"] + stats["near_tie"] <= max(2, total // 20), stats
 
 
+@pytest.mark.parametrize("batch,n_layers,exit_every,conf_mode,threshold", [
+    (1, 3, 1, 0, 0.4), (7, 6, 3, 0, 0.3), (33, 5, 2, 1, 0.2), (64, 4, 1, 0, 0.45), (12, 7, 1, 0, 0.9), (20, 5, 1, 0, 0.05)])
+def test_bf16_exit_decision_carried_by_the_next_projection(batch, n_layers, exit_every, conf_mode, threshold):
+    """Batches the streaming projection kernel serves (the exit decision of a layer is taken inside the next layer's
+    QKV launch): one and two batch tiles, heads after every / every 2nd / 3rd layer, thresholds from "everybody
+    leaves at the first head" (the projection after it runs speculatively) to "nobody ever leaves"."""
+    cfg = small_bf16(batch=batch, n_layers=n_layers, exit_every=exit_every, conf_mode=conf_mode, threshold=threshold,
+                     shuffled_blocks=True, prompt_len=10, min_prompt_len=3)
+    stats = lockstep(cfg, seed=70 + batch, steps=4)
+    total = stats["decisions"] + stats["tokens"]
+    assert stats["near_threshold"] + stats["near_tie"] <= max(2, total // 20), stats
+
+
 def test_small_bf16_head_dim_64_exit_every_2_mode1():
     cfg = small_bf16(n_heads=4, head_dim=64, n_layers=6, exit_every=2, conf_mode=1, batch=9, threshold=0.3)
     lockstep(cfg, seed=21, steps=4)
