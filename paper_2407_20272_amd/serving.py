@@ -211,6 +211,7 @@ def main():
     ap.add_argument("--new-min", type=int, default=16)
     ap.add_argument("--new-max", type=int, default=96)
     ap.add_argument("--chunk", type=int, default=16)
+    ap.add_argument("--max-rows", type=int, default=512, help="rows of one prompt-chunk iteration (all prompts in flight together)")
     ap.add_argument("--exit-rule", choices=["none", "batch", "per_sequence"], default="batch")
     ap.add_argument("--conf-mode", type=int, default=-1, help="-1: the config's measure")
     ap.add_argument("--threshold", type=float, default=0.0)
@@ -226,7 +227,7 @@ def main():
     max_ctx = args.prompt_max + args.new_max
     blocks = args.max_batch * ((max_ctx + cfg.block_size - 1) // cfg.block_size)
     rule = {"none": B.EE_EXIT_NONE, "batch": B.EE_EXIT_BATCH, "per_sequence": B.EE_EXIT_PER_SEQUENCE}[args.exit_rule]
-    eng = Engine(cfg, model, blocks, args.max_batch, max_ctx, chunk=args.chunk, exit_rule=rule,
+    eng = Engine(cfg, model, blocks, args.max_batch, max_ctx, chunk=args.chunk, max_rows=args.max_rows, exit_rule=rule,
                  thresholds=args.threshold or None)
     for _ in range(args.requests):
         pl = int(torch.randint(args.prompt_min, args.prompt_max + 1, (1,), generator=g))
@@ -236,7 +237,7 @@ def main():
     done = eng.run()
     out = summary(done, time.perf_counter() - t0, eng.iterations)
     out.update({"workload": cfg.name, "exit_rule": args.exit_rule, "conf_mode": cfg.conf_mode, "max_batch": args.max_batch,
-                "chunk": args.chunk, "batch_exit_layer_hist": dict(sorted(eng.L_hist.items())), "data": "synthetic"})
+                "chunk": args.chunk, "max_rows": args.max_rows, "batch_exit_layer_hist": dict(sorted(eng.L_hist.items())), "data": "synthetic"})
     print(json.dumps(out))
 
 
