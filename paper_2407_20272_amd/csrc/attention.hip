@@ -75,7 +75,7 @@ __device__ inline uint4 load_stream(const T* p) {
 // would still be NaN.  The choice is made on the ADDRESS; the load itself stays unconditional.
 __device__ uint4 k_zero16;
 
-constexpr int TABLE_LDS_MAX = 16384;   // block-table entries staged in LDS: contexts up to 262144 tokens
+constexpr int TABLE_LDS_MAX = kAttnMaxBlocks;   // block-table entries staged in LDS
 
 template <class T, int DH, bool OUT_XT>
 __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred) {
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   // three in a row.
   const int t0 = (int)threadIdx.x < a.max_blocks ? safe_block(table[threadIdx.x], a.num_blocks) : 0;
   const int len = a.context_lens[b];
-  const int left = a.skip ? a.skip[b] : 0;
+  const int left = a.skip ? __hip_atomic_load(a.skip + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
   const int out_row = a.out_pos ? a.out_pos[b] : b;
   float q[EPL];
   {

@@ -188,13 +188,15 @@ int check_cache(const ee_kv_cache* C) {
   return EE_OK;
 }
 
-int check_batch(const ee_batch* Bt, bool need_tokens) {
+int check_batch(const ee_batch* Bt, bool need_tokens, bool attends = true) {
   if (!Bt) EE_FAIL(EE_ERR_INVALID_ARG, "batch is NULL");
   if (Bt->batch < 0) EE_FAIL(EE_ERR_INVALID_ARG, "batch size %d is negative", Bt->batch);
   if (Bt->batch == 0) return EE_OK;
   if ((need_tokens && !Bt->tokens) || !Bt->context_lens || !Bt->block_tables)
     EE_FAIL(EE_ERR_INVALID_ARG, "batch has a NULL pointer");
   if (Bt->max_blocks < 1) EE_FAIL(EE_ERR_INVALID_ARG, "max_blocks must be positive");
+  if (attends && Bt->max_blocks > kAttnMaxBlocks)
+    EE_FAIL(EE_ERR_UNSUPPORTED, "attention: max_blocks %d outside 1..%d", Bt->max_blocks, kAttnMaxBlocks);
   if (Bt->max_context < 1 || Bt->max_context > Bt->max_blocks * 16)
     EE_FAIL(EE_ERR_SHAPE, "max_context %d does not fit max_blocks %d * 16", Bt->max_context, Bt->max_blocks);
   return EE_OK;
@@ -721,7 +723,7 @@ int ee_exit_check(const ee_model* model, int32_t layer, const float* hidden, int
 int ee_kv_fill(const ee_model* model, const ee_kv_cache* cache, const ee_batch* batch, const float* hidden,
                const int32_t* fill_from_layer, void* workspace, size_t workspace_bytes, void* stream) {
   int rc;
-  if ((rc = check_model(model)) || (rc = check_cache(cache)) || (rc = check_batch(batch, false))) return rc;
+  if ((rc = check_model(model)) || (rc = check_cache(cache)) || (rc = check_batch(batch, false, false))) return rc;
   const ee_model_desc& D = model->desc;
   const int B = batch->batch;
   if (B == 0) return EE_OK;

@@ -289,6 +289,10 @@ void launch_simple_lm(const SimpleShape& g, const LmEpi& e, Pred pred, hipStream
 __host__ __device__ inline int safe_block(int blk, int num_blocks) { return (unsigned)blk < (unsigned)num_blocks ? blk : 0; }
 __host__ __device__ inline int safe_row(int row, int n_rows) { return (unsigned)row < (unsigned)n_rows ? row : 0; }
 
+// Block-table entries per sequence that the attention kernels stage in LDS (contexts up to 262144 tokens).  The
+// entry points check ee_batch.max_blocks against it before anything is enqueued.
+constexpr int kAttnMaxBlocks = 16384;
+
 struct AttnArgs {
   const float* q;               // [B][H*dh] fp32, rotary applied
   const void* k_pool;           // layer base

@@ -11,26 +11,26 @@ namespace ee {
 // otherwise the confidence (or the forced exit layer) decides; the last acceptance of the batch raises `done`.
 __device__ inline void decide_row(const IterState& s, int m, int B, int layer, float conf, float threshold,
                                   const int32_t* forced_exit_layer, float* conf_out) {
-  if (s.status[m] != 0) {
+  if (ctl_load(s.status + m) != 0) {
     if (conf_out) conf_out[m] = __builtin_nanf("");
     return;
   }
   if (conf_out) conf_out[m] = conf;
   const bool accepted = forced_exit_layer ? (layer >= forced_exit_layer[m]) : (conf > threshold);
   if (!accepted) return;
-  s.status[m] = 1;
-  s.exit_layer[m] = layer;
-  const int before = atomicAdd(s.n_exited, 1);
+  ctl_store(s.status + m, 1);
+  ctl_store(s.exit_layer + m, layer);
+  const int before = __hip_atomic_fetch_add(s.n_exited, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (before + 1 == B) {
-    *s.batch_exit_layer = layer;
-    *s.done = 1;
+    ctl_store(s.batch_exit_layer, layer);
+    ctl_store(s.done, 1);
   }
 }
 
 // One workgroup of 256 threads merges the per-tile softmax statistics of row m into the confidence and applies
 // the status rule.  red: 256 float4 of LDS.  layer == 0: final token selection only.
 __device__ inline void combine_row(const CombineArgs& a, int m, float4* red) {
-  if (a.left && a.left[m] != 0) return;   // left at an earlier layer: its token and exit layer stand
+  if (a.left && ctl_load(a.left + m) != 0) return;   // left at an earlier layer: its token and exit layer stand
   HeadStat s = stat_empty();
   for (int i = threadIdx.x; i < a.n_parts; i += blockDim.x)
     s = stat_merge(s, stat_unpack(a.partials[(size_t)m * a.n_parts + i]), a.scale);

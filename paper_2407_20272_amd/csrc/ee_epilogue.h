@@ -6,6 +6,12 @@
 
 namespace ee {
 
+// The control words of an iteration (status, exit layers, the count of accepted sequences, the all-exited flag and
+// the batch exit layer) are written by the workgroups that take an exit decision and read by workgroups of other
+// compute units, sometimes of the same launch: every access is a relaxed device-scope atomic.
+__device__ inline int32_t ctl_load(const int32_t* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ inline void ctl_store(int32_t* p, int32_t v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
 __device__ inline float row_rinv(const float* rowsq, int m, int d, float eps) {
   return rowsq ? rsqrtf(rowsq[m] / (float)d + eps) : 1.0f;
 }
@@ -101,7 +107,7 @@ __device__ inline void epi_qkv4(const QkvEpi& e, int m, int f_lo0, float (&lo)[4
 }
 
 __device__ inline void epi_acc(const AccEpi& e, int m, int f, float v) {
-  if (e.skip && e.skip[m] != 0) return;
+  if (e.skip && ctl_load(e.skip + m) != 0) return;
   float* p = e.Mpad ? e.h + ht_index(m, f, e.Mpad) : e.h + (size_t)m * e.n_out + f;
   unsafeAtomicAdd(p, v);
 }
@@ -219,6 +225,6 @@ __device__ inline HeadStat stat_of(const float (&z)[N], const int (&idx)[N], flo
 __device__ inline float4 stat_pack(const HeadStat& s) { return make_float4(s.zmax, s.sum, s.z2, __int_as_float(s.idx)); }
 __device__ inline HeadStat stat_unpack(const float4& v) { return {v.x, v.y, v.z, __float_as_int(v.w)}; }
 
-__device__ inline bool pred_skip(const Pred& p) { return p.flag && ((*p.flag != 0) != (p.run_when != 0)); }
+__device__ inline bool pred_skip(const Pred& p) { return p.flag && ((ctl_load(p.flag) != 0) != (p.run_when != 0)); }
 
 }  // namespace ee

@@ -42,8 +42,8 @@ struct Lds {
 // workgroup waits for one memory round trip, not three, before its first weight load.
 __device__ inline bool fill_skip(const Pred& pred, const QkvEpi& e, int M, int layer, int& lds_flag) {
   if (e.fill_from_stride == 0) {
-    const int32_t from = e.fill_from[0];
-    const int32_t flag = pred.flag ? pred.flag[0] : 0;
+    const int32_t from = ctl_load(e.fill_from);
+    const int32_t flag = pred.flag ? ctl_load(pred.flag) : 0;
     if (pred.flag && ((flag != 0) != (pred.run_when != 0))) return true;
     return !(from < layer);
   }
@@ -105,7 +105,7 @@ __device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, con
       p[2 * ai] = e.h + ht_index(m, f_lo, e.Mpad);
       p[2 * ai + 1] = e.h + ht_index(m, f_lo + g.pair_stride, e.Mpad);
     }
-    if (m < g.M && !(e.skip && e.skip[m] != 0)) {   // a sequence that has left keeps its hidden state
+    if (m < g.M && !(e.skip && ctl_load(e.skip + m) != 0)) {   // a sequence that has left keeps its hidden state
 #pragma unroll
       for (int ai = 0; ai < 2; ++ai) {
         unsafeAtomicAdd(p[2 * ai], vlo[ai]);
@@ -289,24 +289,33 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
   int bx = blockIdx.x;
   if constexpr (std::is_same<Epi, QkvEpi>::value && !FILL) {
     // Leading workgroups: the exit decision of the previous layer, one row each.  That layer ran if the batch
-    // has not left, or left at that very layer (the word may already show a sibling's update of this launch;
-    // `done` set at an earlier layer comes with a smaller batch exit layer, both long visible).
+    // has not left, or left at that very layer or later (the words may already show a sibling's update of this
+    // launch; `done` set at an earlier layer comes with a smaller batch exit layer, both visible since an earlier
+    // launch).  The projection's own workgroups apply the SAME rule instead of the live flag, so every workgroup of
+    // the launch takes the same branch whatever the interleaving: the projection of the layer after the batch exit
+    // layer always runs (what it caches is what KV filling caches there anyway), and a tile that two workgroups
+    // share is never left half done.
     if (cj.n_wg) {
+      const IterState& cs = cj.kind == 1 ? cj.a.s : cj.d.s;
+      const int decided_layer = cj.kind == 1 ? cj.a.layer : cj.d.layer;
+      const bool ran = ctl_load(cs.done) == 0 || ctl_load(cs.batch_exit_layer) >= decided_layer;
       if (bx < cj.n_wg) {
         if (cj.kind == 1) {
-          if (bx < cj.a.B && (*cj.a.s.done == 0 || *cj.a.s.batch_exit_layer >= cj.a.layer))
-            combine_row(cj.a, bx, reinterpret_cast<float4*>(&s.red[0][0][0]));
-        } else if (bx == 0 && (*cj.d.s.done == 0 || *cj.d.s.batch_exit_layer >= cj.d.layer)) {
+          if (bx < cj.a.B && ran) combine_row(cj.a, bx, reinterpret_cast<float4*>(&s.red[0][0][0]));
+        } else if (bx == 0 && ran) {
           for (int m = threadIdx.x; m < cj.d.B; m += blockDim.x) decide_from_dot(cj.d, m);
         }
         return;
       }
+      if (!ran) return;
       bx -= cj.n_wg;
+    } else if (pred_skip(pred)) {
+      return;
     }
-  }
-  if constexpr (!FILL) {
+  } else if constexpr (!FILL) {
     if (pred_skip(pred)) return;
-  } else {
+  }
+  if constexpr (FILL) {
     const int layer = (int)gridDim.z - (int)blockIdx.z;   // deepest layer first: the slices that have work start first
     if (fill_skip(pred, e, g.M, layer, s.flag)) return;
     g.w = fc.layers.w_qkv[layer - 1];
@@ -578,7 +587,7 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
       for (int mt = 0; mt < MT; ++mt) {
         const int m = (chunk * MT + mt) * 32 + ml;
         const int row = (e.perm && m < M_eff) ? e.perm[m] : m;
-        if (m < M_eff && !(e.skip && e.skip[row] != 0)) {
+        if (m < M_eff && !(e.skip && ctl_load(e.skip + row) != 0)) {
 #pragma unroll
           for (int a = 0; a < 8; ++a) {
             const int f_lo = packed_row_lo(nt0 + t, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);

@@ -76,32 +76,31 @@ __global__ void copy_f32_kernel(const float* src, float* dst, size_t n) {
 
 // ---------------------------------------------------------------------------------------------------
 // bf16 path, RMSNorm in two small steps.
-//   rowsq_kernel : rowsq[m] += sum_k h[m][k]^2 over a 256-channel slice (grid = (d/256, Mpad/32)).
+//   rowsq_kernel : rowsq[m] += sum_k h[m][k]^2 (grid = Mpad/32 workgroups of 1024 threads).
 //   prep_x_kernel: x = bf16(h * rsqrt(rowsq/d + eps) * gain) written in operand-tile order.
 //     A workgroup covers one 32-row batch tile x 64 channels: thread (m = t%32, c = t/32) owns 8 channels.
 //     grid = (d/64, Mpad/32, slabs); slab z uses gains.g[z] and writes slab z of xT (KV filling: one per layer;
 //     after a layer with an exit head: the head's operand and the next layer's attention operand in one launch).
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void rowsq_kernel(const float* hT, float* rowsq, int Mpad, int d, Pred pred) {
+__global__ __launch_bounds__(1024) void rowsq_kernel(const float* hT, float* rowsq, int Mpad, int d, Pred pred) {
+  // One workgroup per 32-row batch tile walks every channel and sums in a fixed order, so the result does not
+  // depend on how workgroups are scheduled (it runs once per call, not once per layer).
   if (pred_skip(pred)) return;
   const int ml = threadIdx.x & 31, cl = threadIdx.x >> 5;
-  const int m = blockIdx.y * 32 + ml;
-  const int k0 = blockIdx.x * 256 + cl * 32;
+  const int m = blockIdx.x * 32 + ml;
   float ss = 0.0f;
-#pragma unroll 8
-  for (int i = 0; i < 32; ++i) {
-    const int k = k0 + i;
-    const float h = k < d ? hT[ht_index(m, k, Mpad)] : 0.0f;
+  for (int k = cl; k < d; k += 32) {
+    const float h = hT[ht_index(m, k, Mpad)];
     ss = fmaf(h, h, ss);
   }
-  __shared__ float part[8][32];
+  __shared__ float part[32][32];
   part[cl][ml] = ss;
   __syncthreads();
   if (cl == 0) {
     float s = 0.0f;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) s += part[j][ml];
-    unsafeAtomicAdd(rowsq + m, s);
+    for (int j = 0; j < 32; ++j) s += part[j][ml];
+    rowsq[m] += s;
   }
 }
 
@@ -266,7 +265,7 @@ __global__ __launch_bounds__(256) void compact_kernel(const int32_t* status, int
   for (int m0 = 0; m0 < B; m0 += 256) {
     const int m = m0 + (int)threadIdx.x;
     const bool in = m < B;
-    const bool active = in && status[m] == 0;
+    const bool active = in && ctl_load(status + m) == 0;
     const unsigned long long bal = __ballot(active);
     if (lane == 0) wave_total[wave] = __popcll(bal);
     __syncthreads();
@@ -332,7 +331,7 @@ void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t st) {
   hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks), dim3(256), 0, st, src, dst, n);
 }
 void launch_rowsq(const float* hT, float* rowsq, int Mpad, int d, Pred pred, hipStream_t st) {
-  hipLaunchKernelGGL(rowsq_kernel, dim3((d + 255) / 256, Mpad / 32), dim3(256), 0, st, hT, rowsq, Mpad, d, pred);
+  hipLaunchKernelGGL(rowsq_kernel, dim3(Mpad / 32), dim3(1024), 0, st, hT, rowsq, Mpad, d, pred);
 }
 void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, float eps, int Mpad, int d,
                    Pred pred, hipStream_t st) {
