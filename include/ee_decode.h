@@ -188,6 +188,25 @@ int ee_exit_check(const ee_model* model, int32_t layer, const float* hidden, int
                   int32_t* done_flag, int32_t* batch_exit_layer, int32_t* argmax, float* conf, void* workspace,
                   size_t workspace_bytes, void* stream);
 
+/* The same exit check for callers that cannot allocate device memory or hand over a workspace: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, semantics and
+ * results as ee_exit_check without the workspace: the scratch memory is a static device array of
+ * EE_NOALLOC_SCRATCH_BYTES inside the library (each GPU the library runs on holds its own copy until the process
+ * ends).  The call allocates and frees nothing.  A shape and batch that need more scratch than the array holds
+ * (ee_exit_check_noalloc_bytes says how much: roughly batch * (vocab / 2 + 6 * d_model) bytes for EE_BF16, batch *
+ * 4 * (vocab + d_model) for EE_FP32) are refused with EE_ERR_WORKSPACE before anything is enqueued.
+ * Every call on one GPU uses that GPU's one array: calls that overlap on a GPU (two streams, two threads) race;
+ * calls on one stream are ordered and each clears what it needs to start at zero.
+ * ee_noalloc_init resolves the array's device address for the current device (one host-side query, no
+ * allocation); it is otherwise done by the first ee_exit_check_noalloc on that device, so call it beforehand
+ * if that first call would fall inside a graph capture. */
+#define EE_NOALLOC_SCRATCH_BYTES (8u << 20)
+int ee_noalloc_init(void);
+size_t ee_exit_check_noalloc_bytes(const ee_model_desc* desc, int32_t batch);
+int ee_exit_check_noalloc(const ee_model* model, int32_t layer, const float* hidden, int32_t batch, float threshold,
+                          const int32_t* forced_exit_layer, int32_t* status, int32_t* exit_layer, int32_t* n_exited,
+                          int32_t* done_flag, int32_t* batch_exit_layer, int32_t* argmax, float* conf, void* stream);
+
 /* KV-cache filling (Algorithm 1's second loop, Section 3.2): for every sequence b and every layer
  * i > fill_from_layer[b], K = RoPE(RMSNorm(hidden_b; g_attn_i) . Wk_i^T, p_b), V = RMSNorm(..) . Wv_i^T, written to
  * position p_b = context_lens[b] of layer i.  The paper's rule passes the same output_layer for every b.

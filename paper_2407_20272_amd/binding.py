@@ -19,7 +19,9 @@ EE_ERR_INVALID_ARG, EE_ERR_SHAPE, EE_ERR_UNSUPPORTED, EE_ERR_WORKSPACE, EE_ERR_H
 EE_FP32, EE_BF16 = 0, 1
 EE_PACK_PLAIN, EE_PACK_QKV, EE_PACK_GATE_UP = 0, 1, 2
 EXPORTS = ["ee_last_error", "ee_packed_weight_bytes", "ee_pack_weight", "ee_workspace_bytes", "ee_decode_iteration",
-           "ee_exit_check", "ee_kv_fill", "ee_paged_attention_decode", "ee_profile_enable", "ee_profile_read", "ee_calibration_copy"]
+           "ee_exit_check", "ee_kv_fill", "ee_paged_attention_decode", "ee_profile_enable", "ee_profile_read", "ee_calibration_copy",
+           "ee_noalloc_init", "ee_exit_check_noalloc_bytes", "ee_exit_check_noalloc"]
+EE_NOALLOC_SCRATCH_BYTES = 8 << 20
 KERNEL_CLASSES = ["norm", "qkv", "attention", "o_proj", "gate_up", "down", "head", "combine", "kv_fill", "other"]
 
 
@@ -77,6 +79,10 @@ def lib() -> C.CDLL:
         L.ee_exit_check.argtypes = [C.POINTER(ee_model), C.c_int32, C.c_void_p, C.c_int32, C.c_float, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_size_t, C.c_void_p]
+        L.ee_exit_check_noalloc.argtypes = L.ee_exit_check.argtypes[:13] + [C.c_void_p]
+        L.ee_exit_check_noalloc_bytes.restype = C.c_size_t
+        L.ee_exit_check_noalloc_bytes.argtypes = [C.POINTER(ee_model_desc), C.c_int32]
+        L.ee_noalloc_init.argtypes = []
         L.ee_kv_fill.argtypes = [C.POINTER(ee_model), C.POINTER(ee_kv_cache), C.POINTER(ee_batch), C.c_void_p,
                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.ee_paged_attention_decode.argtypes = [C.POINTER(ee_model_desc), C.POINTER(ee_kv_cache), C.c_int32, C.c_void_p,
@@ -87,7 +93,8 @@ def lib() -> C.CDLL:
         L.ee_profile_read.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int32]
         L.ee_profile_enable.restype = C.c_int
         L.ee_profile_read.restype = C.c_int
-        for name in ("ee_pack_weight", "ee_decode_iteration", "ee_exit_check", "ee_kv_fill", "ee_paged_attention_decode"):
+        for name in ("ee_pack_weight", "ee_decode_iteration", "ee_exit_check", "ee_kv_fill", "ee_paged_attention_decode",
+                     "ee_exit_check_noalloc", "ee_noalloc_init"):
             getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -247,6 +254,21 @@ def ee_exit_check(model: DeviceModel, layer: int, hidden, threshold: float, forc
     _check(lib().ee_exit_check(C.byref(model.c), layer, _ptr(hidden), int(hidden.shape[0]), float(threshold),
                                _ptr(forced_exit_layer), _ptr(status), _ptr(exit_layer), _ptr(n_exited), _ptr(done_flag),
                                _ptr(batch_exit_layer), _ptr(argmax), _ptr(conf), _ptr(ws.buf), ws.bytes, _stream()))
+
+
+def ee_noalloc_init():
+    _check(lib().ee_noalloc_init())
+
+
+def ee_exit_check_noalloc_bytes(desc: ee_model_desc, batch: int) -> int:
+    return lib().ee_exit_check_noalloc_bytes(C.byref(desc), batch)
+
+
+def ee_exit_check_noalloc(model: DeviceModel, layer: int, hidden, threshold: float, forced_exit_layer, status, exit_layer,
+                          n_exited, done_flag, batch_exit_layer, argmax, conf):
+    _check(lib().ee_exit_check_noalloc(C.byref(model.c), layer, _ptr(hidden), int(hidden.shape[0]), float(threshold),
+                                       _ptr(forced_exit_layer), _ptr(status), _ptr(exit_layer), _ptr(n_exited),
+                                       _ptr(done_flag), _ptr(batch_exit_layer), _ptr(argmax), _ptr(conf), _stream()))
 
 
 def ee_kv_fill(model: DeviceModel, cache: PagedKV, batch: ee_batch, hidden, fill_from_layer, ws: Workspace):

@@ -8,6 +8,9 @@
 
 #include "ee_common.h"
 
+// Scratch of ee_exit_check_noalloc (see noalloc_scratch below).
+static __device__ __align__(256) unsigned char scratch[EE_NOALLOC_SCRATCH_BYTES];
+
 namespace ee {
 
 static thread_local char g_error[512] = "";
@@ -142,6 +145,34 @@ Workspace carve(const ee_model_desc& D, int B, void* base) {
     w.logits = c.take<float>(Bp * V);
     w.hprev = c.take<float>(Bp * d);
     w.msr = c.take<float>(3 * Bp);
+  }
+  w.bytes = (c.off + 255) & ~(size_t)255;
+  return w;
+}
+
+// The part of the workspace the stand-alone exit check touches, carved on its own: the allocation-free entry
+// point fits it into the library's static scratch array instead of a caller's workspace.
+Workspace carve_exit_check(const ee_model_desc& D, int B, void* base) {
+  Workspace w{};
+  Carver c{reinterpret_cast<char*>(base), 0};
+  const int Bp = B < 1 ? 1 : B;
+  const int Mpad = round_up(Bp, 32);
+  const size_t d = D.d_model, V = D.vocab;
+  w.status = c.take<int32_t>(Bp);
+  w.n_exited = c.take<int32_t>(1);
+  w.done = c.take<int32_t>(1);
+  w.scratch_exit_layer = c.take<int32_t>(Bp);
+  w.scratch_L = c.take<int32_t>(1);
+  if (D.dtype == EE_BF16) {
+    w.partials = c.take<float4>((size_t)Mpad * (V / 32));
+    w.hT = c.take<float>(d * Mpad);
+    w.xH = c.take<bf16_t>(d * Mpad);
+    w.zero_count = Mpad;
+    w.rowsq = c.take<float>(w.zero_count);
+  } else {
+    w.partials = c.take<float4>(Bp);
+    w.x = c.take<float>(Bp * d);
+    w.logits = c.take<float>(Bp * V);
   }
   w.bytes = (c.off + 255) & ~(size_t)255;
   return w;
@@ -323,6 +354,72 @@ void enqueue_fill_f32(const ee_model& M, const ee_kv_cache& C, const ee_batch& B
     e.fill_from_stride = stride;
     launch_simple_qkv(g, e, pred, st);
   }
+}
+
+// --- stand-alone exit check: validation and launch sequence shared by the two entry points -----------------
+int check_exit_check_args(const ee_model* model, int32_t layer, const float* hidden, int32_t batch, const int32_t* status,
+                          const int32_t* exit_layer, const int32_t* n_exited, const int32_t* done_flag,
+                          const int32_t* batch_exit_layer) {
+  int rc;
+  if ((rc = check_model(model))) return rc;
+  const ee_model_desc& D = model->desc;
+  if (batch < 0) EE_FAIL(EE_ERR_INVALID_ARG, "batch size %d is negative", batch);
+  if (batch == 0) return EE_OK;
+  if (layer < 1 || layer > D.n_layers) EE_FAIL(EE_ERR_INVALID_ARG, "layer %d outside 1..%d", layer, D.n_layers);
+  if (D.conf_mode >= 2)
+    EE_FAIL(EE_ERR_UNSUPPORTED, "ee_exit_check: conf_mode %d has no exit head; it only runs inside ee_decode_iteration",
+            D.conf_mode);
+  if (!hidden || !status || !exit_layer || !n_exited || !done_flag || !batch_exit_layer)
+    EE_FAIL(EE_ERR_INVALID_ARG, "ee_exit_check: NULL pointer");
+  return EE_OK;
+}
+
+int enqueue_exit_check(const ee_model& M, int32_t layer, const float* hidden, int32_t batch, float threshold,
+                       const int32_t* forced_exit_layer, int32_t* status, int32_t* exit_layer, int32_t* n_exited,
+                       int32_t* done_flag, int32_t* batch_exit_layer, int32_t* argmax, float* conf, const Workspace& w,
+                       hipStream_t st) {
+  const ee_model_desc& D = M.desc;
+  const int Mpad = round_up(batch, 32);
+  const Pred always{nullptr, 0};
+  const float scale = D.logit_scale * (float)layer;
+  if (D.dtype == EE_BF16) {
+    launch_iter_init(IterState{w.status, w.scratch_exit_layer, w.n_exited, w.done, w.scratch_L}, 0, D.n_layers, nullptr,
+                     w.rowsq, (size_t)Mpad, st);
+    launch_hidden_to_ht(hidden, w.hT, batch, Mpad, D.d_model, st);
+    launch_rowsq(w.hT, w.rowsq, Mpad, D.d_model, always, st);
+    enqueue_head_bf16(M, w, batch, Mpad, scale, w.rowsq, layer, false, RowMap{}, always, st);
+  } else {
+    enqueue_head_f32(M, w, hidden, batch, scale, layer, always, st);
+  }
+  IterState s{status, exit_layer, n_exited, done_flag, batch_exit_layer};
+  CombineArgs ca{w.partials, D.dtype == EE_BF16 ? D.vocab / 32 : 1, batch, layer, scale, threshold, D.conf_mode,
+                 forced_exit_layer, s, argmax, conf};
+  launch_combine(ca, always, st);
+  EE_HIP(hipGetLastError());
+  return EE_OK;
+}
+
+// --- scratch of the allocation-free entry point ---------------------------------------------------------------
+// A file-scope device array: every GPU the library runs on holds its own copy at its own address until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress; the address that kernels, fills
+// and copies take is the one resolved below, once per device, with that device current.
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+int noalloc_scratch(void** out) {
+  int dev = -1;
+  EE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) EE_FAIL(EE_ERR_UNSUPPORTED, "device ordinal %d outside 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lk(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    EE_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || (reinterpret_cast<uintptr_t>(p) & 255)) EE_FAIL(EE_ERR_HIP, "static scratch array has no usable device address");
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return EE_OK;
 }
 
 }  // namespace
@@ -687,37 +784,41 @@ int ee_exit_check(const ee_model* model, int32_t layer, const float* hidden, int
                   int32_t* done_flag, int32_t* batch_exit_layer, int32_t* argmax, float* conf, void* workspace,
                   size_t workspace_bytes, void* stream) {
   int rc;
-  if ((rc = check_model(model))) return rc;
-  const ee_model_desc& D = model->desc;
-  if (batch < 0) EE_FAIL(EE_ERR_INVALID_ARG, "batch size %d is negative", batch);
+  if ((rc = check_exit_check_args(model, layer, hidden, batch, status, exit_layer, n_exited, done_flag, batch_exit_layer)))
+    return rc;
   if (batch == 0) return EE_OK;
-  if (layer < 1 || layer > D.n_layers) EE_FAIL(EE_ERR_INVALID_ARG, "layer %d outside 1..%d", layer, D.n_layers);
-  if (D.conf_mode >= 2)
-    EE_FAIL(EE_ERR_UNSUPPORTED, "ee_exit_check: conf_mode %d has no exit head; it only runs inside ee_decode_iteration",
-            D.conf_mode);
-  if (!hidden || !status || !exit_layer || !n_exited || !done_flag || !batch_exit_layer)
-    EE_FAIL(EE_ERR_INVALID_ARG, "ee_exit_check: NULL pointer");
-  if ((rc = check_workspace(D, batch, workspace, workspace_bytes))) return rc;
-  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-  const Workspace w = carve(D, batch, workspace);
-  const int Mpad = round_up(batch, 32);
-  const Pred always{nullptr, 0};
-  const float scale = D.logit_scale * (float)layer;
-  if (D.dtype == EE_BF16) {
-    launch_iter_init(IterState{w.status, w.scratch_exit_layer, w.n_exited, w.done, w.scratch_L}, 0, D.n_layers, nullptr,
-                     w.rowsq, (size_t)Mpad, st);
-    launch_hidden_to_ht(hidden, w.hT, batch, Mpad, D.d_model, st);
-    launch_rowsq(w.hT, w.rowsq, Mpad, D.d_model, always, st);
-    enqueue_head_bf16(*model, w, batch, Mpad, scale, w.rowsq, layer, false, RowMap{}, always, st);
-  } else {
-    enqueue_head_f32(*model, w, hidden, batch, scale, layer, always, st);
-  }
-  IterState s{status, exit_layer, n_exited, done_flag, batch_exit_layer};
-  CombineArgs ca{w.partials, D.dtype == EE_BF16 ? D.vocab / 32 : 1, batch, layer, scale, threshold, D.conf_mode,
-                 forced_exit_layer, s, argmax, conf};
-  launch_combine(ca, always, st);
-  EE_HIP(hipGetLastError());
-  return EE_OK;
+  if ((rc = check_workspace(model->desc, batch, workspace, workspace_bytes))) return rc;
+  return enqueue_exit_check(*model, layer, hidden, batch, threshold, forced_exit_layer, status, exit_layer, n_exited,
+                            done_flag, batch_exit_layer, argmax, conf, carve(model->desc, batch, workspace),
+                            reinterpret_cast<hipStream_t>(stream));
+}
+
+size_t ee_exit_check_noalloc_bytes(const ee_model_desc* desc, int32_t batch) {
+  if (check_desc(desc) != EE_OK || batch < 0) return 0;
+  return carve_exit_check(*desc, batch, nullptr).bytes;
+}
+
+int ee_noalloc_init(void) {
+  void* p = nullptr;
+  return noalloc_scratch(&p);
+}
+
+int ee_exit_check_noalloc(const ee_model* model, int32_t layer, const float* hidden, int32_t batch, float threshold,
+                          const int32_t* forced_exit_layer, int32_t* status, int32_t* exit_layer, int32_t* n_exited,
+                          int32_t* done_flag, int32_t* batch_exit_layer, int32_t* argmax, float* conf, void* stream) {
+  int rc;
+  if ((rc = check_exit_check_args(model, layer, hidden, batch, status, exit_layer, n_exited, done_flag, batch_exit_layer)))
+    return rc;
+  if (batch == 0) return EE_OK;
+  const size_t need = carve_exit_check(model->desc, batch, nullptr).bytes;
+  if (need > (size_t)EE_NOALLOC_SCRATCH_BYTES)
+    EE_FAIL(EE_ERR_WORKSPACE, "ee_exit_check_noalloc: this shape and batch need %zu bytes of scratch, the static array holds %zu",
+            need, (size_t)EE_NOALLOC_SCRATCH_BYTES);
+  void* base = nullptr;
+  if ((rc = noalloc_scratch(&base))) return rc;
+  return enqueue_exit_check(*model, layer, hidden, batch, threshold, forced_exit_layer, status, exit_layer, n_exited,
+                            done_flag, batch_exit_layer, argmax, conf, carve_exit_check(model->desc, batch, base),
+                            reinterpret_cast<hipStream_t>(stream));
 }
 
 int ee_kv_fill(const ee_model* model, const ee_kv_cache* cache, const ee_batch* batch, const float* hidden,

@@ -1,0 +1,96 @@
+"""The allocation-free exit check (static device scratch inside the library) against the entry point that takes a
+caller's workspace: same inputs, two calls in a row on one stream, the second with a smaller batch, so that the
+second call finds the first call's contents in the shared scratch array."""
+import ctypes as C
+
+import pytest
+import torch
+
+from paper_2407_20272_amd import binding as B
+from paper_2407_20272_amd import workloads as W
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(300)]
+
+
+def exit_check_both_ways(cfg, model, seed, batch, layer, threshold, forced=None, pre_status=None):
+    """Runs ee_exit_check and ee_exit_check_noalloc on the same inputs; returns the two result tuples."""
+    n = cfg.n_layers
+    g = torch.Generator().manual_seed(seed)
+    hidden = (torch.randn(batch, cfg.d_model, generator=g) * 3.0).cuda()
+    status0 = torch.zeros(batch, dtype=torch.int32) if pre_status is None else pre_status.clone()
+    exit0 = torch.where(status0 > 0, torch.ones_like(status0), torch.full_like(status0, n))
+    f = None if forced is None else forced.cuda()
+    ws = B.Workspace(model.desc, batch, 16)
+    outs = []
+    for noalloc in (False, True):
+        status, exit_layer = status0.cuda(), exit0.cuda()
+        n_exited = torch.tensor([int(status0.sum())], dtype=torch.int32, device="cuda")
+        done = torch.zeros(1, dtype=torch.int32, device="cuda")
+        L = torch.full((1,), n, dtype=torch.int32, device="cuda")
+        argmax = torch.full((batch,), -1, dtype=torch.int32, device="cuda")
+        conf = torch.zeros(batch, dtype=torch.float32, device="cuda")
+        if noalloc:
+            B.ee_exit_check_noalloc(model, layer, hidden, threshold, f, status, exit_layer, n_exited, done, L, argmax, conf)
+        else:
+            B.ee_exit_check(model, layer, hidden, threshold, f, status, exit_layer, n_exited, done, L, argmax, conf, ws)
+        torch.cuda.synchronize()
+        outs.append((status.cpu(), exit_layer.cpu(), int(n_exited.item()), int(done.item()), int(L.item()), argmax.cpu(),
+                     conf.cpu()))
+    return outs
+
+
+def assert_same(a, b, what):
+    """Both entry points run the same kernels on the same inputs in the same order: every output is identical,
+    bit for bit (NaN marks rows that were not checked, in the same places)."""
+    for x, y, name in zip(a[:6], b[:6], ("status", "exit_layer", "n_exited", "done", "batch_exit_layer", "argmax")):
+        assert (torch.equal(x, y) if isinstance(x, torch.Tensor) else x == y), f"{what}: {name} differs"
+    assert torch.equal(torch.isnan(a[6]), torch.isnan(b[6])), f"{what}: different rows were checked"
+    ok = ~torch.isnan(a[6])
+    assert torch.equal(a[6][ok], b[6][ok]), f"{what}: confidences differ by {(a[6][ok] - b[6][ok]).abs().max()}"
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "fp32"])
+def test_noalloc_exit_check_equals_workspace_exit_check_twice_second_call_smaller(dtype):
+    cfg = W.reduced(W.CONFIGS[1], n_layers=6, d_model=256, n_heads=4, head_dim=64, d_ffn=512, vocab=1024 + 64,
+                    logit_scale=2.0, batch=70, dtype=dtype)
+    w = W.make_weights(cfg, seed=11, gain_jitter=0.2)
+    model = B.DeviceModel(cfg, w)
+    B.ee_noalloc_init()
+    assert 0 < B.ee_exit_check_noalloc_bytes(model.desc, 70) <= B.EE_NOALLOC_SCRATCH_BYTES
+    # first call: 70 rows (three batch tiles, the last one ragged), some already accepted, a threshold that splits the rest
+    pre = torch.zeros(70, dtype=torch.int32)
+    pre[::9] = 1
+    a, b = exit_check_both_ways(cfg, model, seed=1, batch=70, layer=3, threshold=0.2, pre_status=pre)
+    assert 0 < int(a[0].sum()) and a[2] < 70, "the threshold should split the batch"
+    assert_same(a, b, "first call, batch 70")
+    # second call right behind it: 5 rows, everybody accepted (forced), so the done flag and the batch exit layer are set;
+    # the scratch array still holds the first call's 70 rows
+    forced = torch.tensor([2, 1, 4, 3, 4], dtype=torch.int32)
+    a, b = exit_check_both_ways(cfg, model, seed=2, batch=5, layer=4, threshold=0.5, forced=forced)
+    assert a[3] == 1 and a[4] == 4 and a[2] == 5
+    assert_same(a, b, "second call, batch 5")
+    # and once more with a plain threshold on the small batch
+    a, b = exit_check_both_ways(cfg, model, seed=3, batch=5, layer=5, threshold=0.3)
+    assert_same(a, b, "third call, batch 5")
+
+
+def test_noalloc_exit_check_at_llama7b_width_and_size_limit():
+    """The LM head of the 7B-shaped workload at batch 32 fits the static array; a batch that does not is refused on the
+    host with a message, before anything is enqueued."""
+    cfg = W.reduced(W.CONFIGS[1], n_layers=2, d_ffn=256)
+    w = W.make_weights(cfg, seed=40, device="cuda")
+    model = B.DeviceModel(cfg, w)
+    del w
+    a, b = exit_check_both_ways(cfg, model, seed=4, batch=32, layer=1, threshold=0.9)
+    assert_same(a, b, "7B width, batch 32")
+    a, b = exit_check_both_ways(cfg, model, seed=5, batch=7, layer=1, threshold=0.9)
+    assert_same(a, b, "7B width, batch 7")
+    too_many = 512
+    assert B.ee_exit_check_noalloc_bytes(model.desc, too_many) > B.EE_NOALLOC_SCRATCH_BYTES
+    hidden = torch.zeros(too_many, cfg.d_model, device="cuda")
+    st = torch.zeros(too_many, dtype=torch.int32, device="cuda")
+    one = torch.zeros(1, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.EEError) as err:
+        B.ee_exit_check_noalloc(model, 1, hidden, 0.9, None, st, st.clone(), one, one.clone(), one.clone(), None, None)
+    assert err.value.code == B.EE_ERR_WORKSPACE and "static array" in str(err.value)
+    assert int(st.sum()) == 0
