@@ -43,7 +43,9 @@ the batch leaving together); its docstring states its rule.
 Pins (tests/test_oracle_*.py): brute-force uncached causal forward, threshold > 1 equals the
 head-less full-layer pass, forced exit on a saturated model leaves the cache identical to a full
 pass, control logic against its three-line definition, closed forms of the confidence, rotary and
-attention special cases against library routines.  The 7B/13B-shaped token values themselves are
+attention special cases against library routines.  The bf16 storage points listed above are pinned
+by a second brute-force forward, from library routines, that rounds at exactly those points
+(tests/test_oracle_bf16_contract.py): removing or adding any single rounding here fails it.  The 7B/13B-shaped token values themselves are
 "parity unpinned" by anything external: no published value exists for them.
 """
 from __future__ import annotations

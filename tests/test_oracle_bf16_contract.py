@@ -1,0 +1,203 @@
+"""Pin for the oracle's bf16 numerics contract: WHERE values are rounded to bf16.
+
+The decode step keeps some tensors in bf16 storage (weights, the K/V cache, and every operand of a projection:
+the normalised hidden state, the attention output, the SwiGLU product) and keeps others in float (the residual
+stream, q, scores, softmax, logits, confidences).  The oracle mirrors that with `store()` calls.  Moving one of
+them changes values by a few tenths of a percent: too little for a tolerance of 2e-2 to see, enough to move exit
+confidences.  So the placement itself is pinned here, against something other than the oracle:
+
+  P9  a brute-force UNCACHED causal forward over the whole token history, built from library routines only
+      (F.linear, F.rms_norm, F.silu, scaled_dot_product_attention, complex-number rotary), that rounds with
+      `.to(torch.bfloat16)` at exactly the storage points listed above and nowhere else.  Tokens, the whole cache
+      (bit for bit: it holds bf16 values), the per-layer hidden states, the exit-head confidences and the filled
+      K/V of a forced exit must agree with the oracle run in dtype "bf16".
+  P9m planted mistakes: every `store()` of the oracle is removed or an extra one added, one at a time (the mistake
+      is planted in the oracle, on the CPU); each such oracle must FAIL P9.
+"""
+import inspect
+import math
+
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import ee_oracle as O
+from paper_2407_20272_amd import workloads as W
+
+F64 = torch.float64
+BF = torch.bfloat16
+
+
+def r16(x):
+    """Value after a trip through bf16 storage (from the float the decode step holds it in)."""
+    return x.to(torch.float32).to(BF).to(F64)
+
+
+def cfg_bf16(**kw):
+    base = dict(n_layers=3, d_model=64, n_heads=2, head_dim=32, d_ffn=96, vocab=50, batch=3, prompt_len=6,
+                min_prompt_len=3, decode_steps=3, weight_std=0.15, dtype="bf16", tied_head=False, logit_scale=1.5,
+                threshold=0.3)
+    base.update(kw)
+    return W.reduced(W.CONFIGS[0], **base)
+
+
+def rope_complex(x, theta):
+    """x [T][H][dh] at positions 0..T-1; pairs (j, j+dh/2) rotated as complex numbers."""
+    T, H, dh = x.shape
+    half = dh // 2
+    z = torch.complex(x[..., :half], x[..., half:])
+    freq = theta ** (-torch.arange(half, dtype=F64) * 2.0 / dh)
+    rot = torch.polar(torch.ones(T, half, dtype=F64), torch.arange(T, dtype=F64)[:, None] * freq[None, :])
+    z = z * rot[:, None, :]
+    return torch.cat([z.real, z.imag], dim=-1)
+
+
+def brute_forward_bf16(cfg, w, toks):
+    """Uncached causal forward of toks [T] with bf16 storage points.  Returns (hidden states of the LAST position
+    after each layer [n][d], K list, V list per layer as [T][H][dh] holding bf16 values)."""
+    T = toks.shape[0]
+    H, dh, d = cfg.n_heads, cfg.head_dim, cfg.d_model
+    h = w["embed"].to(F64)[toks.long()]                                        # embedding rows are bf16 already
+    hs, Ks, Vs = [], [], []
+    for lw in w["layers"]:
+        x = r16(F.rms_norm(h, (d,), lw["g_attn"].to(F64), cfg.rms_eps))       # storage: operand of the QKV projection
+        q = rope_complex(F.linear(x, lw["w_q"].to(F64)).view(T, H, dh), cfg.rope_theta)          # float, not stored
+        k = r16(rope_complex(F.linear(x, lw["w_k"].to(F64)).view(T, H, dh), cfg.rope_theta))     # storage: cache
+        v = r16(F.linear(x, lw["w_v"].to(F64)).view(T, H, dh))                                   # storage: cache
+        Ks.append(k)
+        Vs.append(v)
+        a = F.scaled_dot_product_attention(q.transpose(0, 1), k.transpose(0, 1), v.transpose(0, 1), is_causal=True)
+        a = r16(a.transpose(0, 1).reshape(T, H * dh))                          # storage: operand of the output projection
+        h = h + F.linear(a, lw["w_o"].to(F64))                                 # residual stream: float
+        x = r16(F.rms_norm(h, (d,), lw["g_ffn"].to(F64), cfg.rms_eps))        # storage: operand of gate/up
+        act = r16(F.silu(F.linear(x, lw["w_gate"].to(F64))) * F.linear(x, lw["w_up"].to(F64)))   # storage: operand of down
+        h = h + F.linear(act, lw["w_down"].to(F64))
+        hs.append(h[-1].clone())
+    return torch.stack(hs), Ks, Vs
+
+
+def head_bf16(cfg, w, h):
+    """Unscaled LM-head logits of hidden rows: the head's operand is stored in bf16, the logits are not."""
+    x = r16(F.rms_norm(h, (cfg.d_model,), w["g_final"].to(F64), cfg.rms_eps))
+    return F.linear(x, w["w_lm"].to(F64))
+
+
+def check_contract(cfg=None, seed=11):
+    """Runs the oracle (dtype bf16) and the brute force side by side; raises AssertionError on any difference."""
+    cfg = cfg or cfg_bf16()
+    n, Bsz, steps = cfg.n_layers, cfg.batch, cfg.decode_steps
+    w = W.make_weights(cfg, seed=seed, gain_jitter=0.2)
+    m = O.model_from_config(cfg, w)
+    prompts, lens = W.make_prompts(cfg, seed=seed), W.make_context_lens(cfg, seed=seed)
+
+    # (a) full layers: tokens, the whole cache, the hidden state of every layer, logits
+    cache = O.DenseKV(n, Bsz, int(lens.max()) + steps, cfg.n_heads, cfg.head_dim, cfg.dtype)
+    tok = O.prefill(m, cache, prompts, lens)
+    hist = [torch.cat([prompts[b, :int(lens[b])], tok[b:b + 1]]) for b in range(Bsz)]
+    pos = lens.clone().long()
+    for s in range(steps):
+        tr = {}
+        nxt, _, L = O.decode_iteration(m, cache, tok, pos, 2.0, trace=tr)
+        assert L == n
+        for b in range(Bsz):
+            hs, _, _ = brute_forward_bf16(cfg, w, hist[b])
+            for i in range(n):
+                torch.testing.assert_close(tr["h"][i][b], hs[i], rtol=1e-9, atol=1e-11,
+                                           msg=lambda t: f"step {s}, sequence {b}, hidden state after layer {i + 1}: {t}")
+            z = head_bf16(cfg, w, hs[-1])
+            torch.testing.assert_close(O.head_logits(m, tr["h_exit"][b:b + 1])[0], z, rtol=1e-9, atol=1e-11)
+            assert int(torch.argmax(z)) == int(nxt[b]), (s, b)
+            hist[b] = torch.cat([hist[b], nxt[b:b + 1]])
+        tok = nxt
+        pos += 1
+    for b in range(Bsz):
+        T = int(lens[b]) + steps
+        _, Ks, Vs = brute_forward_bf16(cfg, w, hist[b][:T])
+        for i in range(n):
+            assert cache.K[i].dtype == BF and cache.V[i].dtype == BF
+            assert torch.equal(cache.K[i][b, :T].to(F64), Ks[i]), f"K cache of layer {i + 1}, sequence {b}"
+            assert torch.equal(cache.V[i][b, :T].to(F64), Vs[i]), f"V cache of layer {i + 1}, sequence {b}"
+
+    # (b) early exit with the config's threshold: confidences of every check that was made, and the filled K/V
+    cache = O.DenseKV(n, Bsz, int(lens.max()) + 1, cfg.n_heads, cfg.head_dim, cfg.dtype)
+    tok = O.prefill(m, cache, prompts, lens)
+    pos = lens.clone().long()
+    forced_L = 1
+    tr = {}
+    _, e, L = O.decode_iteration(m, cache, tok, pos, cfg.threshold,
+                                 forced_exit_layer=torch.full((Bsz,), forced_L, dtype=torch.int32), trace=tr)
+    assert L == forced_L
+    for b in range(Bsz):
+        hist_b = torch.cat([prompts[b, :int(lens[b])], tok[b:b + 1]])
+        hs, _, _ = brute_forward_bf16(cfg, w, hist_b)
+        z = head_bf16(cfg, w, hs[forced_L - 1])
+        c = torch.softmax(cfg.logit_scale * forced_L * z, -1).max()
+        assert float(tr["conf"][forced_L - 1, b]) == pytest.approx(float(c), rel=1e-9), f"confidence of sequence {b}"
+        p = int(pos[b])
+        for i in range(forced_L + 1, n + 1):                  # Section 3.2: K/V of the skipped layers from the exit state
+            lw = w["layers"][i - 1]
+            x = r16(F.rms_norm(hs[forced_L - 1], (cfg.d_model,), lw["g_attn"].to(F64), cfg.rms_eps))
+            k = F.linear(x, lw["w_k"].to(F64)).view(cfg.n_heads, cfg.head_dim)
+            k = r16(rope_complex(k[None].expand(p + 1, -1, -1).contiguous(), cfg.rope_theta)[p])
+            v = r16(F.linear(x, lw["w_v"].to(F64)).view(cfg.n_heads, cfg.head_dim))
+            assert torch.equal(cache.K[i - 1][b, p].to(F64), k), f"filled K of layer {i}, sequence {b}"
+            assert torch.equal(cache.V[i - 1][b, p].to(F64), v), f"filled V of layer {i}, sequence {b}"
+
+
+def test_p9_bf16_storage_points_against_bruteforce():
+    check_contract()
+
+
+def test_p9_bf16_storage_points_other_shape_and_seed():
+    check_contract(cfg_bf16(n_layers=2, d_model=96, n_heads=3, d_ffn=80, vocab=37, batch=2, prompt_len=4,
+                            min_prompt_len=4, decode_steps=2), seed=12)
+
+
+# ------------------------------------------------------------------------------------------------
+# P9m: planted mistakes in the oracle's rounding points must fail the pin
+# ------------------------------------------------------------------------------------------------
+MUTANTS = {
+    # name: (oracle function, text to replace, replacement, which occurrence)
+    "attention output not rounded": ("layer_forward", "a = store(a.reshape(B, H * dh), dt)", "a = a.reshape(B, H * dh)", 0),
+    "SwiGLU product not rounded": ("layer_forward", "act = store(g / (1.0 + torch.exp(-g)) * u, dt)",
+                                   "act = g / (1.0 + torch.exp(-g)) * u", 0),
+    "FFN-norm operand not rounded": ("layer_forward", 'x = store(rmsnorm(h, m.weights["layers"][i - 1]["g_ffn"], m.rms_eps), dt)',
+                                     'x = rmsnorm(h, m.weights["layers"][i - 1]["g_ffn"], m.rms_eps)', 0),
+    "attention-norm operand not rounded": ("layer_forward",
+                                           'x = store(rmsnorm(h, m.weights["layers"][i - 1]["g_attn"], m.rms_eps), dt)',
+                                           'x = rmsnorm(h, m.weights["layers"][i - 1]["g_attn"], m.rms_eps)', 0),
+    "residual stream rounded after the FFN": ("layer_forward", 'return h + act @ _w(m, i, "w_down").T',
+                                              'return store(h + act @ _w(m, i, "w_down").T, dt)', 0),
+    "residual stream rounded after attention": ("layer_forward", 'h = h + a @ _w(m, i, "w_o").T',
+                                                'h = store(h + a @ _w(m, i, "w_o").T, dt)', 0),
+    "q rounded": ("layer_forward", "q = rope(q, pos, m.rope_theta)", "q = store(rope(q, pos, m.rope_theta), dt)", 0),
+    "gate rounded before the product": ("layer_forward", 'g = x @ _w(m, i, "w_gate").T', 'g = store(x @ _w(m, i, "w_gate").T, dt)', 0),
+    "exit-head operand not rounded": ("head_logits", 'x = store(rmsnorm(h, m.weights["g_final"], m.rms_eps), m.dtype)',
+                                      'x = rmsnorm(h, m.weights["g_final"], m.rms_eps)', 0),
+    "exit-head logits rounded": ("head_logits", 'return x @ m.weights["w_lm"].to(F64).T',
+                                 'return store(x @ m.weights["w_lm"].to(F64).T, m.dtype)', 0),
+    "filling operand not rounded": ("kv_fill", 'x = store(rmsnorm(h, m.weights["layers"][i - 1]["g_attn"], m.rms_eps), dt)',
+                                    'x = rmsnorm(h, m.weights["layers"][i - 1]["g_attn"], m.rms_eps)', 0),
+    "filled K rounded before the rotation": ("kv_fill", 'k = rope((x @ _w(m, i, "w_k").T).reshape(B, H, dh), pos, m.rope_theta)',
+                                             'k = rope(store(x @ _w(m, i, "w_k").T, dt).reshape(B, H, dh), pos, m.rope_theta)', 0),
+}
+
+
+def make_mutant(fn_name, old, new, which):
+    """The oracle function `fn_name` with one piece of its source text replaced, compiled in a copy of the
+    oracle's namespace."""
+    src = inspect.getsource(getattr(O, fn_name))
+    assert src.count(old) > which, f"the oracle's source no longer contains {old!r}"
+    parts = src.split(old)
+    src = old.join(parts[:which + 1]) + new + old.join(parts[which + 1:])
+    ns = dict(vars(O))
+    exec(compile(src, f"<mutant of {fn_name}>", "exec"), ns)
+    return ns[fn_name]
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_p9m_planted_rounding_mistakes_fail_the_pin(monkeypatch, name):
+    fn_name, old, new, which = MUTANTS[name]
+    monkeypatch.setattr(O, fn_name, make_mutant(fn_name, old, new, which))
+    with pytest.raises(AssertionError):
+        check_contract()
