@@ -14,7 +14,6 @@ confidences.  So the placement itself is pinned here, against something other th
   P9m planted mistakes: every `store()` of the oracle is removed or an extra one added, one at a time (the mistake
       is planted in the oracle, on the CPU); each such oracle must FAIL P9.
 """
-import inspect
 import math
 
 import pytest
@@ -22,6 +21,7 @@ import torch
 import torch.nn.functional as F
 
 from oracle import ee_oracle as O
+from oracle_mutants import MUTANTS, planted
 from paper_2407_20272_amd import workloads as W
 
 F64 = torch.float64
@@ -156,48 +156,9 @@ def test_p9_bf16_storage_points_other_shape_and_seed():
 # ------------------------------------------------------------------------------------------------
 # P9m: planted mistakes in the oracle's rounding points must fail the pin
 # ------------------------------------------------------------------------------------------------
-MUTANTS = {
-    # name: (oracle function, text to replace, replacement, which occurrence)
-    "attention output not rounded": ("layer_forward", "a = store(a.reshape(B, H * dh), dt)", "a = a.reshape(B, H * dh)", 0),
-    "SwiGLU product not rounded": ("layer_forward", "act = store(g / (1.0 + torch.exp(-g)) * u, dt)",
-                                   "act = g / (1.0 + torch.exp(-g)) * u", 0),
-    "FFN-norm operand not rounded": ("layer_forward", 'x = store(rmsnorm(h, m.weights["layers"][i - 1]["g_ffn"], m.rms_eps), dt)',
-                                     'x = rmsnorm(h, m.weights["layers"][i - 1]["g_ffn"], m.rms_eps)', 0),
-    "attention-norm operand not rounded": ("layer_forward",
-                                           'x = store(rmsnorm(h, m.weights["layers"][i - 1]["g_attn"], m.rms_eps), dt)',
-                                           'x = rmsnorm(h, m.weights["layers"][i - 1]["g_attn"], m.rms_eps)', 0),
-    "residual stream rounded after the FFN": ("layer_forward", 'return h + act @ _w(m, i, "w_down").T',
-                                              'return store(h + act @ _w(m, i, "w_down").T, dt)', 0),
-    "residual stream rounded after attention": ("layer_forward", 'h = h + a @ _w(m, i, "w_o").T',
-                                                'h = store(h + a @ _w(m, i, "w_o").T, dt)', 0),
-    "q rounded": ("layer_forward", "q = rope(q, pos, m.rope_theta)", "q = store(rope(q, pos, m.rope_theta), dt)", 0),
-    "gate rounded before the product": ("layer_forward", 'g = x @ _w(m, i, "w_gate").T', 'g = store(x @ _w(m, i, "w_gate").T, dt)', 0),
-    "exit-head operand not rounded": ("head_logits", 'x = store(rmsnorm(h, m.weights["g_final"], m.rms_eps), m.dtype)',
-                                      'x = rmsnorm(h, m.weights["g_final"], m.rms_eps)', 0),
-    "exit-head logits rounded": ("head_logits", 'return x @ m.weights["w_lm"].to(F64).T',
-                                 'return store(x @ m.weights["w_lm"].to(F64).T, m.dtype)', 0),
-    "filling operand not rounded": ("kv_fill", 'x = store(rmsnorm(h, m.weights["layers"][i - 1]["g_attn"], m.rms_eps), dt)',
-                                    'x = rmsnorm(h, m.weights["layers"][i - 1]["g_attn"], m.rms_eps)', 0),
-    "filled K rounded before the rotation": ("kv_fill", 'k = rope((x @ _w(m, i, "w_k").T).reshape(B, H, dh), pos, m.rope_theta)',
-                                             'k = rope(store(x @ _w(m, i, "w_k").T, dt).reshape(B, H, dh), pos, m.rope_theta)', 0),
-}
-
-
-def make_mutant(fn_name, old, new, which):
-    """The oracle function `fn_name` with one piece of its source text replaced, compiled in a copy of the
-    oracle's namespace."""
-    src = inspect.getsource(getattr(O, fn_name))
-    assert src.count(old) > which, f"the oracle's source no longer contains {old!r}"
-    parts = src.split(old)
-    src = old.join(parts[:which + 1]) + new + old.join(parts[which + 1:])
-    ns = dict(vars(O))
-    exec(compile(src, f"<mutant of {fn_name}>", "exec"), ns)
-    return ns[fn_name]
-
-
 @pytest.mark.parametrize("name", sorted(MUTANTS))
-def test_p9m_planted_rounding_mistakes_fail_the_pin(monkeypatch, name):
-    fn_name, old, new, which = MUTANTS[name]
-    monkeypatch.setattr(O, fn_name, make_mutant(fn_name, old, new, which))
-    with pytest.raises(AssertionError):
-        check_contract()
+def test_p9m_planted_rounding_mistakes_fail_the_pin(name):
+    with planted(name):
+        with pytest.raises(AssertionError):
+            check_contract()
+    check_contract()          # and the oracle is itself again afterwards
