@@ -83,26 +83,32 @@ struct Workspace {
   float* q;           // [B][d]
   float2* rope;       // [B][head_dim/2] (cos, sin) of this iteration's rotary angles
   float4* partials;   // bf16: [Mpad][vocab/32]; fp32: [B]
+  float* h;           // residual stream: bf16 [Mpad][d], fp32 [B][d]
   // bf16 path
-  float* hT;          // [d][Mpad]
+  float* y;           // [slices][Mpad][d] partial results of the output / down projection
   bf16_t* xH;         // [Mpad][d] exit-head operand, directly followed by
-  bf16_t* xT;         // [Mpad][d] layer operand (the pair is written by one launch after a layer with a head)
+  bf16_t* xT;         // [Mpad][d] layer operand
   bf16_t* aoT;        // [Mpad][d]
   bf16_t* actT;       // [Mpad][f]
   float* rowsq;       // [2n + 2][Mpad]: sum of squares of the residual rows after the embedding / each update
-  int32_t* tile_cnt;  // [(d/32) * Mpad/32] arrival counters of the accumulate epilogue (directly behind rowsq)
-  size_t zero_count;  // floats from rowsq on that must be zero when an iteration starts
   bf16_t* fill_x;     // [n][Mpad][d]
-  float* split_scratch;     // [d/32][1024] meeting place of the QKV tiles that two workgroups share (zeroed with rowsq)
+  float* split_scratch;     // [d/32][1024] meeting place of the QKV tiles that two workgroups share
   int32_t* split_counters;  // [d/32]
-  float* dots;        // [n][Mpad] per-layer row dot products of the head-less confidence measures (zeroed with rowsq)
-  float* hprev;       // bf16: [d][Mpad], fp32: [B][d]: hidden state before the current layer (similarity measure)
+  size_t zero_count;  // floats from split_scratch on that must be zero when an iteration starts
+  float* dots;        // [n][Mpad] per-layer row dot products of the head-less confidence measures
+  float* hprev;       // bf16: [Mpad][d], fp32: [B][d]: hidden state before the current layer (similarity measure)
   float* msr;         // fp32: [3][B] sums of the head-less confidence measures
   RowMap rowmap;      // bf16: [Mpad] + [Mpad] + [1] row map of the sequences still active (per-sequence exit)
   // fp32 path
-  float *h, *x, *ao, *act, *logits;
+  float *x, *ao, *act, *logits;
   size_t bytes;
 };
+
+// Contraction slices of the two accumulate projections of a layer (what the launches will write).
+int acc_slices_max(const ee_model_desc& D, int B) {
+  const int a = gemm_acc_slices(B, D.d_model / 32, D.d_model), b = gemm_acc_slices(B, D.d_model / 32, D.d_ffn);
+  return a > b ? a : b;
+}
 
 Workspace carve(const ee_model_desc& D, int B, void* base) {
   Workspace w{};
@@ -119,17 +125,17 @@ Workspace carve(const ee_model_desc& D, int B, void* base) {
   w.rope = c.take<float2>((size_t)Bp * (D.head_dim / 2));
   if (D.dtype == EE_BF16) {
     w.partials = c.take<float4>((size_t)Mpad * (V / 32));
-    w.hT = c.take<float>(d * Mpad);
+    w.h = c.take<float>(d * Mpad);
+    w.y = c.take<float>((size_t)acc_slices_max(D, Bp) * d * Mpad);
     w.xH = c.take<bf16_t>(2 * d * Mpad);
     w.xT = w.xH ? w.xH + d * Mpad : nullptr;
     w.aoT = c.take<bf16_t>(d * Mpad);
     w.actT = c.take<bf16_t>(f * Mpad);
-    const size_t split_words = Mpad == 32 ? (d / 32) * 1025 : 0;   // only batches of one tile split QKV tiles
-    w.zero_count = (2 * n + 2) * Mpad + (d / 32) * (Mpad / 32) + n * Mpad + split_words;
-    w.rowsq = c.take<float>(w.zero_count);
-    w.tile_cnt = reinterpret_cast<int32_t*>(w.rowsq ? w.rowsq + (2 * n + 2) * Mpad : nullptr);
-    w.dots = w.rowsq ? w.rowsq + (2 * n + 2) * Mpad + (d / 32) * (Mpad / 32) : nullptr;
-    w.split_scratch = (w.rowsq && split_words) ? w.dots + n * Mpad : nullptr;
+    w.rowsq = c.take<float>((2 * n + 2) * Mpad);
+    w.dots = c.take<float>(n * Mpad);
+    w.zero_count = Mpad == 32 ? (d / 32) * 1025 : 0;   // only batches of one tile split QKV tiles
+    w.split_scratch = c.take<float>(w.zero_count);
+    if (!w.zero_count) w.split_scratch = nullptr;
     w.split_counters = reinterpret_cast<int32_t*>(w.split_scratch ? w.split_scratch + (d / 32) * 1024 : nullptr);
     w.fill_x = c.take<bf16_t>(n * Mpad * d);
     w.hprev = c.take<float>(d * Mpad);
@@ -165,10 +171,7 @@ Workspace carve_exit_check(const ee_model_desc& D, int B, void* base) {
   w.scratch_L = c.take<int32_t>(1);
   if (D.dtype == EE_BF16) {
     w.partials = c.take<float4>((size_t)Mpad * (V / 32));
-    w.hT = c.take<float>(d * Mpad);
     w.xH = c.take<bf16_t>(d * Mpad);
-    w.zero_count = Mpad;
-    w.rowsq = c.take<float>(w.zero_count);
   } else {
     w.partials = c.take<float4>(Bp);
     w.x = c.take<float>(Bp * d);
@@ -195,6 +198,7 @@ int check_desc(const ee_model_desc* D) {
   if (D->dtype == EE_BF16) {
     if (D->d_model % 64 || D->d_ffn % 16 || D->vocab % 32)
       EE_FAIL(EE_ERR_UNSUPPORTED, "bf16 path needs d_model %% 64 == 0, d_ffn %% 16 == 0, vocab %% 32 == 0");
+    if (D->d_model > 8192) EE_FAIL(EE_ERR_UNSUPPORTED, "bf16 path: d_model %d exceeds 8192", D->d_model);
   }
   return EE_OK;
 }
@@ -250,15 +254,6 @@ bool bf16_compactable(const ee_model_desc& D, int B) {
          gemm_bf16_is_tiled(B, D.vocab / 32);
 }
 
-// Workgroups along the contraction for the accumulate epilogue: enough to cover the chip twice, no more (each
-// extra slice costs one more round of float atomics per output and shortens every wavefront's stream).
-int acc_ksplit(int n_tiles, int K) {
-  const int k_steps = K / 16;
-  int s = (512 + n_tiles - 1) / n_tiles;
-  if (s > k_steps / 64) s = k_steps / 64;
-  return s < 1 ? 1 : s;
-}
-
 size_t pool_layer_elems(const ee_model_desc& D, const ee_kv_cache& C) {
   return (size_t)C.num_blocks * D.n_heads * 16 * D.head_dim;
 }
@@ -291,19 +286,27 @@ QkvEpi make_qkv_epi(const ee_model_desc& D, const ee_kv_cache& C, const ee_batch
 }
 
 // --- exit head: statistics of (scale * logits) for every row of the hidden state ------------------------
-// prepped: the normalised operand is already in w.xH (written together with the next layer's operand).
-void enqueue_head_bf16(const ee_model& M, const Workspace& w, int B, int Mpad, float scale, const float* rowsq_slot,
-                       int layer, bool prepped, const RowMap& rm, Pred pred, hipStream_t st) {
+// The normalised operand is already in w.xH (written by the normalisation launch before).
+void enqueue_head_bf16(const ee_model& M, const Workspace& w, int B, float scale, int layer, const RowMap& rm, Pred pred,
+                       hipStream_t st) {
   const ee_model_desc& D = M.desc;
-  if (!prepped) {
-    ProfScope ps(EE_K_NORM, layer, st);
-    launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(M.g_final), w.xH, rowsq_slot, D.rms_eps, Mpad, D.d_model, pred, st);
-  }
   GemmShape g{M.w_lm, w.xH, D.d_model, B, 0, D.vocab / 32, 16, 1};
-  g.n_rows_dev = rm.n_active;   // compacted operand (prepped by the caller through the same map)
+  g.n_rows_dev = rm.n_active;   // compacted operand (prepared by the caller through the same map)
   LmEpi e{w.partials, nullptr, D.vocab / 32, D.vocab, scale, nullptr, D.rms_eps, D.d_model, rm.perm};
   ProfScope ps(EE_K_HEAD, layer, st);
   launch_gemm_lm_bf16(g, e, pred, st);
+}
+// RMSNorm of hidden rows h [B][d] (nothing added) with one gain into x.
+NormArgs plain_norm(const ee_model_desc& D, const float* h, const void* gain, bf16_t* x, int B) {
+  NormArgs a{};
+  a.h_in = h;
+  a.gain[0] = reinterpret_cast<const bf16_t*>(gain);
+  a.x[0] = x;
+  a.eps = D.rms_eps;
+  a.B = B;
+  a.Mpad = round_up(B, 32);
+  a.d = D.d_model;
+  return a;
 }
 void enqueue_head_f32(const ee_model& M, const Workspace& w, const float* h, int B, float scale, int layer, Pred pred,
                       hipStream_t st) {
@@ -317,12 +320,9 @@ void enqueue_head_f32(const ee_model& M, const Workspace& w, const float* h, int
 }
 
 // --- KV filling for layers above fill_from ----------------------------------------------------------------
-// rowsq_layer_stride == 0: rowsq_slot is zeroed scratch and receives the row sums of squares of the hidden state
-// (stand-alone call).  > 0: rowsq_slot is slot 0 of the iteration's table and the sums of the exit hidden state are
-// already in slot 2 * batch_exit_layer, left there by that layer's down projection.
-void enqueue_fill_bf16(const ee_model& M, const ee_kv_cache& C, const ee_batch& Bt, const Workspace& w, int Mpad,
-                       const int32_t* fill_from, int stride, float* rowsq_slot, size_t rowsq_layer_stride,
-                       const int32_t* slot_ptr, Pred pred, hipStream_t st) {
+// h: hidden rows [B][d] (inside an iteration: the residual stream, final at the batch exit layer).
+void enqueue_fill_bf16(const ee_model& M, const ee_kv_cache& C, const ee_batch& Bt, const Workspace& w, const float* h,
+                       int Mpad, const int32_t* fill_from, int stride, Pred pred, hipStream_t st) {
   const ee_model_desc& D = M.desc;
   GainTable gt{};
   FillLayers fl{};
@@ -331,9 +331,7 @@ void enqueue_fill_bf16(const ee_model& M, const ee_kv_cache& C, const ee_batch& 
     fl.w_qkv[i] = M.layers[i].w_qkv;
   }
   ProfScope ps(EE_K_KVFILL, 0, st);
-  if (rowsq_layer_stride == 0) launch_rowsq(w.hT, rowsq_slot, Mpad, D.d_model, pred, st);
-  launch_prep_x_layers(w.hT, gt, D.n_layers, w.fill_x, rowsq_slot, rowsq_layer_stride, slot_ptr, D.rms_eps, fill_from,
-                       stride, Bt.batch, Mpad, D.d_model, pred, st);
+  launch_fill_prep(h, gt, D.n_layers, w.fill_x, D.rms_eps, fill_from, stride, Bt.batch, Mpad, D.d_model, pred, st);
   GemmShape g{nullptr, nullptr, D.d_model, Bt.batch, D.d_model / 32, 2 * D.d_model / 32, D.head_dim / 2, 1};
   QkvEpi e = make_qkv_epi(D, C, Bt, w, 1, nullptr);
   e.fill_from = fill_from;
@@ -379,15 +377,11 @@ int enqueue_exit_check(const ee_model& M, int32_t layer, const float* hidden, in
                        int32_t* done_flag, int32_t* batch_exit_layer, int32_t* argmax, float* conf, const Workspace& w,
                        hipStream_t st) {
   const ee_model_desc& D = M.desc;
-  const int Mpad = round_up(batch, 32);
   const Pred always{nullptr, 0};
   const float scale = D.logit_scale * (float)layer;
   if (D.dtype == EE_BF16) {
-    launch_iter_init(IterState{w.status, w.scratch_exit_layer, w.n_exited, w.done, w.scratch_L}, 0, D.n_layers, nullptr,
-                     w.rowsq, (size_t)Mpad, st);
-    launch_hidden_to_ht(hidden, w.hT, batch, Mpad, D.d_model, st);
-    launch_rowsq(w.hT, w.rowsq, Mpad, D.d_model, always, st);
-    enqueue_head_bf16(M, w, batch, Mpad, scale, w.rowsq, layer, false, RowMap{}, always, st);
+    launch_finish_norm(plain_norm(D, hidden, M.g_final, w.xH, batch), always, st);
+    enqueue_head_bf16(M, w, batch, scale, layer, RowMap{}, always, st);
   } else {
     enqueue_head_f32(M, w, hidden, batch, scale, layer, always, st);
   }
@@ -546,17 +540,35 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   auto rs = [&](int slot) { return w.rowsq + (size_t)slot * Mpad; };
   {
     ProfScope ps(EE_K_OTHER, 0, st);
-    launch_iter_init(s, B, n, out_conf, bf ? w.rowsq : nullptr, bf ? w.zero_count : 0, st);
+    launch_iter_init(s, B, n, out_conf, bf ? w.split_scratch : nullptr, bf ? w.zero_count : 0, st);
     launch_rope_table(batch->context_lens, w.rope, B, D.head_dim, D.rope_theta, st);
     if (bf) {
-      launch_embed_bf16(reinterpret_cast<const bf16_t*>(model->embed), batch->tokens, w.hT, B, Mpad, d, D.vocab, st);
-      launch_rowsq(w.hT, rs(0), Mpad, d, always, st);
-      if (compact) launch_compact(w.status, B, rmap, nullptr, 0, Mpad, always, st);   // nobody has left: identity
+      launch_embed_bf16(reinterpret_cast<const bf16_t*>(model->embed), batch->tokens, w.h, B, Mpad, d, D.vocab, st);
+      if (compact) launch_compact(w.status, B, rmap, always, st);   // nobody has left: identity
     } else {
       launch_embed_f32(reinterpret_cast<const float*>(model->embed), batch->tokens, w.h, B, d, D.vocab, st);
       if (simmode) launch_copy_f32(w.h, w.hprev, (size_t)B * d, st);   // h_0, the "previous" state of layer 1
     }
   }
+  // bf16 path: the residual update of a projection and the RMSNorm that follows it are one launch (NormArgs):
+  // it adds the projection's partial results (n_slices of them) to the residual rows, leaves the rows' sums of
+  // squares in rowsq slot `slot` and writes the operand(s) of what comes next.
+  auto norm_args = [&](int n_slices, int slot) {
+    NormArgs a{};
+    a.h_in = w.h;
+    a.h_out = n_slices ? w.h : nullptr;
+    a.y = w.y;
+    a.S = n_slices;
+    a.skip = compact ? nullptr : left;   // with a row map, a sequence that has left has no position in it
+    a.rm = rmap;
+    a.rowsq_out = rs(slot);
+    a.eps = D.rms_eps;
+    a.B = B;
+    a.Mpad = Mpad;
+    a.d = d;
+    return a;
+  };
+  const int slices_o = bf ? gemm_acc_slices(B, d / 32, d) : 0, slices_down = bf ? gemm_acc_slices(B, d / 32, f) : 0;
 
   // The exit decision of layer i (softmax-response measures, bf16, batches the streaming projection kernel serves)
   // rides along with the QKV projection launch of layer i + 1: one launch less per checked layer.
@@ -574,13 +586,13 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
                 batch->row_table, rmap.cpos, cache->num_blocks};
     const bool head_here = use_exit_heads && has_head(D, i);
     if (bf) {
-      if (i == 1) {
+      if (i == 1) {   // operand of the first layer from the embedding (also h_0, the "previous" hidden state of layer 1)
         ProfScope ps(EE_K_NORM, i, st);
-        if (simmode)   // also keeps h_0 as the "previous" hidden state of layer 1
-          launch_prep_x_dot(w.hT, reinterpret_cast<const bf16_t*>(L.g_attn), w.xT, rs(0), nullptr, 0, D.rms_eps, Mpad, d,
-                            RowDot{nullptr, w.hprev, nullptr, 0}, run_layers, st);
-        else
-          launch_prep_x(w.hT, reinterpret_cast<const bf16_t*>(L.g_attn), w.xT, rs(0), D.rms_eps, Mpad, d, run_layers, st);
+        NormArgs na = norm_args(0, 0);
+        na.gain[0] = reinterpret_cast<const bf16_t*>(L.g_attn);
+        na.x[0] = w.xT;
+        if (simmode) na.rd = RowDot{nullptr, w.hprev, nullptr, 1};
+        launch_finish_norm(na, run_layers, st);
       }
       {
         ProfScope ps(EE_K_QKV, i, st);
@@ -602,19 +614,18 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
         if ((rc = launch_attention(at, D.dtype, run_layers, st))) return rc;
       }
       {
-        ProfScope ps(EE_K_OPROJ, i, st);   // also leaves the row sums of squares the FFN norm needs
-        GemmShape go{L.w_o, w.aoT, d, B, 0, d / 32, 16, acc_ksplit(d / 32, d)};
+        ProfScope ps(EE_K_OPROJ, i, st);
+        GemmShape go{L.w_o, w.aoT, d, B, 0, d / 32, 16, 1};
         go.n_rows_dev = rmap.n_active;
-        launch_gemm_acc_bf16(go, AccEpi{w.hT, Mpad, d, rs(2 * i - 1), w.tile_cnt, compact ? nullptr : left, rmap.perm},
-                             run_layers, st);
+        launch_gemm_acc_bf16(go, AccEpi{w.y, Mpad, d, nullptr}, run_layers, st);
       }
-      {
+      {   // h += attention update; operand of the FFN (compacted with a row map)
         ProfScope ps(EE_K_NORM, i, st);
-        const bf16_t* g_ffn = reinterpret_cast<const bf16_t*>(L.g_ffn);
-        if (compact)
-          launch_prep_x_compact(w.hT, g_ffn, nullptr, w.xT, rs(2 * i - 1), rmap, D.rms_eps, Mpad, d, run_layers, st);
-        else
-          launch_prep_x(w.hT, g_ffn, w.xT, rs(2 * i - 1), D.rms_eps, Mpad, d, run_layers, st);
+        NormArgs na = norm_args(slices_o, 2 * i - 1);
+        na.gain[0] = reinterpret_cast<const bf16_t*>(L.g_ffn);
+        na.x[0] = w.xT;
+        na.compacted[0] = compact;
+        launch_finish_norm(na, run_layers, st);
       }
       {
         ProfScope ps(EE_K_GATEUP, i, st);
@@ -623,33 +634,36 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
         launch_gemm_gateup_bf16(gg, GateUpEpi{w.actT, f, nullptr, D.rms_eps, d}, run_layers, st);
       }
       {
-        ProfScope ps(EE_K_DOWN, i, st);    // row sums for the exit head and for the next layer's attention norm
-        GemmShape gd{L.w_down, w.actT, f, B, 0, d / 32, 16, acc_ksplit(d / 32, f)};
+        ProfScope ps(EE_K_DOWN, i, st);
+        GemmShape gd{L.w_down, w.actT, f, B, 0, d / 32, 16, 1};
         gd.n_rows_dev = rmap.n_active;
-        launch_gemm_acc_bf16(gd, AccEpi{w.hT, Mpad, d, rs(2 * i), w.tile_cnt, compact ? nullptr : left, rmap.perm},
-                             run_layers, st);
+        launch_gemm_acc_bf16(gd, AccEpi{w.y, Mpad, d, nullptr}, run_layers, st);
       }
-      if (i < n) {   // operand of the next layer's attention (and of this layer's exit head, in the same launch)
+      {
+        // h += FFN update; then the operand of the next layer's attention, and of this layer's exit head (compacted
+        // with a row map) in the same launch; after the last layer: the operand of the final LM-head pass.  The
+        // head-less confidence measures take their dot product here as well (with h_{i-1} or the classifier's row).
         ProfScope ps(EE_K_NORM, i, st);
-        const bf16_t* g_next = reinterpret_cast<const bf16_t*>(model->layers[i].g_attn);
-        if (head_here && !dotmode) {
-          const bf16_t* g_head = reinterpret_cast<const bf16_t*>(model->g_final);
-          if (compact)   // the head's operand compacted, the next layer's in place
-            launch_prep_x_compact(w.hT, g_head, g_next, w.xH, rs(2 * i), rmap, D.rms_eps, Mpad, d, run_layers, st);
-          else
-            launch_prep_x_pair(w.hT, g_head, g_next, w.xH, rs(2 * i), D.rms_eps, Mpad, d, run_layers, st);
-        } else if (simmode) {
-          // h_{i-1} . h_i where a check follows; the snapshot moves on after every layer
-          float* dots = head_here ? w.dots + (size_t)(i - 1) * Mpad : nullptr;
-          launch_prep_x_dot(w.hT, g_next, w.xT, rs(2 * i), nullptr, 0, D.rms_eps, Mpad, d,
-                            RowDot{dots ? w.hprev : nullptr, w.hprev, dots, 1}, run_layers, st);
-        } else if (head_here && dotmode) {
-          launch_prep_x_dot(w.hT, g_next, w.xT, rs(2 * i), nullptr, 0, D.rms_eps, Mpad, d,
-                            RowDot{model->w_cls + (size_t)(i - 1) * d, nullptr, w.dots + (size_t)(i - 1) * Mpad, 0},
-                            run_layers, st);
+        NormArgs na = norm_args(slices_down, 2 * i);
+        if (i < n) {
+          na.gain[0] = reinterpret_cast<const bf16_t*>(model->layers[i].g_attn);
+          na.x[0] = w.xT;
+          if (head_here && !dotmode) {
+            na.gain[1] = reinterpret_cast<const bf16_t*>(model->g_final);
+            na.x[1] = w.xH;
+            na.compacted[1] = compact;
+          }
+          if (simmode) {   // h_{i-1} . h_i where a check follows; the snapshot moves on after every layer
+            float* dots = head_here ? w.dots + (size_t)(i - 1) * Mpad : nullptr;
+            na.rd = RowDot{dots ? w.hprev : nullptr, w.hprev, dots, 1};
+          } else if (head_here && dotmode) {
+            na.rd = RowDot{model->w_cls + (size_t)(i - 1) * d, nullptr, w.dots + (size_t)(i - 1) * Mpad, 0};
+          }
         } else {
-          launch_prep_x(w.hT, g_next, w.xT, rs(2 * i), D.rms_eps, Mpad, d, run_layers, st);
+          na.gain[0] = reinterpret_cast<const bf16_t*>(model->g_final);
+          na.x[0] = w.xH;
         }
+        launch_finish_norm(na, run_layers, st);
       }
     } else {
       {
@@ -668,7 +682,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       {
         ProfScope ps(EE_K_OPROJ, i, st);
         SimpleShape go{reinterpret_cast<const float*>(L.w_o), w.ao, d, B, 0, d, 1};
-        launch_simple_acc(go, AccEpi{w.h, 0, d, nullptr, nullptr, left}, run_layers, st);
+        launch_simple_acc(go, AccEpi{w.h, 0, d, left}, run_layers, st);
       }
       {
         ProfScope ps(EE_K_GATEUP, i, st);
@@ -679,7 +693,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       {
         ProfScope ps(EE_K_DOWN, i, st);
         SimpleShape gd{reinterpret_cast<const float*>(L.w_down), w.act, f, B, 0, d, 1};
-        launch_simple_acc(gd, AccEpi{w.h, 0, d, nullptr, nullptr, left}, run_layers, st);
+        launch_simple_acc(gd, AccEpi{w.h, 0, d, left}, run_layers, st);
       }
     }
     if (!bf && simmode && !head_here && i < n) launch_copy_f32(w.h, w.hprev, (size_t)B * d, st);
@@ -714,11 +728,11 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
         ProfScope ps(EE_K_COMBINE, i, st);
         launch_decide(da, run_layers, st);
       }
-      if (compact) launch_compact(w.status, B, rmap, w.rowsq, 2 * i, Mpad, run_layers, st);
+      if (compact) launch_compact(w.status, B, rmap, run_layers, st);
     } else if (head_here) {
       const float scale = D.logit_scale * (float)i;
       if (bf)
-        enqueue_head_bf16(*model, w, B, Mpad, scale, rs(2 * i), i, true, rmap, run_layers, st);
+        enqueue_head_bf16(*model, w, B, scale, i, rmap, run_layers, st);
       else
         enqueue_head_f32(*model, w, w.h, B, scale, i, run_layers, st);
       CombineArgs ca{w.partials, bf ? D.vocab / 32 : 1, B, i, scale, thresholds[i - 1], D.conf_mode, forced_exit_layer, s,
@@ -730,10 +744,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
         ProfScope ps(EE_K_COMBINE, i, st);
         launch_combine(ca, run_layers, st);
       }
-      if (compact) launch_compact(w.status, B, rmap, w.rowsq, 2 * i, Mpad, run_layers, st);
-    } else if (compact && i < n) {
-      // no check after this layer: the map stands, the sums of the rows that left still move on
-      launch_compact(w.status, B, rmap, w.rowsq, 2 * i, Mpad, run_layers, st);
+      if (compact) launch_compact(w.status, B, rmap, run_layers, st);
     }
   }
 
@@ -742,25 +753,24 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   // layers' own QKV projections (see above); every column of the residual stream is that sequence's exit state.
   if (use_exit_heads) {
     if (bf)
-      enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, out_batch_exit_layer, 0, rs(0), (size_t)2 * Mpad,
-                        out_batch_exit_layer, run_fill, st);
+      enqueue_fill_bf16(*model, *cache, *batch, w, w.h, Mpad, out_batch_exit_layer, 0, run_fill, st);
     else
       enqueue_fill_f32(*model, *cache, *batch, w, w.h, out_batch_exit_layer, 0, run_fill, st);
   }
 
   // With a head-less confidence measure no exit head has produced a token: the LM head then always runs, on the
-  // hidden state at output_layer (still in place: later layers were skipped), normalised with that layer's sums.
+  // hidden state at output_layer (still in place: later layers were skipped).  Otherwise it runs only when the loop
+  // reached the last layer, whose normalisation launch has left the head's operand in place.
   {
     const Pred final_pred = dotmode ? always : run_layers;
     if (bf && dotmode) {
       {
         ProfScope ps(EE_K_NORM, n, st);
-        launch_prep_x_dot(w.hT, reinterpret_cast<const bf16_t*>(model->g_final), w.xH, rs(0), out_batch_exit_layer,
-                          (size_t)2 * Mpad, D.rms_eps, Mpad, d, RowDot{}, always, st);
+        launch_finish_norm(plain_norm(D, w.h, model->g_final, w.xH, B), always, st);
       }
-      enqueue_head_bf16(*model, w, B, Mpad, 0.0f, nullptr, n, true, RowMap{}, always, st);
+      enqueue_head_bf16(*model, w, B, 0.0f, n, RowMap{}, always, st);
     } else if (bf) {
-      enqueue_head_bf16(*model, w, B, Mpad, 0.0f, rs(2 * n), n, false, RowMap{}, run_layers, st);
+      enqueue_head_bf16(*model, w, B, 0.0f, n, RowMap{}, run_layers, st);
     } else {
       enqueue_head_f32(*model, w, w.h, B, 0.0f, n, final_pred, st);
     }
@@ -768,12 +778,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     ProfScope ps(EE_K_COMBINE, n, st);
     launch_combine(ca, final_pred, st);
   }
-  if (out_hidden) {
-    if (bf)
-      launch_ht_to_hidden(w.hT, out_hidden, B, Mpad, d, st);
-    else
-      launch_copy_f32(w.h, out_hidden, (size_t)B * d, st);
-  }
+  if (out_hidden) launch_copy_f32(w.h, out_hidden, (size_t)B * d, st);
   (void)always;
   EE_HIP(hipGetLastError());
   return EE_OK;
@@ -835,14 +840,10 @@ int ee_kv_fill(const ee_model* model, const ee_kv_cache* cache, const ee_batch* 
   const int Mpad = round_up(B, 32);
   const Pred always{nullptr, 0};
   launch_rope_table(batch->context_lens, w.rope, B, D.head_dim, D.rope_theta, st);
-  if (D.dtype == EE_BF16) {
-    launch_iter_init(IterState{w.status, w.scratch_exit_layer, w.n_exited, w.done, w.scratch_L}, 0, D.n_layers, nullptr,
-                     w.rowsq, (size_t)Mpad, st);
-    launch_hidden_to_ht(hidden, w.hT, B, Mpad, D.d_model, st);
-    enqueue_fill_bf16(*model, *cache, *batch, w, Mpad, fill_from_layer, 1, w.rowsq, 0, nullptr, always, st);
-  } else {
+  if (D.dtype == EE_BF16)
+    enqueue_fill_bf16(*model, *cache, *batch, w, hidden, Mpad, fill_from_layer, 1, always, st);
+  else
     enqueue_fill_f32(*model, *cache, *batch, w, hidden, fill_from_layer, 1, always, st);
-  }
   EE_HIP(hipGetLastError());
   return EE_OK;
 }

@@ -33,14 +33,15 @@ void set_error(const char* fmt, ...);
 // XT ("operand tiles"): a [rows m][cols k] bf16 activation matrix stored in the order in which the
 //   32x32x16 MFMA wants its second operand: [m/32][k/16][lane][8] with lane = (m%32) + 32*((k%16)/8) and
 //   element k%8, so a wavefront fetches one 32x16 operand tile as 1 KiB of consecutive bytes.
-// HT ("transposed residual"): the fp32 residual stream stored [k][Mpad] (channel-major) so that the
-//   atomic accumulation from an MFMA result tile (lanes = consecutive m) touches consecutive words.
+// The fp32 residual stream is plain row-major [Mpad][d].  The output and down projections do not add into it:
+//   each contraction slice writes its partial result to a slice of its own ([slices][Mpad][d], plain stores), and
+//   the normalisation kernel that follows sums the slices in slice order, adds them to the residual row and
+//   normalises it.  No float atomics anywhere, so the bf16 path is reproducible bit for bit.
 // ---------------------------------------------------------------------------------------------------
 __host__ __device__ inline size_t xt_index(int m, int k, int K) {
   return ((size_t)(m >> 5) * (size_t)(K >> 4) + (size_t)(k >> 4)) * 512 + (size_t)((((k >> 3) & 1) << 5) + (m & 31)) * 8 +
          (size_t)(k & 7);
 }
-__host__ __device__ inline size_t ht_index(int m, int k, int Mpad) { return (size_t)k * Mpad + m; }
 __host__ __device__ inline int round_up(int x, int to) { return (x + to - 1) / to * to; }
 
 // Packed weight row order: packed tile `nt`, row r (0..31) holds plain output row
@@ -90,14 +91,13 @@ struct QkvEpi {                 // rotary embedding + paged cache write (+ q out
   int num_blocks;               // blocks per layer of the pools: a slot whose block id or position is out of range is not written
   int table_rows;               // rows of block_tables (the batch size): a row_table entry outside 0..table_rows-1 is read as 0
 };
-struct AccEpi {                 // h += value
-  float* h;
-  int Mpad;                     // HT pitch (bf16 path) or 0: plain [M][n_out]
+struct AccEpi {                 // residual update
+  float* h;                     // fp32 path: the residual stream [M][n_out], added to in place (one contributor per element).
+                                // bf16 path: partial results [slices][Mpad][n_out]; slice s receives the sum over the
+                                // s-th part of the contraction (operand row m -> row m: compacted operands stay compacted)
+  int Mpad;                     // row count of a slice (bf16 path) or 0 (fp32 path)
   int n_out;
-  float* rowsq;                 // bf16 path: nullptr, or [Mpad] zeroed: receives sum_k h[m][k]^2 of the finished rows
-  int32_t* tile_counters;       // bf16 path with rowsq: [n_tiles * m_tiles] zeroed arrival counters (left at zero)
-  const int32_t* skip;          // nullptr, or [M]: rows with skip[m] != 0 keep their hidden state (sequences that have left)
-  const int32_t* perm;          // nullptr, or [M]: operand row m is batch row perm[m] (compacted operand, tiled kernel only)
+  const int32_t* skip;          // fp32 path: nullptr, or [M]: rows with skip[m] != 0 keep their hidden state
 };
 struct GateUpEpi {              // act = silu(gate) * up
   void* act;                    // XT bf16 [Mpad][f] (bf16 path) or plain float [M][f]
@@ -119,9 +119,8 @@ struct LmEpi {                  // per-tile softmax statistics of the scaled log
 };
 
 // ---------------------------------------------------------------------------------------------------
-// Launchers (each enqueues on `st`; `done` may be nullptr; when *done == want_done_zero ? ... see below)
-// `skip_if_done`: pointer to the done flag; kernels return at once when *skip_if_done != 0.
-// `run_if_done`:  kernels return at once when *run_if_done == 0 (KV filling).
+// Launchers (each enqueues on `st`).  A launch carries a predicate on a device word: its kernels return at once
+// unless (*flag != 0) == run_when.  The layer loop runs while the all-exited flag is 0, KV filling once it is 1.
 // ---------------------------------------------------------------------------------------------------
 struct Pred {
   const int32_t* flag;  // nullptr = always run
@@ -131,50 +130,48 @@ struct Pred {
 // misc.hip
 void launch_iter_init(const IterState& s, int B, int n_layers, float* conf_out, float* zero_buf, size_t zero_count,
                       hipStream_t st);
-void launch_embed_bf16(const bf16_t* E, const int32_t* tokens, float* hT, int B, int Mpad, int d, int vocab, hipStream_t st);
+void launch_embed_bf16(const bf16_t* E, const int32_t* tokens, float* h, int B, int Mpad, int d, int vocab, hipStream_t st);
 void launch_embed_f32(const float* E, const int32_t* tokens, float* h, int B, int d, int vocab, hipStream_t st);
-void launch_hidden_to_ht(const float* plain, float* hT, int B, int Mpad, int d, hipStream_t st);
-void launch_ht_to_hidden(const float* hT, float* plain, int B, int Mpad, int d, hipStream_t st);
 void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t st);
 void launch_rope_table(const int32_t* context_lens, float2* table, int B, int head_dim, float theta, hipStream_t st);
-// RMSNorm of the bf16 path: rowsq[m] += sum_k h^2, then x = bf16(h * rsqrt(rowsq/d + eps) * g) in XT order.
-// launch_prep_x_layers writes one slab per layer with that layer's gain (KV filling).
 struct GainTable {
   const void* g[EE_MAX_LAYERS];
 };
-void launch_rowsq(const float* hT, float* rowsq, int Mpad, int d, Pred pred, hipStream_t st);
-void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, float eps, int Mpad, int d,
-                   Pred pred, hipStream_t st);
-// Two normalisations of the same rows in one launch: slab 0 of xT_pair with gain_a, slab 1 (Mpad * d elements on) with gain_b.
-void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT_pair, const float* rowsq,
-                        float eps, int Mpad, int d, Pred pred, hipStream_t st);
-// Compacted operands: one slab (gain_b == nullptr) or the pair above, where slab 0 is gathered through the row map
-// (position p holds RMSNorm of batch row perm[p], zeros from *n_active on) and slab 1 stays in place, every row.
-void launch_prep_x_compact(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT, const float* rowsq,
-                           const RowMap& rm, float eps, int Mpad, int d, Pred pred, hipStream_t st);
-// Rebuilds the row map from the status words (active rows keep their order).  carry_to, if set, is the table of
-// row sums of squares ([slots][Mpad]): a row that has left gets the sums of slot `slot` copied into the next two
-// slots, which the compacted projections of the next layer leave untouched for it.
-void launch_compact(const int32_t* status, int B, const RowMap& rm, float* rowsq_table, int slot, int Mpad, Pred pred,
-                    hipStream_t st);
-// rowsq_layer_stride > 0: the sums are at rowsq + slot_ptr[0] * rowsq_layer_stride.
-void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
-                          size_t rowsq_layer_stride, const int32_t* slot_ptr, float eps, const int32_t* fill_from,
-                          int fill_from_stride, int B, int Mpad, int d, Pred pred, hipStream_t st);
-// Optional second job of an operand preparation (confidence measures that need no LM head, Section 2.1):
-// dots[m] += sum_k h[m][k] * other, where other is the previous hidden state (per_row: HT layout, the
-// similarity measure) or one weight row shared by all rows ([d], the dedicated classifier); snapshot, if set,
-// receives h in HT layout (it may be the buffer `other` points to: every element is read before it is written).
+// Optional second job of a normalisation launch (confidence measures that need no LM head, Section 2.1):
+// dots[m] = sum_k h[m][k] * other, where other is the previous hidden state (per_row: [Mpad][d], the similarity
+// measure) or one weight row shared by all rows ([d], the dedicated classifier); snapshot, if set, receives h
+// (it may be the buffer `other` points to: every element is read before it is written, by the same thread).
 struct RowDot {
   const float* other;
   float* snapshot;
-  float* dots;      // [Mpad], zero before the launch
+  float* dots;      // [Mpad]
   int per_row;
 };
-// Like launch_prep_x, with the second job above, and with the row sums taken from slot *slot_ptr of a table
-// (rowsq + *slot_ptr * slot_stride) when slot_ptr is set.
-void launch_prep_x_dot(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, const int32_t* slot_ptr,
-                       size_t slot_stride, float eps, int Mpad, int d, const RowDot& rd, Pred pred, hipStream_t st);
+// Rebuilds the row map from the status words (active rows keep their order).
+void launch_compact(const int32_t* status, int B, const RowMap& rm, Pred pred, hipStream_t st);
+// Residual update + RMSNorm of the bf16 path, one workgroup per batch row:
+//   h[m] += y[0][p] + y[1][p] + .. (slice order; p = m, or cpos[m] with a row map; not for rows that have left),
+//   rowsq_out[m] = sum_k h[m][k]^2, and for each gain j: x[j] row = bf16(h * rsqrt(rowsq/d + eps) * gain[j]) in
+//   operand-tile order (at row m, or at position cpos[m] of a compacted operand, which is zero from *n_active on).
+struct NormArgs {
+  const float* h_in;      // [rows][d]
+  float* h_out;           // nullptr (nothing to add) or the same buffer
+  const float* y;         // [S][Mpad][d]
+  int S;
+  const int32_t* skip;    // nullptr, or [B] status words: rows with skip[m] != 0 have left and keep their hidden state
+  RowMap rm;              // perm == nullptr: no compaction
+  const bf16_t* gain[2];
+  bf16_t* x[2];           // nullptr = unused
+  int compacted[2];
+  float* rowsq_out;       // nullptr or [Mpad]
+  RowDot rd;
+  float eps;
+  int B, Mpad, d;
+};
+void launch_finish_norm(const NormArgs& a, Pred pred, hipStream_t st);
+// KV filling: x slab of layer l = bf16(RMSNorm(h; gains.g[l-1])) for every layer some row needs (fill_from < l).
+void launch_fill_prep(const float* h, const GainTable& gains, int n_layers, bf16_t* x_slabs, float eps,
+                      const int32_t* fill_from, int fill_from_stride, int B, int Mpad, int d, Pred pred, hipStream_t st);
 void launch_rmsnorm_f32(const float* h, const float* gain, float* x, int B, int d, float eps, Pred pred, hipStream_t st);
 // fp32 path: out[0][m] = h[m] . other, out[1][m] = |other|^2, out[2][m] = |h[m]|^2 (out is [3][B]); other is
 // the previous hidden state [B][d] (per_row) or one row [d]; with per_row, h is then copied over other.
@@ -238,7 +235,7 @@ struct GemmShape {
   int tile_begin;   // first packed 32-row tile
   int n_tiles;      // tiles to compute
   int pair_stride;  // row order of the packed matrix
-  int ksplit;       // workgroups along K (> 1 only with the accumulate epilogue)
+  int unused_;      // (kept so that aggregate initialisers stay positional)
   // QKV projection with one batch tile: the last split_tiles tiles are each computed by two workgroups (half the
   // contraction each, dispatched first) that meet in split_scratch; see gemm_mfma.hip.  0 = off.
   int split_tiles;
@@ -259,6 +256,8 @@ bool gemm_bf16_is_tiled(int M, int n_tiles);
 void launch_gemm_qkv_bf16(const GemmShape& g, const QkvEpi& e, Pred pred, hipStream_t st,
                           const CombineArgs* with_combine = nullptr, const DecideArgs* with_decide = nullptr);
 bool gemm_qkv_carries_combine(int M);
+// Contraction slices the accumulate launch of this shape writes (the launch below uses exactly this many).
+int gemm_acc_slices(int M, int n_tiles, int K);
 void launch_gemm_acc_bf16(const GemmShape& g, const AccEpi& e, Pred pred, hipStream_t st);
 void launch_gemm_gateup_bf16(const GemmShape& g, const GateUpEpi& e, Pred pred, hipStream_t st);
 void launch_gemm_lm_bf16(const GemmShape& g, const LmEpi& e, Pred pred, hipStream_t st);

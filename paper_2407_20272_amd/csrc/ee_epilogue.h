@@ -108,8 +108,7 @@ __device__ inline void epi_qkv4(const QkvEpi& e, int m, int f_lo0, float (&lo)[4
 
 __device__ inline void epi_acc(const AccEpi& e, int m, int f, float v) {
   if (e.skip && ctl_load(e.skip + m) != 0) return;
-  float* p = e.Mpad ? e.h + ht_index(m, f, e.Mpad) : e.h + (size_t)m * e.n_out + f;
-  unsafeAtomicAdd(p, v);
+  e.h[(size_t)m * e.n_out + f] += v;   // fp32 path: every element of the residual stream has one contributor per launch
 }
 
 // SwiGLU product; f_lo is the gate row f, f_hi the up row f + d_ffn.

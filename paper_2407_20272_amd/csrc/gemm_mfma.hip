@@ -98,51 +98,22 @@ __device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, con
       if (part == 0 && mm < g.M) e.partials[(size_t)mm * e.n_parts + (nt - g.tile_begin)] = stat_pack(st);
     }
   } else if constexpr (std::is_same<Epi, AccEpi>::value) {
-    float* p[4];
+    // This workgroup summed one slice of the contraction (blockIdx.y): the tile goes to that slice of the partial
+    // results with plain stores, transposed through LDS so that a batch row's 32 channels leave as whole 16-byte
+    // pieces.  The normalisation launch that follows sums the slices in slice order: no atomics, no dependence on
+    // which workgroup finishes first.  (Plain row order of the packed matrix: tile row r is channel nt*32 + r.)
 #pragma unroll
     for (int ai = 0; ai < 2; ++ai) {
-      const int f_lo = packed_row_lo(nt, r16[ai], g.pair_stride);
-      p[2 * ai] = e.h + ht_index(m, f_lo, e.Mpad);
-      p[2 * ai + 1] = e.h + ht_index(m, f_lo + g.pair_stride, e.Mpad);
+      s.zt[r16[ai]][l2 & 31] = vlo[ai];
+      s.zt[r16[ai] + 16][l2 & 31] = vhi[ai];
     }
-    if (m < g.M && !(e.skip && ctl_load(e.skip + m) != 0)) {   // a sequence that has left keeps its hidden state
-#pragma unroll
-      for (int ai = 0; ai < 2; ++ai) {
-        unsafeAtomicAdd(p[2 * ai], vlo[ai]);
-        unsafeAtomicAdd(p[2 * ai + 1], vhi[ai]);
-      }
-    }
-    if (e.rowsq) {
-      // The workgroup that adds the last contraction slice of this tile reads the finished residual values back
-      // and adds their squares to the row sums the next RMSNorm needs (no separate reduction kernel).
-      // Every access to these words is a device-scope atomic (adds above, loads below), so no cache maintenance
-      // is needed: each thread waits until its adds have been performed, then the arrival counter is bumped.
-      __builtin_amdgcn_s_waitcnt(0);
-      __syncthreads();
-      const int cidx = (nt - g.tile_begin) * ((g.M + 31) >> 5) + mt_global;
-      if (threadIdx.x == 0) s.flag = atomicAdd(e.tile_counters + cidx, 1);
-      __syncthreads();
-      const bool last = s.flag == (int)gridDim.y - 1;
-      if (last) {
-        float ss = 0.0f;
-        if (m < g.M) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float v = __hip_atomic_load(p[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            ss = fmaf(v, v, ss);
-          }
-        }
-        s.part[(l2 >> 5) * 4 + qq][l2 & 31] = ss;
-      }
-      __syncthreads();
-      if (last) {
-        if (threadIdx.x < 32) {
-          float t = 0.0f;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) t += s.part[j][threadIdx.x];
-          if (mt_global * 32 + threadIdx.x < g.M) unsafeAtomicAdd(e.rowsq + mt_global * 32 + threadIdx.x, t);
-        }
-        if (threadIdx.x == 0) e.tile_counters[cidx] = 0;   // ready for the next launch
+    __syncthreads();
+    {
+      const int mr = threadIdx.x >> 3, c0 = (threadIdx.x & 7) * 4;
+      const int mm = mt_global * 32 + mr;
+      if (mm < g.M) {
+        const float4 v = make_float4(s.zt[c0][mr], s.zt[c0 + 1][mr], s.zt[c0 + 2][mr], s.zt[c0 + 3][mr]);
+        *reinterpret_cast<float4*>(e.h + ((size_t)blockIdx.y * e.Mpad + mm) * e.n_out + nt * 32 + c0) = v;
       }
     }
   } else {
@@ -412,7 +383,6 @@ __device__ u32x4 k_zero_tile[64];   // one operand tile of zeros, never written 
 template <int MT>
 struct TiledLds {
   u32x4 b[2][UT][MT][64];
-  float part[NW][2][MT][32];
   int flag;
 };
 
@@ -581,66 +551,24 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
         }
       }
   } else if constexpr (std::is_same<Epi, AccEpi>::value) {
+    // this workgroup's contraction slice (ksl) of the partial results, plain 16-byte stores: a lane holds, for its
+    // batch row, two runs of four consecutive channels and the two runs 16 channels further on
 #pragma unroll
     for (int t = 0; t < NTW; ++t)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         const int m = (chunk * MT + mt) * 32 + ml;
-        const int row = (e.perm && m < M_eff) ? e.perm[m] : m;
-        if (m < M_eff && !(e.skip && ctl_load(e.skip + row) != 0)) {
+        if (m < M_eff) {
+          float* row = e.h + ((size_t)ksl * e.Mpad + m) * e.n_out + (nt0 + t) * 32 + half * 4;
 #pragma unroll
-          for (int a = 0; a < 8; ++a) {
-            const int f_lo = packed_row_lo(nt0 + t, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
-            unsafeAtomicAdd(e.h + ht_index(row, f_lo, e.Mpad), acc[t][mt][a]);
-            unsafeAtomicAdd(e.h + ht_index(row, f_lo + g.pair_stride, e.Mpad), acc[t][mt][a + 8]);
+          for (int q = 0; q < 2; ++q) {
+            *reinterpret_cast<float4*>(row + q * 8) =
+                make_float4(acc[t][mt][4 * q], acc[t][mt][4 * q + 1], acc[t][mt][4 * q + 2], acc[t][mt][4 * q + 3]);
+            *reinterpret_cast<float4*>(row + q * 8 + 16) =
+                make_float4(acc[t][mt][4 * q + 8], acc[t][mt][4 * q + 9], acc[t][mt][4 * q + 10], acc[t][mt][4 * q + 11]);
           }
         }
       }
-    if (e.rowsq) {
-      // last contraction slice of this workgroup's tiles: read the finished values back (device-scope atomic
-      // loads of words that were only ever touched by device-scope atomic adds) and add their squares to the
-      // row sums the next RMSNorm needs
-      __builtin_amdgcn_s_waitcnt(0);
-      __syncthreads();
-      const int cidx = bx * chunks + chunk;
-      if (threadIdx.x == 0) s.flag = atomicAdd(e.tile_counters + cidx, 1);
-      __syncthreads();
-      const bool last = s.flag == ksplit - 1;
-      if (last) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          const int m = (chunk * MT + mt) * 32 + ml;
-          float ss = 0.0f;
-          if (m < M_eff) {
-            const int row = e.perm ? e.perm[m] : m;
-#pragma unroll
-            for (int t = 0; t < NTW; ++t)
-#pragma unroll
-              for (int a = 0; a < 8; ++a) {
-                const int f_lo = packed_row_lo(nt0 + t, (a >> 2) * 8 + half * 4 + (a & 3), g.pair_stride);
-                const float v0 = __hip_atomic_load(e.h + ht_index(row, f_lo, e.Mpad), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const float v1 = __hip_atomic_load(e.h + ht_index(row, f_lo + g.pair_stride, e.Mpad), __ATOMIC_RELAXED,
-                                                   __HIP_MEMORY_SCOPE_AGENT);
-                ss = fmaf(v0, v0, ss);
-                ss = fmaf(v1, v1, ss);
-              }
-          }
-          s.part[wave][half][mt][ml] = ss;
-        }
-      }
-      __syncthreads();
-      if (last) {
-        for (int t = threadIdx.x; t < MT * 32; t += blockDim.x) {
-          const int mt = t >> 5, mm = t & 31;
-          float tot = 0.0f;
-#pragma unroll
-          for (int w = 0; w < NW; ++w) tot += s.part[w][0][mt][mm] + s.part[w][1][mt][mm];
-          const int m = (chunk * MT + mt) * 32 + mm;
-          if (m < M_eff) unsafeAtomicAdd(e.rowsq + (e.perm ? e.perm[m] : m), tot);
-        }
-        if (threadIdx.x == 0) e.tile_counters[cidx] = 0;
-      }
-    }
   } else {
 #pragma unroll
     for (int t = 0; t < NTW; ++t)
@@ -681,11 +609,42 @@ int pick_mt(int M, int cap) {
 // once per pass of the streaming kernel.
 bool tiled(int M, int n_tiles) { return (M + 31) / 32 >= 3 && n_tiles % NW == 0; }
 
+// Which kernel an accumulate projection (output or down projection) of M rows onto n_tiles packed tiles over a
+// contraction of K runs in, and how many contraction slices it writes.  Every slice is one more partial result for
+// the normalisation launch to read, so the count stays as small as filling the chip allows.
+struct AccPlan {
+  int kind;     // 0: streaming kernel, 1: tiled kernel with 128-row chunks, 2: tiled kernel, one chunk of one or two tiles
+  int ksplit;
+};
+AccPlan acc_plan(int M, int n_tiles, int K) {
+  const int m_tiles = (M + 31) / 32, k_steps = K / 16;
+  AccPlan p{0, 1};
+  if (tiled(M, n_tiles)) {
+    const int chunks = (m_tiles + 3) / 4, groups = n_tiles / NW;
+    // one workgroup per compute unit (measured at 96-512 rows: better than two), slices of at least 64 steps
+    p.kind = 1;
+    p.ksplit = 256 / (groups * chunks);
+  } else if (m_tiles <= 2 && n_tiles % NW == 0 && k_steps >= 512) {
+    p.kind = 2;
+    p.ksplit = 256 / (n_tiles / NW);
+  } else {
+    // streaming kernel (its four wavefronts already split the slice four ways): enough workgroups for every
+    // compute unit, no more
+    p.ksplit = (256 + n_tiles - 1) / n_tiles;
+  }
+  if (p.ksplit > k_steps / 64) p.ksplit = k_steps / 64;
+  if (p.ksplit > 8) p.ksplit = 8;   // the normalisation launch adds at most eight partial results
+  if (p.ksplit < 1) p.ksplit = 1;
+  return p;
+}
+
 template <class Epi, bool FILL>
 void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int nz, hipStream_t st,
             const CombineJob& cj = CombineJob{}) {
   dim3 block(256);
   const int m_tiles = (g.M + 31) / 32;
+  constexpr bool ACC = std::is_same<Epi, AccEpi>::value;
+  const AccPlan ap = ACC ? acc_plan(g.M, g.n_tiles, g.K) : AccPlan{0, 1};
   // Batch chunks of 4 tiles (128 rows) measured faster than 8 at batch 256 and 512: twice the workgroups, each
   // with half the accumulators, keeps more loads in flight; the second chunk's weight reads mostly hit the caches.
   if (tiled(g.M, g.n_tiles)) {
@@ -695,15 +654,7 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
     // workgroups) measured slower at batch 256 and 512 for every shape but the LM head: halving the LDS reads per
     // MFMA does not pay by itself, so LDS bandwidth alone is not what limits the kernel.
     const int groups = g.n_tiles / NW;
-    int ksplit = 1;
-    if constexpr (std::is_same<Epi, AccEpi>::value) {
-      const int k_steps = g.K / 16;
-      // one workgroup per compute unit (measured at 96-512 rows: better than two; further slices only add
-      // rounds of float atomics), slices of at least 64 contraction steps
-      ksplit = 256 / (groups * chunks);
-      if (ksplit > k_steps / 64) ksplit = k_steps / 64;
-      if (ksplit < 1) ksplit = 1;
-    }
+    const int ksplit = ap.ksplit;
     if constexpr (std::is_same<Epi, QkvEpi>::value && !FILL) {
       // Few output tiles and one 128-row chunk leave most compute units idle (QKV at 7B width: 96 workgroups):
       // 64-row chunks double the workgroups as long as they all still start at once (measured at 128 rows:
@@ -728,20 +679,15 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
   // of the streaming kernel): LM head, gate/up and the down projection (measured at 32 rows: 47.0 -> 44.0,
   // 34.6 -> 33.2, 21.8 -> 20.8 us; at 64 rows: 62.8 -> 43.5, 44.4 -> 38.3, 27.5 -> 25.4).  QKV and the output
   // projection have too few tiles for that and stay with the streaming kernel.
-  if constexpr (!FILL && !std::is_same<Epi, QkvEpi>::value) {
-    const int k_steps = g.K / 16;
-    const bool enough = std::is_same<Epi, AccEpi>::value ? k_steps >= 512 : true;
-    if (m_tiles <= 2 && g.n_tiles % NW == 0 && g.split_tiles == 0 && enough) {
+  // KV filling takes the same route: one launch covers many layers, so there are always enough workgroups, and the
+  // four tiles of a workgroup are the 128 channels of one head, whose cache lines then leave from one L2.
+  if constexpr (FILL || !std::is_same<Epi, QkvEpi>::value) {
+    const bool small_tiled = ACC ? ap.kind == 2 : (m_tiles <= 2 && g.n_tiles % NW == 0 && g.split_tiles == 0);
+    if (small_tiled) {
       const int groups = g.n_tiles / NW;
-      int ksplit = 1;
-      if constexpr (std::is_same<Epi, AccEpi>::value) {
-        ksplit = 256 / groups;
-        if (ksplit > k_steps / 64) ksplit = k_steps / 64;
-        if (ksplit < 1) ksplit = 1;
-      }
       GemmShape gs = g;
-      gs.grid_y = ksplit;   // one chunk
-      dim3 grid1((groups + 7) / 8 * 8 * ksplit, 1, nz);
+      gs.grid_y = ap.ksplit;   // one chunk
+      dim3 grid1((groups + 7) / 8 * 8 * ap.ksplit, 1, nz);
       if (m_tiles == 1)
         hipLaunchKernelGGL((gemm_tiled_kernel<1, 1, Epi, FILL>), grid1, block, 0, st, gs, e, pred, fc);
       else
@@ -750,7 +696,7 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
     }
   }
   // split tiles take two workgroups each (one batch tile only); the workgroups of a combine job come first
-  dim3 grid(g.n_tiles + g.split_tiles + cj.n_wg, g.ksplit, nz);
+  dim3 grid(g.n_tiles + g.split_tiles + cj.n_wg, ACC ? ap.ksplit : 1, nz);
   switch (pick_mt(g.M, 4)) {
     case 4:
       hipLaunchKernelGGL((gemm_mfma_kernel<4, 2, Epi, FILL>), grid, block, 0, st, g, e, pred, fc, cj);
@@ -766,6 +712,8 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
 }  // namespace
 
 bool gemm_bf16_is_tiled(int M, int n_tiles) { return tiled(M, n_tiles); }
+
+int gemm_acc_slices(int M, int n_tiles, int K) { return acc_plan(M, n_tiles, K).ksplit; }
 
 bool gemm_qkv_carries_combine(int M) { return (M + 31) / 32 <= 2; }   // the streaming kernel serves these batches
 

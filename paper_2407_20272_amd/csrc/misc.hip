@@ -28,16 +28,14 @@ __global__ void iter_init_kernel(IterState s, int B, int n_layers, float* conf_o
 
 // hidden_states <- Embed(input_tokens): one row gather per sequence; padding rows of the last tile are zero.
 // A token id outside 0..vocab-1 reads row 0 (the result is unspecified, the access stays inside the table).
-__global__ void embed_bf16_kernel(const bf16_t* E, const int32_t* tokens, float* hT, int B, int Mpad, int d, int vocab) {
-  const int k = blockIdx.x * blockDim.y + threadIdx.y;
-  const int m = blockIdx.y * 32 + threadIdx.x;
-  if (k >= d || m >= Mpad) return;
-  float v = 0.0f;
+__global__ __launch_bounds__(256) void embed_bf16_kernel(const bf16_t* E, const int32_t* tokens, float* h, int B, int d, int vocab) {
+  const int m = blockIdx.x;
+  const bf16_t* row = nullptr;
   if (m < B) {
     const int tok = tokens[m];
-    v = (float)E[(size_t)((unsigned)tok < (unsigned)vocab ? tok : 0) * d + k];
+    row = E + (size_t)((unsigned)tok < (unsigned)vocab ? tok : 0) * d;
   }
-  hT[ht_index(m, k, Mpad)] = v;
+  for (int k = threadIdx.x; k < d; k += blockDim.x) h[(size_t)m * d + k] = row ? (float)row[k] : 0.0f;
 }
 __global__ void embed_f32_kernel(const float* E, const int32_t* tokens, float* h, int B, int d, int vocab) {
   const int k = blockIdx.x * blockDim.x + threadIdx.x;
@@ -46,18 +44,6 @@ __global__ void embed_f32_kernel(const float* E, const int32_t* tokens, float* h
   if (k < d) h[(size_t)m * d + k] = E[(size_t)((unsigned)tok < (unsigned)vocab ? tok : 0) * d + k];
 }
 
-__global__ void hidden_to_ht_kernel(const float* plain, float* hT, int B, int Mpad, int d) {
-  const int k = blockIdx.x * blockDim.y + threadIdx.y;
-  const int m = blockIdx.y * 32 + threadIdx.x;
-  if (k >= d || m >= Mpad) return;
-  hT[ht_index(m, k, Mpad)] = m < B ? plain[(size_t)m * d + k] : 0.0f;
-}
-__global__ void ht_to_hidden_kernel(const float* hT, float* plain, int B, int Mpad, int d) {
-  const int k = blockIdx.x * blockDim.y + threadIdx.y;
-  const int m = blockIdx.y * 32 + threadIdx.x;
-  if (k >= d || m >= B) return;
-  plain[(size_t)m * d + k] = hT[ht_index(m, k, Mpad)];
-}
 // (cos, sin) of pos_m * theta^(-2j/dh) for every sequence m and channel pair j, angles formed in double.
 __global__ void rope_table_kernel(const int32_t* context_lens, float2* table, int B, int head_dim, float theta) {
   const int half = head_dim >> 1;
@@ -75,107 +61,160 @@ __global__ void copy_f32_kernel(const float* src, float* dst, size_t n) {
 }
 
 // ---------------------------------------------------------------------------------------------------
-// bf16 path, RMSNorm in two small steps.
-//   rowsq_kernel : rowsq[m] += sum_k h[m][k]^2 (grid = Mpad/32 workgroups of 1024 threads).
-//   prep_x_kernel: x = bf16(h * rsqrt(rowsq/d + eps) * gain) written in operand-tile order.
-//     A workgroup covers one 32-row batch tile x 64 channels: thread (m = t%32, c = t/32) owns 8 channels.
-//     grid = (d/64, Mpad/32, slabs); slab z uses gains.g[z] and writes slab z of xT (KV filling: one per layer;
-//     after a layer with an exit head: the head's operand and the next layer's attention operand in one launch).
+// bf16 path: residual update + RMSNorm, one workgroup per batch row.
+//   The projection before (output or down projection) left S partial results of the row, one per contraction
+//   slice; they are summed in slice order and added to the residual row (nothing is added for a sequence that has
+//   left, or when S == 0).  The row's sum of squares is reduced in a fixed order (lanes, then wavefronts), so the
+//   whole update is reproducible bit for bit.  Then x = bf16(h * rsqrt(sumsq/d + eps) * gain) is written in
+//   operand-tile order for up to two gains (after a layer with an exit head: the head's operand and the next
+//   layer's).
 // ---------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void rowsq_kernel(const float* hT, float* rowsq, int Mpad, int d, Pred pred) {
-  // One workgroup per 32-row batch tile walks every channel and sums in a fixed order, so the result does not
-  // depend on how workgroups are scheduled (it runs once per call, not once per layer).
-  if (pred_skip(pred)) return;
-  const int ml = threadIdx.x & 31, cl = threadIdx.x >> 5;
-  const int m = blockIdx.x * 32 + ml;
-  float ss = 0.0f;
-  for (int k = cl; k < d; k += 32) {
-    const float h = hT[ht_index(m, k, Mpad)];
-    ss = fmaf(h, h, ss);
-  }
-  __shared__ float part[32][32];
-  part[cl][ml] = ss;
-  __syncthreads();
-  if (cl == 0) {
-    float s = 0.0f;
+constexpr int NORM_THREADS = 512;
+constexpr int NORM_CHUNKS = 2;    // thread t owns channels [c * 4096 + 8t, +8), c = 0..1: d <= 8192
+
+__device__ inline float block_sum(float v, float* red /* [NORM_THREADS / 64] of LDS */) {
 #pragma unroll
-    for (int j = 0; j < 32; ++j) s += part[j][ml];
-    rowsq[m] += s;
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float t = 0.0f;
+#pragma unroll
+  for (int w = 0; w < NORM_THREADS / 64; ++w) t += red[w];
+  __syncthreads();
+  return t;
+}
+
+__device__ inline void load8(const float* p, float (&v)[8]) {
+  const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ inline void store8(float* p, const float (&v)[8]) {
+  *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+}
+__device__ inline void zero_x_row(bf16_t* x, int m, int d) {
+  for (int k0 = threadIdx.x * 8; k0 < d; k0 += NORM_THREADS * 8) {
+    bf16x8 z;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) z[i] = (bf16_t)0.0f;
+    *reinterpret_cast<bf16x8*>(x + xt_index(m, k0, d)) = z;
+  }
+}
+__device__ inline void write_x_row(bf16_t* x, int row, int d, const float (&v)[NORM_CHUNKS][8], float r, const bf16_t* gain) {
+#pragma unroll
+  for (int c = 0; c < NORM_CHUNKS; ++c) {
+    const int k0 = (c * NORM_THREADS + threadIdx.x) * 8;
+    if (k0 < d) {
+      const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gain + k0);
+      bf16x8 out;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) out[i] = (bf16_t)(v[c][i] * r * (float)gv[i]);
+      *reinterpret_cast<bf16x8*>(x + xt_index(row, k0, d)) = out;
+    }
   }
 }
 
-__global__ __launch_bounds__(256) void prep_x_kernel(const float* hT, GainTable gains, const bf16_t* gain0, bf16_t* xT,
-                                                     size_t slab_elems, const float* rowsq, size_t rowsq_layer_stride,
-                                                     const int32_t* slot_ptr, float eps, const int32_t* fill_from,
-                                                     int fill_from_stride, int B, int Mpad, int d, RowDot rd,
-                                                     RowMap rm, Pred pred) {
+// S: number of partial results to add (0 = none), a template parameter so that all of a thread's loads are in
+// flight together; they are then added in slice order.
+template <int S>
+__global__ __launch_bounds__(NORM_THREADS) void finish_norm_kernel(NormArgs a, Pred pred) {
   if (pred_skip(pred)) return;
-  const int z = blockIdx.z;
-  const int ml = threadIdx.x & 31, cl = threadIdx.x >> 5;
-  const int m = blockIdx.y * 32 + ml;
-  // slab 0 of a launch with a row map is compacted: position m holds batch row perm[m], zeros from *n_active on
-  // (never combined with the second job below)
-  const bool compacted = rm.perm != nullptr && z == 0;
-  const int n_valid = compacted ? rm.n_active[0] : Mpad;
-  if ((int)blockIdx.y * 32 >= n_valid) return;
-  const bool valid = m < n_valid;
-  const int row = (compacted && valid) ? rm.perm[m] : m;
-  if (fill_from) {
-    // KV filling: slab z is layer z+1; skip slabs no sequence needs
-    const int layer = z + 1;
-    if (fill_from_stride == 0) {
-      if (!(fill_from[0] < layer)) return;
+  __shared__ float red[NORM_THREADS / 64];
+  const int m = blockIdx.x;
+  const int d = a.d;
+  // rows that hold no sequence: padding rows of an in-place operand, positions behind the active rows of a
+  // compacted one
+  const int n_act = a.rm.perm ? a.rm.n_active[0] : a.B;
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+    if (a.x[j] && m >= (a.compacted[j] ? n_act : a.B)) zero_x_row(a.x[j], m, d);
+  if (m >= a.B) return;
+  const int pos = a.rm.perm ? a.rm.cpos[m] : m;   // row of the partial results; -1 for a sequence that has left
+  const bool frozen = pos < 0 || (a.skip && ctl_load(a.skip + m) != 0);
+  const bool add = S > 0 && !frozen;
+  float v[NORM_CHUNKS][8];
+  float ss = 0.0f, dot = 0.0f;
+#pragma unroll
+  for (int c = 0; c < NORM_CHUNKS; ++c) {
+    const int k0 = (c * NORM_THREADS + threadIdx.x) * 8;
+    if (k0 < d) {
+      load8(a.h_in + (size_t)m * d + k0, v[c]);
+      if (add) {
+        float part[S > 0 ? S : 1][8];
+#pragma unroll
+        for (int s = 0; s < S; ++s) load8(a.y + ((size_t)s * a.Mpad + pos) * d + k0, part[s]);
+#pragma unroll
+        for (int s = 1; s < S; ++s)
+#pragma unroll
+          for (int i = 0; i < 8; ++i) part[0][i] += part[s][i];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) v[c][i] += part[0][i];
+        store8(a.h_out + (size_t)m * d + k0, v[c]);
+      }
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ss = fmaf(v[c][i], v[c][i], ss);
+      if (a.rd.dots) {
+        float o[8];
+        load8(a.rd.other + (a.rd.per_row ? (size_t)m * d : (size_t)0) + k0, o);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) dot = fmaf(v[c][i], o[i], dot);
+      }
+      if (a.rd.snapshot) store8(a.rd.snapshot + (size_t)m * d + k0, v[c]);
     } else {
-      __shared__ int any_row;
-      if (threadIdx.x == 0) any_row = 0;
-      __syncthreads();
-      int need = 0;
-      for (int r = threadIdx.x; r < B; r += blockDim.x) need |= fill_from[r] < layer;
-      if (need) any_row = 1;
-      __syncthreads();
-      if (!any_row) return;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[c][i] = 0.0f;
     }
   }
-  const bf16_t* gain = gains.g[z] ? reinterpret_cast<const bf16_t*>(gains.g[z]) : gain0;
-  const int c = blockIdx.x * 8 + cl;  // 8-channel chunk
-  const int k0 = c * 8;
-  // Hidden state of the batch exit layer L (KV filling and the final token inside a decode iteration): its sums
-  // were left by the down projection of layer L in slot 2L of the per-iteration table; *slot_ptr = L
-  if (rowsq_layer_stride) rowsq += (size_t)slot_ptr[0] * rowsq_layer_stride;
-  const float rq = rowsq[row];
-  float hv[8];
+  ss = block_sum(ss, red);
+  if (a.rd.dots) {
+    dot = block_sum(dot, red);
+    if (threadIdx.x == 0) a.rd.dots[m] = dot;
+  }
+  if (a.rowsq_out && threadIdx.x == 0) a.rowsq_out[m] = ss;
+  const float r = rsqrtf(ss / (float)d + a.eps);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) hv[i] = valid ? hT[ht_index(row, k0 + i, Mpad)] : 0.0f;
-  const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gain + k0);
-  const float r = valid ? rsqrtf(rq / (float)d + eps) : 0.0f;
-  bf16x8 out;
+  for (int j = 0; j < 2; ++j) {
+    if (!a.x[j]) continue;
+    const int row = a.compacted[j] ? pos : m;
+    if (row >= 0) write_x_row(a.x[j], row, d, v, r, a.gain[j]);
+  }
+}
+
+// KV filling: grid (Mpad, n_layers); workgroup (m, l-1) normalises row m with layer l's attention gain into slab
+// l-1.  Same arithmetic, thread for thread, as finish_norm_kernel, so that what is filled for a layer equals bit
+// for bit the operand that layer's own pass would have built from the same hidden state.
+__global__ __launch_bounds__(NORM_THREADS) void fill_prep_kernel(const float* h, GainTable gains, bf16_t* x_slabs,
+                                                                 size_t slab_elems, float eps, const int32_t* fill_from,
+                                                                 int fill_from_stride, int B, int d, Pred pred) {
+  if (pred_skip(pred)) return;
+  __shared__ float red[NORM_THREADS / 64];
+  const int m = blockIdx.x, layer = blockIdx.y + 1;
+  bf16_t* x = x_slabs + (size_t)blockIdx.y * slab_elems;
+  if (fill_from_stride == 0) {
+    if (!(ctl_load(fill_from) < layer)) return;     // Algorithm 1: one batch exit layer for everybody
+  } else if (m < B && !(fill_from[m] < layer)) {
+    return;                                          // this row's K/V of this layer exist already: its operand row is never used
+  }
+  if (m >= B) {
+    zero_x_row(x, m, d);
+    return;
+  }
+  float v[NORM_CHUNKS][8];
+  float ss = 0.0f;
 #pragma unroll
-  for (int i = 0; i < 8; ++i) out[i] = (bf16_t)(hv[i] * r * (float)gv[i]);
-  *reinterpret_cast<bf16x8*>(xT + (size_t)z * slab_elems + xt_index(m, k0, d)) = out;
-  if (z != 0) return;
-  // second job (uniform over the launch): dot product of every row with the previous hidden state or a weight
-  // row, and the snapshot that becomes the next layer's "previous hidden state"
-  if (rd.dots) {
-    float acc = 0.0f;
+  for (int c = 0; c < NORM_CHUNKS; ++c) {
+    const int k0 = (c * NORM_THREADS + threadIdx.x) * 8;
+    if (k0 < d) {
+      load8(h + (size_t)m * d + k0, v[c]);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float o = rd.per_row ? rd.other[ht_index(m, k0 + i, Mpad)] : rd.other[k0 + i];
-      acc = fmaf(hv[i], o, acc);
-    }
-    __shared__ float part[8][32];
-    part[cl][ml] = acc;
-    __syncthreads();
-    if (cl == 0) {
-      float t = 0.0f;
+      for (int i = 0; i < 8; ++i) ss = fmaf(v[c][i], v[c][i], ss);
+    } else {
 #pragma unroll
-      for (int j = 0; j < 8; ++j) t += part[j][ml];
-      unsafeAtomicAdd(rd.dots + m, t);
+      for (int i = 0; i < 8; ++i) v[c][i] = 0.0f;
     }
   }
-  if (rd.snapshot) {
-#pragma unroll
-    for (int i = 0; i < 8; ++i) rd.snapshot[ht_index(m, k0 + i, Mpad)] = hv[i];
-  }
+  ss = block_sum(ss, red);
+  write_x_row(x, m, d, v, rsqrtf(ss / (float)d + eps), reinterpret_cast<const bf16_t*>(gains.g[blockIdx.y]));
 }
 
 // fp32 path: the three sums a one-dot-product confidence measure needs, one workgroup per row.
@@ -255,9 +294,8 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineArgs a, Pred pred) 
 }
 
 // Row map of the sequences that are still active, in batch order (one workgroup walks the batch 256 rows at a
-// time); rows that have left get their sums of squares carried into the next layer's two slots.
-__global__ __launch_bounds__(256) void compact_kernel(const int32_t* status, int B, RowMap rm, float* rowsq_table,
-                                                      int slot, int Mpad, Pred pred) {
+// time).
+__global__ __launch_bounds__(256) void compact_kernel(const int32_t* status, int B, RowMap rm, Pred pred) {
   if (pred_skip(pred)) return;
   __shared__ int wave_total[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -276,11 +314,6 @@ __global__ __launch_bounds__(256) void compact_kernel(const int32_t* status, int
       rm.cpos[m] = off;
     } else if (in) {
       rm.cpos[m] = -1;
-      if (rowsq_table) {
-        const float v = rowsq_table[(size_t)slot * Mpad + m];
-        rowsq_table[(size_t)(slot + 1) * Mpad + m] = v;
-        rowsq_table[(size_t)(slot + 2) * Mpad + m] = v;
-      }
     }
     base += wave_total[0] + wave_total[1] + wave_total[2] + wave_total[3];
     __syncthreads();
@@ -307,17 +340,11 @@ void launch_iter_init(const IterState& s, int B, int n_layers, float* conf_out, 
   if (blocks > 1024) blocks = 1024;
   hipLaunchKernelGGL(iter_init_kernel, dim3(blocks), dim3(256), 0, st, s, B, n_layers, conf_out, zero_buf, zero_count);
 }
-void launch_embed_bf16(const bf16_t* E, const int32_t* tokens, float* hT, int B, int Mpad, int d, int vocab, hipStream_t st) {
-  hipLaunchKernelGGL(embed_bf16_kernel, dim3((d + 7) / 8, Mpad / 32), dim3(32, 8), 0, st, E, tokens, hT, B, Mpad, d, vocab);
+void launch_embed_bf16(const bf16_t* E, const int32_t* tokens, float* h, int B, int Mpad, int d, int vocab, hipStream_t st) {
+  hipLaunchKernelGGL(embed_bf16_kernel, dim3(Mpad), dim3(256), 0, st, E, tokens, h, B, d, vocab);
 }
 void launch_embed_f32(const float* E, const int32_t* tokens, float* h, int B, int d, int vocab, hipStream_t st) {
   hipLaunchKernelGGL(embed_f32_kernel, dim3((d + 255) / 256, B), dim3(256), 0, st, E, tokens, h, B, d, vocab);
-}
-void launch_hidden_to_ht(const float* plain, float* hT, int B, int Mpad, int d, hipStream_t st) {
-  hipLaunchKernelGGL(hidden_to_ht_kernel, dim3((d + 7) / 8, Mpad / 32), dim3(32, 8), 0, st, plain, hT, B, Mpad, d);
-}
-void launch_ht_to_hidden(const float* hT, float* plain, int B, int Mpad, int d, hipStream_t st) {
-  hipLaunchKernelGGL(ht_to_hidden_kernel, dim3((d + 7) / 8, Mpad / 32), dim3(32, 8), 0, st, hT, plain, B, Mpad, d);
 }
 void launch_rope_table(const int32_t* context_lens, float2* table, int B, int head_dim, float theta, hipStream_t st) {
   if (theta <= 0.0f || B == 0) return;
@@ -330,49 +357,27 @@ void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t st) {
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(copy_f32_kernel, dim3(blocks), dim3(256), 0, st, src, dst, n);
 }
-void launch_rowsq(const float* hT, float* rowsq, int Mpad, int d, Pred pred, hipStream_t st) {
-  hipLaunchKernelGGL(rowsq_kernel, dim3(Mpad / 32), dim3(1024), 0, st, hT, rowsq, Mpad, d, pred);
+void launch_finish_norm(const NormArgs& a, Pred pred, hipStream_t st) {
+  const dim3 grid(a.Mpad), block(NORM_THREADS);
+  switch (a.S) {
+    case 0: hipLaunchKernelGGL(finish_norm_kernel<0>, grid, block, 0, st, a, pred); break;
+    case 1: hipLaunchKernelGGL(finish_norm_kernel<1>, grid, block, 0, st, a, pred); break;
+    case 2: hipLaunchKernelGGL(finish_norm_kernel<2>, grid, block, 0, st, a, pred); break;
+    case 3: hipLaunchKernelGGL(finish_norm_kernel<3>, grid, block, 0, st, a, pred); break;
+    case 4: hipLaunchKernelGGL(finish_norm_kernel<4>, grid, block, 0, st, a, pred); break;
+    case 5: hipLaunchKernelGGL(finish_norm_kernel<5>, grid, block, 0, st, a, pred); break;
+    case 6: hipLaunchKernelGGL(finish_norm_kernel<6>, grid, block, 0, st, a, pred); break;
+    case 7: hipLaunchKernelGGL(finish_norm_kernel<7>, grid, block, 0, st, a, pred); break;
+    default: hipLaunchKernelGGL(finish_norm_kernel<8>, grid, block, 0, st, a, pred); break;   // the planner never asks for more
+  }
 }
-void launch_prep_x(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, float eps, int Mpad, int d,
-                   Pred pred, hipStream_t st) {
-  GainTable none{};
-  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 1), dim3(256), 0, st, hT, none, gain, xT, (size_t)0, rowsq, (size_t)0,
-                     (const int32_t*)nullptr, eps, (const int32_t*)nullptr, 0, 0, Mpad, d, RowDot{}, RowMap{}, pred);
+void launch_fill_prep(const float* h, const GainTable& gains, int n_layers, bf16_t* x_slabs, float eps,
+                      const int32_t* fill_from, int fill_from_stride, int B, int Mpad, int d, Pred pred, hipStream_t st) {
+  hipLaunchKernelGGL(fill_prep_kernel, dim3(Mpad, n_layers), dim3(NORM_THREADS), 0, st, h, gains, x_slabs, (size_t)Mpad * d, eps,
+                     fill_from, fill_from_stride, B, d, pred);
 }
-void launch_prep_x_dot(const float* hT, const bf16_t* gain, bf16_t* xT, const float* rowsq, const int32_t* slot_ptr,
-                       size_t slot_stride, float eps, int Mpad, int d, const RowDot& rd, Pred pred, hipStream_t st) {
-  GainTable none{};
-  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 1), dim3(256), 0, st, hT, none, gain, xT, (size_t)0, rowsq,
-                     slot_ptr ? slot_stride : (size_t)0, slot_ptr, eps, (const int32_t*)nullptr, 0, 0, Mpad, d, rd, RowMap{}, pred);
-}
-void launch_prep_x_pair(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT_pair, const float* rowsq,
-                        float eps, int Mpad, int d, Pred pred, hipStream_t st) {
-  GainTable two{};
-  two.g[0] = gain_a;
-  two.g[1] = gain_b;
-  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, 2), dim3(256), 0, st, hT, two, (const bf16_t*)nullptr, xT_pair,
-                     (size_t)Mpad * d, rowsq, (size_t)0, (const int32_t*)nullptr, eps, (const int32_t*)nullptr, 0, 0, Mpad, d,
-                     RowDot{}, RowMap{}, pred);
-}
-void launch_prep_x_compact(const float* hT, const bf16_t* gain_a, const bf16_t* gain_b, bf16_t* xT, const float* rowsq,
-                           const RowMap& rm, float eps, int Mpad, int d, Pred pred, hipStream_t st) {
-  GainTable two{};
-  two.g[0] = gain_a;
-  two.g[1] = gain_b;
-  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, gain_b ? 2 : 1), dim3(256), 0, st, hT, two, (const bf16_t*)nullptr,
-                     xT, (size_t)Mpad * d, rowsq, (size_t)0, (const int32_t*)nullptr, eps, (const int32_t*)nullptr, 0, 0, Mpad,
-                     d, RowDot{}, rm, pred);
-}
-void launch_compact(const int32_t* status, int B, const RowMap& rm, float* rowsq_table, int slot, int Mpad, Pred pred,
-                    hipStream_t st) {
-  hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(256), 0, st, status, B, rm, rowsq_table, slot, Mpad, pred);
-}
-void launch_prep_x_layers(const float* hT, const GainTable& gains, int n_layers, bf16_t* xT_slabs, const float* rowsq,
-                          size_t rowsq_layer_stride, const int32_t* slot_ptr, float eps, const int32_t* fill_from,
-                          int fill_from_stride, int B, int Mpad, int d, Pred pred, hipStream_t st) {
-  hipLaunchKernelGGL(prep_x_kernel, dim3(d / 64, Mpad / 32, n_layers), dim3(256), 0, st, hT, gains,
-                     (const bf16_t*)nullptr, xT_slabs, (size_t)Mpad * d, rowsq, rowsq_layer_stride, slot_ptr, eps, fill_from,
-                     fill_from_stride, B, Mpad, d, RowDot{}, RowMap{}, pred);
+void launch_compact(const int32_t* status, int B, const RowMap& rm, Pred pred, hipStream_t st) {
+  hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(256), 0, st, status, B, rm, pred);
 }
 void launch_rmsnorm_f32(const float* h, const float* gain, float* x, int B, int d, float eps, Pred pred, hipStream_t st) {
   hipLaunchKernelGGL(rmsnorm_f32_kernel, dim3(B), dim3(256), 0, st, h, gain, x, d, eps, pred);
