@@ -20,17 +20,21 @@ def tol_of(cfg) -> float:
     return 1e-4 if cfg.dtype == "fp32" else 2e-2
 
 
-def assert_close_scaled(got: torch.Tensor, want: torch.Tensor, tol: float, what: str, dim=None):
-    """|got - want| <= tol * max|want| (max over the whole tensor, or over `dim` of each row).
+DEEP = 16   # layers up to which two correct bf16 computations stay within 2e-2 element by element (see below)
 
-    bf16 workloads only: two correct computations whose inputs differ by rounding noise disagree on which way some
-    values round to bf16, and tens of layers of a random-weight model amplify that disagreement: at the 7B shape this
-    position's K/V of layers 21-32 differ from the oracle's by 1.4-1.55e-2 relative RMS, run after run, and the largest
-    of the 4096 errors of one row (a 4-5 sigma draw that moves with the order of the float atomics) lands between
-    1.1e-2 and 2.1e-2 of the row's maximum: right on the figure when it is read element-wise.  So for a bf16 tensor
-    (tol 2e-2) the stated "within rel. 2e-2" is read norm-wise where the element-wise reading trips: relative RMS error
-    <= tol, and no element off by more than 2*tol of the maximum.  Anything structural (a wrong index, a dropped term,
-    a rounding point in the wrong place) is off by more and still fails."""
+
+def assert_close_scaled(got: torch.Tensor, want: torch.Tensor, tol: float, what: str, dim=None, depth: int = 0):
+    """|got - want| <= tol * max|want| (max over the whole tensor, or over `dim` of each row), element by element.
+
+    depth = number of decoder layers the compared values have been through.  For bf16 workloads (tol 2e-2) and
+    depth > DEEP the stated "within rel. 2e-2" is read norm-wise where the element-wise reading trips: relative RMS
+    error <= tol and no element off by more than 2 * tol of the maximum.  The reason is measured on the CPU, with no
+    GPU involved (tests/test_bf16_divergence.py): the float64 oracle and the same oracle accumulating its projections
+    in float32, both rounding to bf16 at the same storage points, disagree on which way values round, and a deep
+    random-weight model amplifies that: at the 7B width their hidden states and K/V are 1.0e-2 relative RMS and
+    1.2e-2 of the row maximum apart after 16 layers, 1.5e-2 and 2.0e-2 after 32 (2.5e-2 at width 2048).  No
+    implementation can be held to less against the oracle than a float32 copy of the oracle achieves.  Anything
+    structural (a wrong index, a dropped term, a rounding point in the wrong place) is off by more and still fails."""
     got, want = got.detach().cpu().to(F64), want.detach().cpu().to(F64)
     assert got.shape == want.shape, (what, got.shape, want.shape)
     if want.numel() == 0:
@@ -39,7 +43,7 @@ def assert_close_scaled(got: torch.Tensor, want: torch.Tensor, tol: float, what:
     scale = torch.clamp(scale, min=1e-30)
     err = ((got - want).abs() / scale).max().item()
     assert math.isfinite(err), f"{what}: non-finite values"
-    if err > tol and tol >= 1e-2:
+    if err > tol and tol >= 1e-2 and depth > DEEP:
         rms = float(((got - want) ** 2).mean().sqrt() / torch.clamp((want ** 2).mean().sqrt(), min=1e-30))
         assert rms <= tol and err <= 2 * tol, f"{what}: scaled max error {err:.3e}, relative RMS error {rms:.3e}"
         return err
@@ -112,9 +116,10 @@ class HipRun:
     """Device-side state of one workload: model, paged cache, block tables, workspace, output buffers."""
 
     def __init__(self, cfg, weights_cpu: Dict, context_lens: torch.Tensor, extra_tokens: int, seed: int = 0,
-                 spare_blocks: int = 2, pool_fill: float = 0.0, weights_dev: Optional[Dict] = None):
+                 spare_blocks: int = 2, pool_fill: float = 0.0, weights_dev: Optional[Dict] = None, model=None):
         self.cfg = cfg
-        self.model = B.DeviceModel(cfg, weights_dev if weights_dev is not None else weights_cpu)
+        # model: an existing B.DeviceModel of the same weights (full-size tests share one between cases)
+        self.model = model if model is not None else B.DeviceModel(cfg, weights_dev if weights_dev is not None else weights_cpu)
         self.block_tables, self.num_blocks = W.make_block_tables(context_lens, extra_tokens, cfg.block_size,
                                                                  cfg.shuffled_blocks, seed, spare_blocks)
         self.cache = B.PagedKV(cfg, self.num_blocks, fill=pool_fill)
@@ -247,7 +252,7 @@ def lockstep(cfg, seed: int, steps: int, thresholds=None, forced_seq=None, heads
         assert torch.equal(ev, ~g_conf.isnan()), f"step {s}: different (layer, sequence) pairs were checked"
         if ev.any():
             stats["max_conf_err"] = max(stats["max_conf_err"], check_confidences(cfg, m, tr, g_conf, f"step {s}"))
-        assert_close_scaled(g_hid, tr["h_exit"], tol, f"step {s}: hidden state at the exit layer", dim=-1)
+        assert_close_scaled(g_hid, tr["h_exit"], tol, f"step {s}: hidden state at the exit layer", dim=-1, depth=g_L)
         token_check(g_tok, o_tok, tr["h_exit"], f"step {s}")
         pos = pos + 1
         compare_cache(cfg, run, ocache, pos, tol, f"step {s}", only_pos=pos - 1)
@@ -266,7 +271,8 @@ def compare_cache(cfg, run: HipRun, ocache, lens, tol, what, only_pos=None):
             want = dense[:, :ctx].to(F64)
             for b in range(cfg.batch):
                 sl = slice(0, int(lens[b])) if only_pos is None else slice(int(only_pos[b]), int(only_pos[b]) + 1)
-                assert_close_scaled(got[b, sl], want[b, sl], tol, f"{what}: {name} cache layer {i + 1} sequence {b}")
+                assert_close_scaled(got[b, sl], want[b, sl], tol, f"{what}: {name} cache layer {i + 1} sequence {b}",
+                                    depth=i + 1)
 
 
 def assert_untouched(cfg, run: HipRun, lens, sentinel):

@@ -64,7 +64,7 @@ def one_iteration_case(cfg, seed, sample, forced=None, kv_scale=0.5, threshold=N
             i = min(int(o_exit[r]), int(g_exit[b]))
             assert forced is None and near_threshold(cfg, m, tr, i, r, lam), (b, int(o_exit[r]), int(g_exit[b]))
             near += 1
-    assert_close_scaled(g_hid[sample], tr["h_exit"], tol, "hidden state at the batch exit layer", dim=-1)
+    assert_close_scaled(g_hid[sample], tr["h_exit"], tol, "hidden state at the batch exit layer", dim=-1, depth=g_L)
     z = O.head_logits(m, tr["h_exit"])
     for r, b in enumerate(sample):
         if int(g_tok[b]) != int(o_tok[r]):
@@ -78,8 +78,8 @@ def one_iteration_case(cfg, seed, sample, forced=None, kv_scale=0.5, threshold=N
     for i in range(1, n + 1):                       # this position's K/V in every layer (forward or filled)
         for r, b in enumerate(sample):
             k, v = run.kv_at(i, b, int(lens[b]))
-            assert_close_scaled(k, oc.K[i - 1][r, int(lens[b])], tol, f"K layer {i} sequence {b}")
-            assert_close_scaled(v, oc.V[i - 1][r, int(lens[b])], tol, f"V layer {i} sequence {b}")
+            assert_close_scaled(k, oc.K[i - 1][r, int(lens[b])], tol, f"K layer {i} sequence {b}", depth=min(i, g_L + 1))
+            assert_close_scaled(v, oc.V[i - 1][r, int(lens[b])], tol, f"V layer {i} sequence {b}", depth=min(i, g_L + 1))
     return g_L, near
 
 
@@ -130,7 +130,7 @@ def per_sequence_case(cfg, seed, sample, forced, kv_scale=0.5):
     o_tok, o_exit, o_L = O.decode_iteration_freeze(m, oc, tokens[sample], sub_lens.long(), cfg.threshold,
                                                    forced_exit_layer=forced[sample], trace=tr)
     assert torch.equal(o_exit, g_exit[sample])
-    assert_close_scaled(g_hid[sample], tr["h_exit"], tol, "each sequence's own exit hidden state", dim=-1)
+    assert_close_scaled(g_hid[sample], tr["h_exit"], tol, "each sequence's own exit hidden state", dim=-1, depth=g_L)
     z = O.head_logits(m, tr["h_exit"])
     for r, b in enumerate(sample):
         if int(g_tok[b]) != int(o_tok[r]):
@@ -139,8 +139,8 @@ def per_sequence_case(cfg, seed, sample, forced, kv_scale=0.5):
     for i in range(1, n + 1):
         for r, b in enumerate(sample):
             k, v = run.kv_at(i, b, int(lens[b]))
-            assert_close_scaled(k, oc.K[i - 1][r, int(lens[b])], tol, f"K layer {i} sequence {b}")
-            assert_close_scaled(v, oc.V[i - 1][r, int(lens[b])], tol, f"V layer {i} sequence {b}")
+            assert_close_scaled(k, oc.K[i - 1][r, int(lens[b])], tol, f"K layer {i} sequence {b}", depth=i)
+            assert_close_scaled(v, oc.V[i - 1][r, int(lens[b])], tol, f"V layer {i} sequence {b}", depth=i)
     return g_L
 
 
@@ -217,10 +217,8 @@ def test_config1_full_size_one_iteration_sampled():
 @pytest.mark.parametrize("dtype", ["fp32", "bf16", "bf16_per_sequence_160"])
 def test_hip_graph_replay_matches_eager(dtype):
     """The launch configuration bench.py times: one iteration captured into a HIP graph and replayed, with eager work and
-    synchronisations between replays; every replay must reproduce the eager iteration's outputs.  The fp32 path is
-    deterministic (every residual element has one contributor): exact equality.  The bf16 path sums with float atomics
-    in arrival order, so two runs of it agree only up to rounding: hidden states within the bf16 tolerance, and at
-    most one in ten tokens / exit layers may sit on a near tie."""
+    synchronisations between replays; every replay must reproduce the eager iteration's outputs bit for bit, in fp32 and
+    in bf16 (no sum in either path depends on the order in which workgroups finish)."""
     if dtype == "fp32":
         cfg = W.CONFIGS[0].with_(n_layers=5, batch=8, prompt_len=40, min_prompt_len=40, weight_std=0.05, logit_scale=1.0,
                                  threshold=0.4)
@@ -259,7 +257,7 @@ def test_hip_graph_replay_matches_eager(dtype):
         iteration()
         torch.cuda.synchronize()
         eager.append((run.out_tokens.cpu().clone(), run.out_exit.cpu().clone(), int(run.out_L.item()), run.out_hidden.cpu().clone()))
-    k1 = run.cache.k.clone()
+    k1, v1 = run.cache.k.clone(), run.cache.v.clone()
     side = torch.cuda.Stream()
     reset()
     with torch.cuda.stream(side):
@@ -272,24 +270,11 @@ def test_hip_graph_replay_matches_eager(dtype):
     torch.cuda.synchronize()
     reset()
     scratch = torch.zeros(1 << 20, device="cuda")
-    alive = torch.ones(cfg.batch, dtype=torch.bool)
     for s in range(steps):
         g.replay()
         scratch.add_(1.0)                             # the program's own eager work between replays
         torch.cuda.synchronize()
         t, e, L, h = eager[s]
-        if dtype == "fp32":
-            assert torch.equal(run.out_tokens.cpu(), t) and torch.equal(run.out_exit.cpu(), e) and int(run.out_L.item()) == L, s
-            assert torch.equal(run.out_hidden.cpu(), h), s
-        else:
-            same_tok, same_exit = run.out_tokens.cpu() == t, run.out_exit.cpu() == e
-            assert float(same_tok.float().mean()) >= 0.9, s
-            assert float(same_exit.float().mean()) >= 0.9, s
-            rows = alive & same_tok & same_exit         # sequences still on the eager run's trajectory
-            if int(run.out_L.item()) == L:
-                assert_close_scaled(run.out_hidden.cpu()[rows], h[rows], 2e-2, f"replay {s}: hidden state", dim=-1)
-            alive &= same_tok                           # a different token (a near tie) is fed back: that sequence's future differs
-    if dtype == "fp32":
-        assert torch.equal(run.cache.k, k1)
-    elif bool(alive.all()):
-        torch.testing.assert_close(run.cache.k.float(), k1.float(), rtol=5e-2, atol=5e-2)
+        assert torch.equal(run.out_tokens.cpu(), t) and torch.equal(run.out_exit.cpu(), e) and int(run.out_L.item()) == L, s
+        assert torch.equal(run.out_hidden.cpu(), h), s
+    assert torch.equal(run.cache.k, k1) and torch.equal(run.cache.v, v1)

@@ -98,10 +98,7 @@ def test_threshold_above_one_equals_full_layer_path():
                 pos += 1
             outs.append((torch.stack(toks), run.cache.k.clone(), run.cache.v.clone()))
         assert torch.equal(outs[0][0], outs[1][0])
-        if cfg.dtype == "fp32":      # bf16 path accumulates the residual with float atomics: order may vary
-            assert torch.equal(outs[0][1], outs[1][1]) and torch.equal(outs[0][2], outs[1][2])
-        else:
-            torch.testing.assert_close(outs[0][1].float(), outs[1][1].float(), rtol=2e-2, atol=2e-2)
+        assert torch.equal(outs[0][1], outs[1][1]) and torch.equal(outs[0][2], outs[1][2])     # fp32 and bf16 alike
 
 
 @pytest.mark.parametrize("cfg", [TINY.with_(n_layers=6, decode_steps=3), small_bf16(n_layers=6)], ids=["fp32", "bf16"])
@@ -143,8 +140,17 @@ def test_saturated_model_forced_exit_cache_equals_full_pass(dtype):
     if dtype == "fp32":
         assert torch.equal(res[0][1], res[1][1]) and torch.equal(res[0][2], res[1][2])
     else:
-        torch.testing.assert_close(res[0][1].float(), res[1][1].float(), rtol=2e-2, atol=2e-2)
-        torch.testing.assert_close(res[0][2].float(), res[1][2].float(), rtol=2e-2, atol=2e-2)
+        # Layers up to L0 ran the same kernels on the same values in both runs: identical bits.  Above L0 the filling
+        # launch and the full pass's own QKV launch project the same normalised operand but sum the contraction in
+        # different orders (different kernels; the V tiles of the forward launch are split between two workgroups), so
+        # a value may land on the neighbouring bf16 number (or, where the terms cancel, within float noise of zero).
+        for pool in (1, 2):
+            assert torch.equal(res[0][pool][:L0], res[1][pool][:L0])
+            a, b = res[0][pool][L0:].float(), res[1][pool][L0:].float()
+            step = torch.exp2(torch.floor(torch.log2(torch.clamp(b.abs(), min=1e-30))) - 7)        # one bf16 step at b
+            assert bool(((a - b).abs() <= torch.clamp(step * 1.001, min=1e-5 * float(b.abs().max()))).all()), \
+                "a filled value is more than one bf16 step from the full pass's"
+            assert float((a != b).float().mean()) < 0.02, "more than 2 % of the filled values differ in the last bit"
 
 
 def test_empty_batch_is_a_noop():
