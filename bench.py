@@ -26,38 +26,100 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 
 
-def algorithmic_bytes(cfg, cls, mean_ctx_plus1):
-    """Bytes one launch of a kernel class must move (weights once; K and V of every cached position once)."""
-    d, f, V, B = cfg.d_model, cfg.d_ffn, cfg.vocab, cfg.batch
-    return {
-        "qkv": 3 * d * d * 2,
-        "o_proj": d * d * 2,
-        "gate_up": 2 * f * d * 2,
-        "down": d * f * 2,
-        "head": V * d * 2,
-        "attention": int(B * mean_ctx_plus1 * 2 * d * 2),
-    }.get(cls)
+def algorithmic_bytes(cfg, cls):
+    """Bytes one launch of a projection class must move: its weights, once."""
+    d, f, V = cfg.d_model, cfg.d_ffn, cfg.vocab
+    return {"qkv": 3 * d * d * 2, "o_proj": d * d * 2, "gate_up": 2 * f * d * 2, "down": d * f * 2, "head": V * d * 2}.get(cls)
+
+
+def kv_bytes_per_position(cfg):
+    """K and V of one cached position of one layer (what attention must read for it)."""
+    return 2 * cfg.d_model * 2
+
+
+def layers_with_head(cfg, upto):
+    return sum(1 for i in range(1, upto + 1) if i < cfg.n_layers and i % cfg.exit_every == 0)
+
+
+def iteration_bytes(cfg, kind, L, attended_layer_positions):
+    """Algorithmic HBM bytes of ONE decode iteration that left at batch exit layer L.
+    attended_layer_positions: sum over sequences of (layers the sequence attended in) x (positions it attends, this
+    one included): L x (context + 1) under Algorithm 1, its own exit layer x (context + 1) when sequences leave on
+    their own (a sequence that has left attends nothing).
+    kind: "full" (no heads), "head" (an LM-head pass per checked layer), "dot" (head-less measures)."""
+    n, d = cfg.n_layers, cfg.d_model
+    total = L * sum(algorithmic_bytes(cfg, c) for c in ("qkv", "o_proj", "gate_up", "down"))
+    total += attended_layer_positions * kv_bytes_per_position(cfg)
+    if kind == "head":
+        total += layers_with_head(cfg, L) * algorithmic_bytes(cfg, "head")
+        if L == n:
+            total += algorithmic_bytes(cfg, "head")               # the final LM-head pass
+    else:
+        total += algorithmic_bytes(cfg, "head")                   # one LM-head pass for the tokens
+    total += (n - L) * 2 * d * d * 2                              # KV filling: K and V rows of every skipped layer
+    return total
 
 
 # Thresholds of the two measures that need no LM head.  The weights are random, so no value is "right": these are
 # set where the batch leaves around the middle of the model (see the exit-layer histograms in the output).
 SIM_THRESHOLD = {1: 0.967}
 CLS_THRESHOLD = {1: 0.5}
+SR_THRESHOLD = {1: 0.6}     # softmax response as the paper writes it: top-1 minus top-2 probability
+
+
+def profile_figures(name, key):
+    """Lines `<key> <label...> <value>` of a committed rocprofv3 summary under profiles/ (the machine-readable part)."""
+    out = {}
+    try:
+        with open(os.path.join(ROOT, "profiles", name)) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 3 and parts[0] == key:
+                    out[" ".join(parts[1:-1])] = float(parts[-1])
+    except OSError:
+        pass
+    return out
 
 
 def traffic_ratios():
-    """Measured HBM bytes per algorithmic byte of each kernel class, from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE + WRITE_SIZE, calibrated against a plain copy of known size)."""
+    """Measured HBM bytes per algorithmic byte of each kernel class (FETCH_SIZE + WRITE_SIZE, calibrated against a
+    plain copy of known size)."""
+    return profile_figures("hbm_traffic_llama7b_b32_pmc.md", "traffic_ratio")
+
+
+def measure_peaks(torch, B):
+    """Attainable rates of this chip, measured with the library's calibration kernels (HIP events on the stream they
+    run on): a plain device copy, a plain streaming read, and a register-only loop of bf16 matrix instructions."""
+    st = torch.cuda.current_stream()
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for i in range(reps):
+            fn(i)
+        e1.record(st)
+        e1.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+
     out = {}
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_llama7b_b32_pmc.md")
-    try:
-        with open(path) as f:
-            for line in f:
-                parts = line.split()
-                if len(parts) == 3 and parts[0] == "traffic_ratio":
-                    out[parts[1]] = float(parts[2])
-    except OSError:
-        pass
+    bufs = [torch.full((100 << 20,), 1.0 + i, dtype=torch.float32, device="cuda") for i in range(4)]   # 4 x 400 MiB, rotating
+    sink = torch.zeros(256, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(bufs[0])
+    t = timed(lambda i=0: B.ee_calibration_copy(bufs[i % 3], dst), 12)
+    out["copy_GBps_read_plus_write"] = 2 * bufs[0].numel() * 4 / t / 1e9
+    best = 0.0
+    for wgs in (256, 512, 1024, 2048):
+        t = timed(lambda i=0: B.ee_calibration_read(bufs[i % 4], sink, wgs), 16)
+        best = max(best, bufs[0].numel() * 4 / t / 1e9)
+    out["read_GBps"] = best
+    iters = 20000
+    for per_simd in (1, 2):
+        wgs = 256 * per_simd
+        t = timed(lambda i=0: B.ee_calibration_mfma(wgs, iters, sink), 3)
+        out[f"mfma_bf16_TFLOPs_{per_simd}_wavefront_per_simd"] = wgs * 4 * iters * 4 * 2.0 * 32 * 32 * 16 / t / 1e12
+    out["note"] = "library calibration kernels, HIP events; published peaks: HBM 8000 GB/s, bf16 MFMA 2500 TFLOP/s"
     return out
 
 
@@ -70,8 +132,11 @@ def main():
     ap.add_argument("--layers", type=int, default=0, help="override the layer count (debugging only; invalidates the result)")
     ap.add_argument("--profile-steps", type=int, default=8)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--modes", default="ee,full,never,ee+ps,sim",
+    ap.add_argument("--peaks", action="store_true",
+                    help="also measure this chip's attainable copy / read / MFMA rates with the library's calibration kernels")
+    ap.add_argument("--modes", default="ee,full,never,ee+ps,sim,sr",
                     help="ee: the config's softmax-response heads; full: no heads; never: heads that never fire; "
+                         "sr: softmax response as the paper writes it (top-1 minus top-2 probability); "
                          "sim / cls: hidden-state-similarity / dedicated-classifier checks (no LM head in the loop); "
                          "a +ps suffix lets each sequence leave at its own layer (extension of Algorithm 1).  "
                          "The headline value is always mode ee")
@@ -80,6 +145,7 @@ def main():
                          "instead of the whole batch leaving together")
     ap.add_argument("--sim-threshold", type=float, default=0.0, help="threshold of mode sim (0: a built-in per-config value)")
     ap.add_argument("--cls-threshold", type=float, default=0.0, help="threshold of mode cls (0: a built-in per-config value)")
+    ap.add_argument("--sr-threshold", type=float, default=0.0, help="threshold of mode sr (0: a built-in per-config value)")
     ap.add_argument("--synthetic-kv", action="store_true",
                     help="fill the cache with seeded random K/V instead of prefilling through the decode step "
                          "(always used when prompt lengths are ragged)")
@@ -178,8 +244,8 @@ def main():
     oneB = torch.ones(Bsz, dtype=torch.int32, device="cuda")
     L_last = torch.zeros(P + 1, dtype=torch.int32, device="cuda")
 
-    variants = {"sim": model.with_conf_mode(2), "cls": model.with_conf_mode(3)}
-    thr_of = {"ee": cfg.threshold, "full": 2.0, "never": 2.0,
+    variants = {"sim": model.with_conf_mode(2), "cls": model.with_conf_mode(3), "sr": model.with_conf_mode(1)}
+    thr_of = {"ee": cfg.threshold, "full": 2.0, "never": 2.0, "sr": args.sr_threshold or SR_THRESHOLD.get(args.config, 0.5),
               "sim": args.sim_threshold or SIM_THRESHOLD.get(args.config, 0.99),
               "cls": args.cls_threshold or CLS_THRESHOLD.get(args.config, 0.9)}
 
@@ -237,10 +303,24 @@ def main():
         torch.cuda.synchronize()
         dt = time.perf_counter() - t1
         Lh, Eh = L_hist.cpu().tolist(), E_hist.cpu().tolist()
+        base_mode = mode.split("+")[0]
+        per_seq_mode = (args.per_sequence or mode.endswith("+ps")) and base_mode not in ("full", "never")
+        kind = "full" if base_mode == "full" else ("dot" if base_mode in ("sim", "cls") else "head")
+        mean_L = sum(i * c for i, c in enumerate(Lh)) / K
+        mean_E = sum(i * c for i, c in enumerate(Eh)) / (K * Bsz)
+        # positions attended per layer, summed over the batch, averaged over the timed steps (the context grows by one per step)
+        positions = float(lens.sum()) + Bsz * (Wm + (K - 1) / 2.0 + 1)
+        att = (mean_E if per_seq_mode else mean_L) * positions      # exit layer and context length taken as independent
+        it_bytes = sum(c / K * iteration_bytes(cfg, kind, L_, 0.0) for L_, c in enumerate(Lh) if c) + att * kv_bytes_per_position(cfg)
         results[mode] = {"tokens_per_s": Bsz * K / dt, "ms_per_step": dt / K * 1e3,
-                         "mean_batch_exit_layer": sum(i * c for i, c in enumerate(Lh)) / K,
+                         "mean_batch_exit_layer": mean_L,
                          "batch_exit_layer_hist": {i: c for i, c in enumerate(Lh) if c},
-                         "mean_seq_exit_layer": sum(i * c for i, c in enumerate(Eh)) / (K * Bsz)}
+                         "mean_seq_exit_layer": mean_E,
+                         # the whole iteration against the HBM roofline: algorithmic bytes of the layers that ran
+                         # (weights once per executed layer, cached K/V once per attending sequence and layer, LM head
+                         # per check, K/V rows of the filled layers) over the measured time per step
+                         "iteration": {"algorithmic_GB": it_bytes / 1e9, "GBps": it_bytes / (dt / K) / 1e9,
+                                       "frac_hbm_peak": it_bytes / (dt / K) / 1e9 / HBM_PEAK_GBS}}
         # instrumented pass (eager): HIP events around every kernel, on the stream the kernels run on
         if P > 0:
             ctx_before = ctx.clone()
@@ -248,9 +328,13 @@ def main():
             Lp = []
             near = torch.zeros(2, dtype=torch.int64, device="cuda")
             conf_buf = conf_all if (mode.split("+")[0] not in ("full",) and forced_all is None) else None
+            E_steps = torch.zeros(P, Bsz, dtype=torch.int32, device="cuda")
+            C_steps = torch.zeros(P, Bsz, dtype=torch.int32, device="cuda")
             for s_ in range(P):
+                C_steps[s_].copy_(ctx)
                 iteration(mode)
                 L_last[s_].copy_(out_L[0])
+                E_steps[s_].copy_(out_exit)
                 if conf_buf is not None:
                     near[0] += ((conf_all - thr_of[mode.split("+")[0]]).abs() < NEAR_TOL).sum()
                     near[1] += (~torch.isnan(conf_all)).sum()
@@ -260,37 +344,43 @@ def main():
             results[mode]["near_threshold"] = {"tol": NEAR_TOL, "count": int(near[0]), "decisions": int(near[1]), "steps": P}
             recs = B.ee_profile_read()
             Lp = L_last[:P].cpu().tolist()
-            mean_ctx1 = float(ctx_before.float().mean()) + 1 + (P - 1) / 2.0
+            E_cpu, C_cpu = E_steps.cpu(), C_steps.cpu()
             per_iter = len(recs) // P
-            agg = collections.defaultdict(lambda: [0, 0.0])
-            fill_bytes = 0.0   # KV filling streams the K and V weight rows of every skipped layer: (n - L) * 2 d^2 * 2 bytes
+            agg = collections.defaultdict(lambda: [0, 0.0, 0.0])     # launches, milliseconds, algorithmic bytes
             for it in range(P):
                 for cls, layer, ms in recs[it * per_iter:(it + 1) * per_iter]:
                     # kernels of layers above the batch exit layer return at once; KV filling only runs after an
                     # early exit; the final LM pass (recorded at layer n) only when the loop reached layer n
                     executed = (Lp[it] < n) if cls == "kv_fill" else (layer == 0 or layer <= Lp[it])
                     # measures without an exit head: the one LM-head pass for the tokens (recorded at layer n) always runs
-                    if mode.split("+")[0] in ("sim", "cls") and layer == n and cls in ("head", "norm", "combine"):
+                    if base_mode in ("sim", "cls") and layer == n and cls in ("head", "norm", "combine"):
                         executed = True
-                    if executed:
-                        agg[cls][0] += 1
-                        agg[cls][1] += ms
-                        if cls == "kv_fill":
-                            fill_bytes += (n - Lp[it]) * 2.0 * cfg.d_model * cfg.d_model * 2
-            prof[mode] = {"mean_ctx_plus1": mean_ctx1}
-            for cls, (cnt, ms) in agg.items():
+                    if not executed:
+                        continue
+                    if cls == "kv_fill":      # K and V weight rows of every skipped layer
+                        ab = (n - Lp[it]) * 2.0 * cfg.d_model * cfg.d_model * 2
+                    elif cls == "attention":  # cached K/V of the sequences that still attend in this layer
+                        attends = (E_cpu[it] >= layer) if per_seq_mode else torch.ones(Bsz, dtype=torch.bool)
+                        ab = float((C_cpu[it][attends] + 1).sum()) * kv_bytes_per_position(cfg)
+                    else:
+                        ab = algorithmic_bytes(cfg, cls) or 0.0
+                    a_ = agg[cls]
+                    a_[0] += 1
+                    a_[1] += ms
+                    a_[2] += ab
+            prof[mode] = {"mean_ctx_plus1": float(C_cpu.float().mean()) + 1}
+            for cls, (cnt, ms, ab) in agg.items():
                 # HIP-event time of a kernel = its duration in a rocprofv3 kernel trace + about 2 us (compared on the
                 # same kernels, see profiles/); it is reported as measured, so the rates below are slightly low
                 avg_us = ms / cnt * 1e3
                 entry = {"launches_per_step": cnt / P, "avg_us": avg_us, "share_of_event_time": None}
-                ab = fill_bytes / cnt if cls == "kv_fill" else algorithmic_bytes(cfg, cls, mean_ctx1)
                 if ab:
-                    entry["algorithmic_MB"] = ab / 1e6
-                    entry["GBps"] = ab / (avg_us * 1e-6) / 1e9
+                    entry["algorithmic_MB"] = ab / cnt / 1e6
+                    entry["GBps"] = ab / (ms * 1e-3) / 1e9
                     entry["frac_hbm_peak"] = entry["GBps"] / HBM_PEAK_GBS
                 prof[mode][cls] = entry
             tot = sum(v[1] for v in agg.values())
-            for cls, (cnt, ms) in agg.items():
+            for cls, (cnt, ms, ab) in agg.items():
                 prof[mode][cls]["share_of_event_time"] = ms / tot
 
     head_mode = "ee" if "ee" in results else next(iter(results))
@@ -334,6 +424,13 @@ def main():
                "sample": f"{n_it} early-exit decode iterations of the same workload (batch {Bsz}, context {c0}.., "
                          f"{n} layers), {dt:.1f} s; tokens/s = {n_it} x batch / that time"}
 
+    # MFMA utilisation of the projection kernels is a counter measurement (rocprofv3 --pmc), not something this run can
+    # take: the committed summary's figures, each with the batch (rows) it was taken at.  At batch 32 a projection has
+    # 32 flop per weight byte, so 10 % of the MFMA peak is its ceiling at the HBM roofline.
+    mfma = {"source": "profiles/mfma_utilisation_projections_pmc.md (SQ_VALU_MFMA_BUSY_CYCLES / GRBM_GUI_ACTIVE)",
+            "percent_of_bf16_mfma_peak": profile_figures("mfma_utilisation_projections_pmc.md", "mfma_util")}
+    peaks = measure_peaks(torch, B) if args.peaks else None
+
     line = {
         "metric": "decode tokens/sec/GPU early-exit vs full-layer; HBM GB/s + MFMA util %",
         "value": r["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm,
@@ -349,7 +446,8 @@ def main():
         "modes": results,
         "speedup_ee_vs_full": (results["ee"]["tokens_per_s"] / results["full"]["tokens_per_s"])
         if "ee" in results and "full" in results else None,
-        "roofline": roof, "kernels": prof, "cpu_baseline": cpu, "setup_s": setup_s,
+        "roofline": roof, "iteration_roofline": r.get("iteration"), "mfma_util": mfma, "measured_peaks": peaks,
+        "kernels": prof, "cpu_baseline": cpu, "setup_s": setup_s,
     }
     print(json.dumps(line))
 

@@ -242,6 +242,14 @@ int ee_paged_attention_decode(const ee_model_desc* desc, const ee_kv_cache* cach
 /* Plain device copy of n_floats floats (dev to dev) with the library's own copy kernel: a kernel of known traffic
  * (4 * n_floats bytes read, as many written) against which hardware byte counters are calibrated. */
 int ee_calibration_copy(const float* src, float* dst, size_t n_floats, void* stream);
+/* Attainable-rate probes of the chip the benchmark runs on (what the fractions of the published peaks are set beside).
+ * ee_calibration_read: a plain streaming read of `bytes` bytes (dev, 16-byte aligned) by `workgroups` workgroups of four
+ *   wavefronts, each wavefront walking one contiguous piece with 16 KiB in flight; `sink` (dev, 16 bytes) is written only
+ *   if the exclusive-or of a wavefront's words equals one fixed pattern.  Traffic: `bytes` read, nothing written.
+ * ee_calibration_mfma: `workgroups` x 4 wavefronts each issue 4 * iterations 32x32x16 bf16 matrix instructions on
+ *   registers (2 * 32 * 32 * 16 flop each), no memory traffic; `sink` (dev, 1 KiB) is never written. */
+int ee_calibration_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream);
+int ee_calibration_mfma(int32_t workgroups, int32_t iterations, float* sink, void* stream);
 int ee_profile_enable(int32_t on);
 int ee_profile_read(int32_t* kernel_class /*host*/, int32_t* layer /*host*/, float* ms /*host*/, int32_t max_records);
 

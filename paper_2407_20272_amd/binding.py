@@ -20,7 +20,7 @@ EE_FP32, EE_BF16 = 0, 1
 EE_PACK_PLAIN, EE_PACK_QKV, EE_PACK_GATE_UP = 0, 1, 2
 EXPORTS = ["ee_last_error", "ee_packed_weight_bytes", "ee_pack_weight", "ee_workspace_bytes", "ee_decode_iteration",
            "ee_exit_check", "ee_kv_fill", "ee_paged_attention_decode", "ee_profile_enable", "ee_profile_read", "ee_calibration_copy",
-           "ee_noalloc_init", "ee_exit_check_noalloc_bytes", "ee_exit_check_noalloc"]
+           "ee_noalloc_init", "ee_exit_check_noalloc_bytes", "ee_exit_check_noalloc", "ee_calibration_read", "ee_calibration_mfma"]
 EE_NOALLOC_SCRATCH_BYTES = 8 << 20
 KERNEL_CLASSES = ["norm", "qkv", "attention", "o_proj", "gate_up", "down", "head", "combine", "kv_fill", "other"]
 
@@ -89,6 +89,10 @@ def lib() -> C.CDLL:
                                                 C.POINTER(ee_batch), C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.ee_calibration_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
         L.ee_calibration_copy.restype = C.c_int
+        L.ee_calibration_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_int32, C.c_void_p]
+        L.ee_calibration_read.restype = C.c_int
+        L.ee_calibration_mfma.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.ee_calibration_mfma.restype = C.c_int
         L.ee_profile_enable.argtypes = [C.c_int32]
         L.ee_profile_read.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int32]
         L.ee_profile_enable.restype = C.c_int
@@ -300,3 +304,12 @@ def ee_profile_read(max_records: int = 1 << 20):
 def ee_calibration_copy(src: torch.Tensor, dst: torch.Tensor):
     assert src.dtype == torch.float32 and dst.dtype == torch.float32 and src.numel() == dst.numel()
     _check(lib().ee_calibration_copy(_ptr(src), _ptr(dst), src.numel(), _stream()))
+
+
+def ee_calibration_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int):
+    _check(lib().ee_calibration_read(_ptr(src), src.numel() * src.element_size(), _ptr(sink), workgroups, _stream()))
+
+
+def ee_calibration_mfma(workgroups: int, iterations: int, sink: torch.Tensor):
+    assert sink.dtype == torch.float32 and sink.numel() >= 256
+    _check(lib().ee_calibration_mfma(workgroups, iterations, _ptr(sink), _stream()))

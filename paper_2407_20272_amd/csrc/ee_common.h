@@ -245,6 +245,7 @@ struct GemmShape {
   // return at once, rows beyond it are not written.
   const int32_t* n_rows_dev;
   int grid_y;   // set by the launcher (tiled kernel): batch chunks x contraction slices per group of output tiles
+  int even_wgs; // set by the launcher (tiled kernel): > 0 = the tiles are dealt out evenly over this many workgroups
 };
 // Whether a projection of M rows onto n_tiles packed tiles runs in the tiled kernel (the one that takes
 // n_rows_dev and the epilogues' perm).

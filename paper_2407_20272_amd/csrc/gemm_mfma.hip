@@ -427,12 +427,28 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
     bx = (slot / ny) * 8 + ((int)blockIdx.x & 7);
     by = slot % ny;
   }
-  if (bx * NW * NTW >= g.n_tiles) return;       // the group count is padded to a multiple of 8
+  // Which output tiles this workgroup owns.  Even split: four per workgroup.  Uneven split (g.even_wgs > 0, one
+  // chunk, no contraction slices): the tiles are dealt out over exactly g.even_wgs workgroups, n_tiles / even_wgs
+  // or one more each, and a wavefront beyond its workgroup's count owns none: it still stages its share of the
+  // activation operand, but streams no weights.  A compute unit sustains only so many bytes per second from beyond
+  // its L2, so the launch is as fast as its most loaded compute unit: 688 tiles as 172 x 4 keep a third of the chip
+  // idle while 172 units stream four tiles each; as 176 x 3 + 80 x 2 nobody streams more than three.
+  int my_tiles = NW, tile0 = bx * NW * NTW;
+  if (g.even_wgs > 0) {
+    if (bx >= g.even_wgs) return;
+    const int base = g.n_tiles / g.even_wgs, rem = g.n_tiles % g.even_wgs;
+    my_tiles = base + (bx < rem ? 1 : 0);
+    tile0 = bx * base + min(bx, rem);
+  } else if (tile0 >= g.n_tiles) {
+    return;                                     // the group count is padded to a multiple of 8
+  }
+  const bool active = wave < my_tiles;
   const int chunk = by / ksplit, ksl = by % ksplit;
   // compacted operand: only the first *n_rows_dev rows hold sequences that are still active
   const int M_eff = g.n_rows_dev ? g.n_rows_dev[0] : g.M;
   if (chunk * MT * 32 >= M_eff) return;
-  const int nt0 = g.tile_begin + (bx * NW + wave) * NTW;   // this wavefront's NTW consecutive output tiles
+  // this wavefront's NTW consecutive output tiles (a wavefront without tiles points at the workgroup's first: never loaded)
+  const int nt0 = g.tile_begin + tile0 + (active ? wave : 0) * NTW;
   const int k_steps = g.K >> 4;
   const int ks0 = (int)((long)k_steps * ksl / ksplit);
   const int ks1 = (int)((long)k_steps * (ksl + 1) / ksplit);
@@ -453,67 +469,82 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
   // Everything in the loop is unconditional (a conditional load would force the compiler to wait for every
   // outstanding load where the branches meet): the group count is rounded up to the rotation period and
   // groups past the end load a clamped weight tile against zero activations.
-  u32x4 W[4][NTW][UT], X[2][XR];
   const int n = (ks1 - ks0 + UT - 1) / UT;
-  auto gload = [&](int grp, u32x4 (&wr)[NTW][UT], u32x4 (&xr)[XR]) {
-    const int kbase = ks0 + grp * UT;
+  // The main loop exists twice, chosen once per wavefront: with and without a weight stream.  Both take the same
+  // barriers.
+  auto main_loop = [&](auto streams_c) {
+    constexpr bool STREAMS = decltype(streams_c)::value;
+    u32x4 W[4][NTW][UT], X[2][XR];
+    auto gload = [&](int grp, u32x4 (&wr)[NTW][UT], u32x4 (&xr)[XR]) {
+      const int kbase = ks0 + grp * UT;
+      if constexpr (STREAMS) {
 #pragma unroll
-    for (int u = 0; u < UT; ++u) {
-      const int kk = kbase + u < ks1 ? kbase + u : ks1 - 1;
+        for (int u = 0; u < UT; ++u) {
+          const int kk = kbase + u < ks1 ? kbase + u : ks1 - 1;
 #pragma unroll
-      for (int t = 0; t < NTW; ++t) wr[t][u] = __builtin_nontemporal_load(wp + t * w_tile_stride + (size_t)kk * 64);
-    }
-#pragma unroll
-    for (int j = 0; j < XR; ++j) {
-      const int t = wave + NW * j, u = t / MT, mt = t % MT;
-      // past the end: a tile of zeros, chosen by address (a select on the loaded value would sit right behind
-      // the load and make the wavefront wait for everything it has in flight)
-      const bool ok = kbase + u < ks1;
-      const u32x4* src = ok ? xp + min(mt, mt_last) * x_tile_stride + (size_t)(kbase + u) * 64 : k_zero_tile + lane;
-      xr[j] = *src;
-    }
-  };
-  // One group: drain its activation registers into LDS stage XS, start the loads of group grp+2 into the
-  // registers just freed and an idle weight set, multiply group grp.
-  auto step = [&](int grp, const u32x4 (&wcur)[NTW][UT], u32x4 (&wnext2)[NTW][UT], u32x4 (&xs)[XR], int XS) {
-    // keeps the LDS stores below from being hoisted into the previous group, ahead of its loads: there they would
-    // wait for loads that were only just issued
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < XR; ++j) {
-      const int t = wave + NW * j;
-      s.b[XS][t / MT][t % MT][lane] = xs[j];
-    }
-    __syncthreads();
-    gload(grp + 2, wnext2, xs);
-    // the LDS reads of contraction step u+1 are issued before the multiplies of step u
-    u32x4 bf[2][MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) bf[0][mt] = s.b[XS][0][mt][lane];
-#pragma unroll
-    for (int u = 0; u < UT; ++u) {
-      if (u + 1 < UT) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) bf[(u + 1) & 1][mt] = s.b[XS][u + 1][mt][lane];
+          for (int t = 0; t < NTW; ++t) wr[t][u] = __builtin_nontemporal_load(wp + t * w_tile_stride + (size_t)kk * 64);
+        }
       }
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
+      for (int j = 0; j < XR; ++j) {
+        const int t = wave + NW * j, u = t / MT, mt = t % MT;
+        // past the end: a tile of zeros, chosen by address (a select on the loaded value would sit right behind
+        // the load and make the wavefront wait for everything it has in flight)
+        const bool ok = kbase + u < ks1;
+        const u32x4* src = ok ? xp + min(mt, mt_last) * x_tile_stride + (size_t)(kbase + u) * 64 : k_zero_tile + lane;
+        xr[j] = *src;
+      }
+    };
+    // One group: drain its activation registers into LDS stage XS, start the loads of group grp+2 into the
+    // registers just freed and an idle weight set, multiply group grp.
+    auto step = [&](int grp, const u32x4 (&wcur)[NTW][UT], u32x4 (&wnext2)[NTW][UT], u32x4 (&xs)[XR], int XS) {
+      // keeps the LDS stores below from being hoisted into the previous group, ahead of its loads: there they would
+      // wait for loads that were only just issued
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int t = 0; t < NTW; ++t)
-          acc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wcur[t][u]),
-                                                               __builtin_bit_cast(bf16x8, bf[u & 1][mt]), acc[t][mt], 0, 0, 0);
-    }
-  };
+      for (int j = 0; j < XR; ++j) {
+        const int t = wave + NW * j;
+        s.b[XS][t / MT][t % MT][lane] = xs[j];
+      }
+      __syncthreads();
+      gload(grp + 2, wnext2, xs);
+      if constexpr (STREAMS) {
+        // the LDS reads of contraction step u+1 are issued before the multiplies of step u
+        u32x4 bf[2][MT];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) bf[0][mt] = s.b[XS][0][mt][lane];
+#pragma unroll
+        for (int u = 0; u < UT; ++u) {
+          if (u + 1 < UT) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) bf[(u + 1) & 1][mt] = s.b[XS][u + 1][mt][lane];
+          }
+#pragma unroll
+          for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int t = 0; t < NTW; ++t)
+              acc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wcur[t][u]),
+                                                                   __builtin_bit_cast(bf16x8, bf[u & 1][mt]), acc[t][mt], 0, 0, 0);
+        }
+      }
+    };
 
-  gload(0, W[0], X[0]);
-  gload(1, W[1], X[1]);
-  for (int gi = 0; gi < n; gi += 4) {
-    step(gi, W[0], W[2], X[0], 0);
-    step(gi + 1, W[1], W[3], X[1], 1);
-    step(gi + 2, W[2], W[0], X[0], 0);
-    step(gi + 3, W[3], W[1], X[1], 1);
+    gload(0, W[0], X[0]);
+    gload(1, W[1], X[1]);
+    for (int gi = 0; gi < n; gi += 4) {
+      step(gi, W[0], W[2], X[0], 0);
+      step(gi + 1, W[1], W[3], X[1], 1);
+      step(gi + 2, W[2], W[0], X[0], 0);
+      step(gi + 3, W[3], W[1], X[1], 1);
+    }
+    __syncthreads();
+  };
+  if (active) {
+    main_loop(std::true_type{});
+  } else {
+    main_loop(std::false_type{});
+    return;       // nothing to finish; the epilogues below take no workgroup barrier
   }
-  __syncthreads();
 
   // epilogue from registers: accumulator a (< 8) of a lane is result row r16 = (a/4)*8 + (lane/32)*4 + a%4 of
   // column lane%32, accumulator a+8 is row r16+16 (its partner row in the packed order)
@@ -688,6 +719,12 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
       GemmShape gs = g;
       gs.grid_y = ap.ksplit;   // one chunk
       dim3 grid1((groups + 7) / 8 * 8 * ap.ksplit, 1, nz);
+      // Fewer groups of four than compute units, more tiles than compute units: deal the tiles out over all 256
+      // units instead (two to four each), so that no unit streams more than its share.
+      if (!ACC && !FILL && groups < 256 && g.n_tiles > 256) {
+        gs.even_wgs = 256;
+        grid1 = dim3(256, 1, nz);
+      }
       if (m_tiles == 1)
         hipLaunchKernelGGL((gemm_tiled_kernel<1, 1, Epi, FILL>), grid1, block, 0, st, gs, e, pred, fc);
       else

@@ -74,7 +74,8 @@ def hidden_rel_err(cfg) -> float:
 
 def measure_tolerance(cfg, m, tr, i, b) -> float:
     """Tolerance of the confidence of sequence b at layer i (1-based), derived from the arithmetic of the measure.
-    conf_mode 0/1: through the softmax from a logit tolerance (conf_tolerance).
+    conf_mode 0: through the softmax from a logit tolerance (conf_tolerance); conf_mode 1 (top-1 minus top-2): the sum
+      of that tolerance for the two probabilities.
     conf_mode 2: cos of two vectors that are each off by a relative error delta moves by about 2 delta sin(angle).
     conf_mode 3: the unit's input w.x (x at unit root mean square, |x| = sqrt(d)) moves by about |w| delta sqrt(d)
       along a random direction, i.e. by 1.5 delta for the generator's rows of variance 1.5^2/d; 4 sigma of that
@@ -86,7 +87,12 @@ def measure_tolerance(cfg, m, tr, i, b) -> float:
     if m.conf_mode == 3:
         return (1e-5 if cfg.dtype == "fp32" else 1e-3) + max(c * (1.0 - c), 1e-3) * 4.0 * 1.5 * hidden_rel_err(cfg)
     z = O.head_logits(m, h[None])
-    return conf_tolerance(cfg, c, cfg.logit_scale * i, float(z.abs().max()))
+    scale = cfg.logit_scale * i
+    if m.conf_mode == 1:
+        # top-1 minus top-2: each of the two probabilities moves by its own p(1-p) * 2 * scale * eps
+        p = torch.topk(torch.softmax(scale * z[0], -1), 2).values
+        return conf_tolerance(cfg, float(p[0]), scale, float(z.abs().max())) + conf_tolerance(cfg, float(p[1]), scale, float(z.abs().max()))
+    return conf_tolerance(cfg, c, scale, float(z.abs().max()))
 
 
 def check_confidences(cfg, m, tr, g_conf, what, lam_l=None, decisions=None):

@@ -177,6 +177,15 @@ def test_config1_chunked_prefill_then_four_decode_iterations(capsys, model7b):
            near_tie=ties_all)
 
 
+def test_config1_full_depth_softmax_response_top1_minus_top2(capsys, model7b):
+    """The paper's own softmax-response measure (Section 2.1: top-1 minus top-2 probability of the exit head) at the 7B
+    shape, 32 layers, batch 32: same fused reduction with the runner-up logit carried along.  The threshold is set
+    where the batch leaves inside the model."""
+    cfg = W.CONFIGS[1].with_(conf_mode=1, threshold=0.6, name="llama7b_b32_ctx512_softmax_response")
+    L = one_iteration(capsys, model7b, cfg, seed=11, sample=[0, 9, 31], what="config 1 shape, top-1 minus top-2")
+    assert 1 <= L <= cfg.n_layers
+
+
 # ------------------------------------------------------------------------------------------------------
 # config 2: batch 256, ragged contexts 128..2048, shuffled blocks, 32 layers
 # ------------------------------------------------------------------------------------------------------
