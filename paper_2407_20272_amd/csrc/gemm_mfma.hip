@@ -681,9 +681,7 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
   if (tiled(g.M, g.n_tiles)) {
     // tiled kernel: the workgroup's output tiles share the activation operand through LDS
     const int chunks = (m_tiles + 3) / 4;
-    // One output tile per wavefront.  Two per wavefront (NTW = 2: each LDS operand read feeds two MFMAs, half the
-    // workgroups) measured slower at batch 256 and 512 for every shape but the LM head: halving the LDS reads per
-    // MFMA does not pay by itself, so LDS bandwidth alone is not what limits the kernel.
+    // One output tile per wavefront, except for the LM head (below).
     const int groups = g.n_tiles / NW;
     const int ksplit = ap.ksplit;
     if constexpr (std::is_same<Epi, QkvEpi>::value && !FILL) {
@@ -701,6 +699,16 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
     }
     GemmShape g4 = g;
     g4.grid_y = chunks * ksplit;
+    if constexpr (!FILL && std::is_same<Epi, LmEpi>::value) {
+      // LM head: two output tiles per wavefront (each LDS operand read feeds two MFMAs, half the workgroups):
+      // 161 -> 153 us at 512 rows.  The same arrangement is slower for gate/up (119 -> 135 us) and is not used there.
+      if (g.n_tiles % (2 * NW) == 0) {
+        const int groups2 = g.n_tiles / (2 * NW);
+        dim3 grid2((groups2 + 7) / 8 * 8 * chunks * ksplit, 1, nz);
+        hipLaunchKernelGGL((gemm_tiled_kernel<4, 2, Epi, FILL>), grid2, block, 0, st, g4, e, pred, fc);
+        return;
+      }
+    }
     dim3 grid((groups + 7) / 8 * 8 * chunks * ksplit, 1, nz);
     hipLaunchKernelGGL((gemm_tiled_kernel<4, 1, Epi, FILL>), grid, block, 0, st, g4, e, pred, fc);
     return;

@@ -100,15 +100,24 @@ __device__ inline void zero_x_row(bf16_t* x, int m, int d) {
     *reinterpret_cast<bf16x8*>(x + xt_index(m, k0, d)) = z;
   }
 }
-__device__ inline void write_x_row(bf16_t* x, int row, int d, const float (&v)[NORM_CHUNKS][8], float r, const bf16_t* gain) {
+// The gains are fetched before the row's sum of squares is reduced, so that the loads overlap the reduction instead of
+// following it.
+__device__ inline void load_gain(const bf16_t* gain, int d, bf16x8 (&gv)[NORM_CHUNKS]) {
+#pragma unroll
+  for (int c = 0; c < NORM_CHUNKS; ++c) {
+    const int k0 = (c * NORM_THREADS + threadIdx.x) * 8;
+    if (k0 < d) gv[c] = *reinterpret_cast<const bf16x8*>(gain + k0);
+  }
+}
+__device__ inline void write_x_row(bf16_t* x, int row, int d, const float (&v)[NORM_CHUNKS][8], float r,
+                                   const bf16x8 (&gv)[NORM_CHUNKS]) {
 #pragma unroll
   for (int c = 0; c < NORM_CHUNKS; ++c) {
     const int k0 = (c * NORM_THREADS + threadIdx.x) * 8;
     if (k0 < d) {
-      const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gain + k0);
       bf16x8 out;
 #pragma unroll
-      for (int i = 0; i < 8; ++i) out[i] = (bf16_t)(v[c][i] * r * (float)gv[i]);
+      for (int i = 0; i < 8; ++i) out[i] = (bf16_t)(v[c][i] * r * (float)gv[c][i]);
       *reinterpret_cast<bf16x8*>(x + xt_index(row, k0, d)) = out;
     }
   }
@@ -134,6 +143,10 @@ __global__ __launch_bounds__(NORM_THREADS) void finish_norm_kernel(NormArgs a, P
   const bool add = S > 0 && !frozen;
   float v[NORM_CHUNKS][8];
   float ss = 0.0f, dot = 0.0f;
+  bf16x8 gv[2][NORM_CHUNKS];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+    if (a.x[j]) load_gain(a.gain[j], d, gv[j]);
 #pragma unroll
   for (int c = 0; c < NORM_CHUNKS; ++c) {
     const int k0 = (c * NORM_THREADS + threadIdx.x) * 8;
@@ -176,7 +189,7 @@ __global__ __launch_bounds__(NORM_THREADS) void finish_norm_kernel(NormArgs a, P
   for (int j = 0; j < 2; ++j) {
     if (!a.x[j]) continue;
     const int row = a.compacted[j] ? pos : m;
-    if (row >= 0) write_x_row(a.x[j], row, d, v, r, a.gain[j]);
+    if (row >= 0) write_x_row(a.x[j], row, d, v, r, gv[j]);
   }
 }
 
@@ -201,6 +214,8 @@ __global__ __launch_bounds__(NORM_THREADS) void fill_prep_kernel(const float* h,
   }
   float v[NORM_CHUNKS][8];
   float ss = 0.0f;
+  bf16x8 gv[NORM_CHUNKS];
+  load_gain(reinterpret_cast<const bf16_t*>(gains.g[blockIdx.y]), d, gv);
 #pragma unroll
   for (int c = 0; c < NORM_CHUNKS; ++c) {
     const int k0 = (c * NORM_THREADS + threadIdx.x) * 8;
@@ -214,7 +229,7 @@ __global__ __launch_bounds__(NORM_THREADS) void fill_prep_kernel(const float* h,
     }
   }
   ss = block_sum(ss, red);
-  write_x_row(x, m, d, v, rsqrtf(ss / (float)d + eps), reinterpret_cast<const bf16_t*>(gains.g[blockIdx.y]));
+  write_x_row(x, m, d, v, rsqrtf(ss / (float)d + eps), gv);
 }
 
 // fp32 path: the three sums a one-dot-product confidence measure needs, one workgroup per row.
