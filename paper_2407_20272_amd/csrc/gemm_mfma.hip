@@ -702,8 +702,9 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
     if constexpr (!FILL && std::is_same<Epi, LmEpi>::value) {
       // LM head: two output tiles per wavefront (each LDS operand read feeds two MFMAs, half the workgroups):
       // 161 -> 153 us at 512 rows.  The same arrangement is slower for gate/up (119 -> 135 us) and is not used there.
-      // (from two 128-row chunks on: with one chunk it would halve the workgroups below the compute units)
-      if (g.n_tiles % (2 * NW) == 0 && chunks >= 2) {
+      // (from two 128-row chunks on: with one chunk it would halve the workgroups below the compute units; for the same
+      // reason not with a compacted operand, where often only the first chunk holds rows)
+      if (g.n_tiles % (2 * NW) == 0 && chunks >= 2 && !g.n_rows_dev) {
         const int groups2 = g.n_tiles / (2 * NW);
         dim3 grid2((groups2 + 7) / 8 * 8 * chunks * ksplit, 1, nz);
         hipLaunchKernelGGL((gemm_tiled_kernel<4, 2, Epi, FILL>), grid2, block, 0, st, g4, e, pred, fc);
