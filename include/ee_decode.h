@@ -193,7 +193,7 @@ int ee_exit_check(const ee_model* model, int32_t layer, const float* hidden, int
  * results as ee_exit_check without the workspace: the scratch memory is a static device array of
  * EE_NOALLOC_SCRATCH_BYTES inside the library (each GPU the library runs on holds its own copy until the process
  * ends).  The call allocates and frees nothing.  A shape and batch that need more scratch than the array holds
- * (ee_exit_check_noalloc_bytes says how much: roughly batch * (vocab / 2 + 6 * d_model) bytes for EE_BF16, batch *
+ * (ee_exit_check_noalloc_bytes says how much: roughly batch * (vocab / 2 + 2 * d_model) bytes for EE_BF16, batch *
  * 4 * (vocab + d_model) for EE_FP32) are refused with EE_ERR_WORKSPACE before anything is enqueued.
  * Every call on one GPU uses that GPU's one array: calls that overlap on a GPU (two streams, two threads) race;
  * calls on one stream are ordered and each clears what it needs to start at zero.
