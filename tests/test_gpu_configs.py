@@ -1,8 +1,8 @@
-"""Parity at the shapes of every benchmark configuration.  The oracle cannot run 32-40 layers of a 7B/13B-shaped
-model over hundreds of sequences in test time, so each case keeps the configuration's real width, batch, context
-mix, block-table structure and exit rule and reduces what the path treats uniformly: the number of layers, and
-for the check itself a seeded subset of sequences (sequences interact only through the batch exit layer, which
-is checked over the full GPU output)."""
+"""Parity at the shapes of every benchmark configuration, at REDUCED depth: each case keeps the configuration's real
+width, batch, context mix, block-table structure and exit rule and reduces the number of layers, so that many variants
+(widths, row counts, exit rules, confidence measures) run in seconds.  The same configurations at their full depth and
+size are in test_gpu_full_depth.py / test_gpu_full_depth_13b.py.  The check itself runs on a seeded subset of sequences
+(sequences interact only through the batch exit layer, which is checked over the full GPU output)."""
 import math
 
 import pytest
