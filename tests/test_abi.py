@@ -44,6 +44,13 @@ def test_workspace_sizes():
     assert L.ee_workspace_bytes(C.byref(desc(d_model=255)), 4, 64) == 0
     assert L.ee_workspace_bytes(None, 4, 64) == 0
     assert B.ee_packed_weight_bytes(64, 32) == 64 * 32 * 2
+    # bf16 path: the normalisation kernel holds a row of at most 8192 channels
+    wide = desc(n_layers=2, d_model=16384, n_heads=128, head_dim=128, d_ffn=1024, vocab=512, dtype=B.EE_BF16)
+    assert L.ee_workspace_bytes(C.byref(wide), 4, 64) == 0 and "8192" in B.ee_last_error()
+    # the allocation-free exit check says what it needs, and refuses what its static array cannot hold
+    small = L.ee_exit_check_noalloc_bytes(C.byref(big), 32)
+    assert 0 < small <= B.EE_NOALLOC_SCRATCH_BYTES < L.ee_exit_check_noalloc_bytes(C.byref(big), 512)
+    assert L.ee_exit_check_noalloc_bytes(None, 4) == 0
 
 
 @pytest.mark.parametrize("bad,code", [
@@ -113,6 +120,18 @@ def test_bad_arguments_are_rejected_before_any_launch():
     wide = B.ee_batch(2, 1, 1, 1, 20000, 17)                                          # block table wider than the LDS copy
     assert L.ee_paged_attention_decode(C.byref(d), C.byref(cache), 1, 1, C.byref(wide), 1, None, 0, None) == B.EE_ERR_UNSUPPORTED
     assert "max_blocks" in B.ee_last_error()
+    # the allocation-free variant validates like the one it mirrors, and checks the size limit on the host
+    assert L.ee_exit_check_noalloc(C.byref(model), 9, 1, 2, 0.5, None, 1, 1, 1, 1, 1, None, None, None) == B.EE_ERR_INVALID_ARG
+    assert L.ee_exit_check_noalloc(C.byref(m2), 1, 1, 2, 0.5, None, 1, 1, 1, 1, 1, None, None, None) == B.EE_ERR_UNSUPPORTED
+    assert L.ee_exit_check_noalloc(C.byref(model), 1, 1, 0, 0.5, None, 1, 1, 1, 1, 1, None, None, None) == B.EE_OK
+    big_model = B.ee_model(desc(vocab=1 << 20), 1, 1, 1, layers)
+    assert L.ee_exit_check_noalloc(C.byref(big_model), 1, 1, 64, 0.5, None, 1, 1, 1, 1, 1, None, None, None) == B.EE_ERR_WORKSPACE
+    assert "static array" in B.ee_last_error()
+    # measurement helpers
+    assert L.ee_calibration_read(None, 1 << 20, 1, 4, None) == B.EE_ERR_INVALID_ARG
+    assert L.ee_calibration_read(16, 1024, 1, 4, None) == B.EE_ERR_INVALID_ARG          # too few bytes per workgroup
+    assert L.ee_calibration_mfma(0, 10, 1, None) == B.EE_ERR_INVALID_ARG
+    assert L.ee_calibration_copy(None, 1, 4, None) == B.EE_ERR_INVALID_ARG
     assert L.ee_pack_weight(1, 33, 16, 0, 0, 1, None) == B.EE_ERR_SHAPE
     assert L.ee_pack_weight(1, 64, 16, 1, 24, 1, None) == B.EE_ERR_SHAPE
     assert L.ee_pack_weight(1, 64, 16, 9, 0, 1, None) == B.EE_ERR_INVALID_ARG
