@@ -92,9 +92,6 @@ struct Workspace {
   bf16_t* actT;       // [Mpad][f]
   float* rowsq;       // [2n + 2][Mpad]: sum of squares of the residual rows after the embedding / each update
   bf16_t* fill_x;     // [n][Mpad][d]
-  float* split_scratch;     // [d/32][1024] meeting place of the QKV tiles that two workgroups share
-  int32_t* split_counters;  // [d/32]
-  size_t zero_count;  // floats from split_scratch on that must be zero when an iteration starts
   float* dots;        // [n][Mpad] per-layer row dot products of the head-less confidence measures
   float* hprev;       // bf16: [Mpad][d], fp32: [B][d]: hidden state before the current layer (similarity measure)
   float* msr;         // fp32: [3][B] sums of the head-less confidence measures
@@ -133,10 +130,6 @@ Workspace carve(const ee_model_desc& D, int B, void* base) {
     w.actT = c.take<bf16_t>(f * Mpad);
     w.rowsq = c.take<float>((2 * n + 2) * Mpad);
     w.dots = c.take<float>(n * Mpad);
-    w.zero_count = Mpad == 32 ? (d / 32) * 1025 : 0;   // only batches of one tile split QKV tiles
-    w.split_scratch = c.take<float>(w.zero_count);
-    if (!w.zero_count) w.split_scratch = nullptr;
-    w.split_counters = reinterpret_cast<int32_t*>(w.split_scratch ? w.split_scratch + (d / 32) * 1024 : nullptr);
     w.fill_x = c.take<bf16_t>(n * Mpad * d);
     w.hprev = c.take<float>(d * Mpad);
     w.rowmap.perm = c.take<int32_t>(Mpad);
@@ -540,7 +533,7 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
   auto rs = [&](int slot) { return w.rowsq + (size_t)slot * Mpad; };
   {
     ProfScope ps(EE_K_OTHER, 0, st);
-    launch_iter_init(s, B, n, out_conf, bf ? w.split_scratch : nullptr, bf ? w.zero_count : 0, st);
+    launch_iter_init(s, B, n, out_conf, st);
     launch_rope_table(batch->context_lens, w.rope, B, D.head_dim, D.rope_theta, st);
     if (bf) {
       launch_embed_bf16(reinterpret_cast<const bf16_t*>(model->embed), batch->tokens, w.h, B, Mpad, d, D.vocab, st);
@@ -597,11 +590,8 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
       {
         ProfScope ps(EE_K_QKV, i, st);
         GemmShape gq{L.w_qkv, w.xT, d, B, 0, 3 * d / 32, D.head_dim / 2, 1};
-        if (w.split_scratch && d / 16 >= 8) {   // V tiles (the last third) halved along the contraction
-          gq.split_tiles = d / 32;
-          gq.split_scratch = w.split_scratch;
-          gq.split_counters = w.split_counters;
-        }
+        // one batch tile: each V tile (the last third; no rotation) is computed as two 16-row halves
+        if (Mpad == 32 && d / 16 >= 8) gq.split_tiles = d / 32;
         QkvEpi qe = make_qkv_epi(D, *cache, *batch, w, i, w.q);
         launch_gemm_qkv_bf16(gq, qe, run_layers, st, have_pending ? &pending : nullptr,
                              have_pending_dot ? &pending_dot : nullptr);

@@ -128,8 +128,7 @@ struct Pred {
 };
 
 // misc.hip
-void launch_iter_init(const IterState& s, int B, int n_layers, float* conf_out, float* zero_buf, size_t zero_count,
-                      hipStream_t st);
+void launch_iter_init(const IterState& s, int B, int n_layers, float* conf_out, hipStream_t st);
 void launch_embed_bf16(const bf16_t* E, const int32_t* tokens, float* h, int B, int Mpad, int d, int vocab, hipStream_t st);
 void launch_embed_f32(const float* E, const int32_t* tokens, float* h, int B, int d, int vocab, hipStream_t st);
 void launch_copy_f32(const float* src, float* dst, size_t n, hipStream_t st);
@@ -236,11 +235,9 @@ struct GemmShape {
   int n_tiles;      // tiles to compute
   int pair_stride;  // row order of the packed matrix
   int unused_;      // (kept so that aggregate initialisers stay positional)
-  // QKV projection with one batch tile: the last split_tiles tiles are each computed by two workgroups (half the
-  // contraction each, dispatched first) that meet in split_scratch; see gemm_mfma.hip.  0 = off.
+  // QKV projection with one batch tile: the last split_tiles tiles (tiles without a rotation: V) are each computed
+  // by two workgroups, 16 of the 32 output rows each, dispatched first; see gemm_mfma.hip.  0 = off.
   int split_tiles;
-  float* split_scratch;      // [split_tiles][1024] floats, zero before the launch, left at zero
-  int32_t* split_counters;   // [split_tiles], zero before the launch, left at zero
   // Tiled kernel only: nullptr, or the device-side number of valid operand rows (<= M).  Row chunks beyond it
   // return at once, rows beyond it are not written.
   const int32_t* n_rows_dev;

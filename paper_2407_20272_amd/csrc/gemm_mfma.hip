@@ -64,7 +64,7 @@ __device__ inline bool fill_skip(const Pred& pred, const QkvEpi& e, int M, int l
 // the upper row group): the two rows that an epilogue needs together always sit in the same thread.
 template <class Epi>
 __device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, const GemmShape& g, const Epi& e, Lds& s,
-                                   int wave, int lane, bool half_tile = false) {
+                                   int wave, int lane, int row_half = -1) {
   __syncthreads();
 #pragma unroll
   for (int a = 0; a < 16; ++a) s.red[wave][a][lane] = acc[a];
@@ -118,30 +118,6 @@ __device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, con
     }
   } else {
     if constexpr (std::is_same<Epi, QkvEpi>::value) {
-      if (half_tile) {
-        // This workgroup summed half of the contraction; its partner the other half.  Both add their halves into
-        // a zeroed scratch tile with device-scope atomics, wait until the adds are performed and bump the tile's
-        // counter; the second to arrive takes the sums back out (leaving zeros) and finishes the tile.  Two
-        // addends, so the result does not depend on who comes first.
-        const int tl = nt - (g.tile_begin + g.n_tiles - g.split_tiles);
-        float* sc = g.split_scratch + (size_t)tl * 1024 + threadIdx.x;
-        unsafeAtomicAdd(sc, vlo[0]);
-        unsafeAtomicAdd(sc + 256, vhi[0]);
-        unsafeAtomicAdd(sc + 512, vlo[1]);
-        unsafeAtomicAdd(sc + 768, vhi[1]);
-        __builtin_amdgcn_s_waitcnt(0);
-        __syncthreads();
-        if (threadIdx.x == 0) s.flag = atomicAdd(g.split_counters + tl, 1);
-        __syncthreads();
-        if (s.flag == 0) return;
-        vlo[0] = atomicExch(sc, 0.0f);
-        vhi[0] = atomicExch(sc + 256, 0.0f);
-        vlo[1] = atomicExch(sc + 512, 0.0f);
-        vhi[1] = atomicExch(sc + 768, 0.0f);
-        if (threadIdx.x == 0) g.split_counters[tl] = 0;
-      }
-    }
-    if constexpr (std::is_same<Epi, QkvEpi>::value) {
       // The tile holds, for each of its 32 batch rows, 16 consecutive channels of one head and their 16 rotary
       // partners (half a head further on).  Rotate in registers, stage the tile in LDS, then write whole 16-channel
       // runs (one 16-byte store per thread) instead of single elements scattered over the cache blocks.
@@ -182,7 +158,9 @@ __device__ inline void tile_finish(const f32x16& acc, int nt, int mt_global, con
       } else if (threadIdx.x < 128) {   // thread -> (row, run, half of the run): eight bf16
         const int mr = threadIdx.x >> 2, part = threadIdx.x & 3, run = part >> 1, c0 = run * 16 + (part & 1) * 8;
         const int mm = mt_global * 32 + mr;
-        if (mm < g.M && !(e.fill_from && !(e.fill_from[(size_t)mm * e.fill_from_stride] < e.layer))) {
+        // a workgroup that computed one half of the tile's rows (row_half) holds one of the two runs only
+        if (mm < g.M && (row_half < 0 || run == row_half) &&
+            !(e.fill_from && !(e.fill_from[(size_t)mm * e.fill_from_stride] < e.layer))) {
           const int p = e.context_lens[mm];
           const bool p_ok = (unsigned)p < (unsigned)(e.max_blocks * 16);
           const int blk = e.block_tables[(size_t)(e.row_table ? safe_row(e.row_table[mm], e.table_rows) : mm) * e.max_blocks + (p_ok ? p >> 4 : 0)];
@@ -298,12 +276,14 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  // Tiles that two workgroups share come first in the grid (two consecutive block indices per tile, each half of
-  // the contraction): they are done, and their meeting in scratch memory is over, while the whole tiles still
-  // stream.  With 384 tiles on 256 compute units this turns two rounds of workgroups into one and a half.
+  // Tiles that two workgroups share come first in the grid (two consecutive block indices per tile): each computes
+  // 16 of the tile's 32 output rows, i.e. one of its two 16-channel runs, over the whole contraction, from the half
+  // of every weight tile that holds those rows (two 256-byte pieces of each kilobyte).  Both halves are complete
+  // results: the workgroups share nothing and never meet.  With 384 tiles on 256 compute units this turns two rounds
+  // of workgroups into one and a half.  Only tiles without a rotation may be split (V: the host sees to that).
   const bool half_tile = bx < 2 * g.split_tiles;
   int tl = half_tile ? bx >> 1 : bx - 2 * g.split_tiles;   // tile within its class (halved / whole)
-  int khalf = bx & 1;
+  int rhalf = bx & 1;
   if constexpr (std::is_same<Epi, QkvEpi>::value) {
     // Four consecutive tiles hold the 128 channels of one head (or two heads of 64): each writes 32-byte runs of
     // the same cache lines of the paged cache (64-byte runs of q).  Workgroup ids congruent modulo 8 run on the
@@ -314,23 +294,25 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
       if (bx < ((2 * g.split_tiles) & ~63)) {
         const int q = (bx >> 3) & 7;
         tl = (((bx >> 6) << 3) + (bx & 7)) * 4 + (q >> 1);
-        khalf = q & 1;
+        rhalf = q & 1;
       }
     } else if (tl < ((g.n_tiles - g.split_tiles) & ~31)) {
       tl = (tl & ~31) + ((tl & 7) << 2) + ((tl >> 3) & 3);
     }
   }
   const int nt = half_tile ? g.tile_begin + g.n_tiles - g.split_tiles + tl : g.tile_begin + tl;
-  const int nslices = half_tile ? 2 : 1;
   const int k_steps = g.K >> 4;
-  const int chunks = gridDim.y * nslices * NW;
-  const int c = (blockIdx.y * nslices + (half_tile ? khalf : 0)) * NW + wave;
+  const int chunks = gridDim.y * NW;
+  const int c = blockIdx.y * NW + wave;
   const int ks0 = (int)((long)k_steps * c / chunks);
   const int ks1 = (int)((long)k_steps * (c + 1) / chunks);
   const int m_tiles = (g.M + 31) >> 5;
   const size_t x_tile_stride = (size_t)k_steps * 64;
 
-  const u32x4* wp = reinterpret_cast<const u32x4*>(g.w) + (size_t)nt * k_steps * 64 + lane;
+  // Lane l of a weight tile holds row l % 32.  In a halved tile the lanes of the other 16 rows fetch what their
+  // partner lanes fetch (the same bytes, no further memory traffic): their result rows are duplicates, never written.
+  const int wlane = half_tile ? ((lane & ~16) | (rhalf << 4)) : lane;
+  const u32x4* wp = reinterpret_cast<const u32x4*>(g.w) + (size_t)nt * k_steps * 64 + wlane;
 
   for (int mt0 = 0; mt0 < m_tiles; mt0 += MT) {
     const u32x4* xp = reinterpret_cast<const u32x4*>(g.x) + (size_t)mt0 * x_tile_stride + lane;
@@ -364,7 +346,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
       frag_mma(A, acc);
     }
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) tile_finish(acc[mt], nt, mt0 + mt, g, e, s, wave, lane, half_tile);
+    for (int mt = 0; mt < MT; ++mt) tile_finish(acc[mt], nt, mt0 + mt, g, e, s, wave, lane, half_tile ? rhalf : -1);
   }
 }
 

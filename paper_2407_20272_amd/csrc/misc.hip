@@ -7,9 +7,9 @@ namespace ee {
 namespace {
 
 // ---------------------------------------------------------------------------------------------------
-// Status <- False for every sequence (Algorithm 1, initialisation), counters, scratch that must start at 0.
+// Status <- False for every sequence (Algorithm 1, initialisation), counters.
 // ---------------------------------------------------------------------------------------------------
-__global__ void iter_init_kernel(IterState s, int B, int n_layers, float* conf_out, float* zero_buf, size_t zero_count) {
+__global__ void iter_init_kernel(IterState s, int B, int n_layers, float* conf_out) {
   const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (size_t i = t; i < (size_t)B; i += stride) {
@@ -23,7 +23,6 @@ __global__ void iter_init_kernel(IterState s, int B, int n_layers, float* conf_o
   }
   if (conf_out)
     for (size_t i = t; i < (size_t)B * n_layers; i += stride) conf_out[i] = __builtin_nanf("");
-  for (size_t i = t; i < zero_count; i += stride) zero_buf[i] = 0.0f;
 }
 
 // hidden_states <- Embed(input_tokens): one row gather per sequence; padding rows of the last tile are zero.
@@ -346,14 +345,12 @@ __global__ __launch_bounds__(256) void decide_kernel(DecideArgs a, Pred pred) {
 
 }  // namespace
 
-void launch_iter_init(const IterState& s, int B, int n_layers, float* conf_out, float* zero_buf, size_t zero_count,
-                      hipStream_t st) {
+void launch_iter_init(const IterState& s, int B, int n_layers, float* conf_out, hipStream_t st) {
   size_t work = (size_t)B * n_layers;
-  if (zero_count > work) work = zero_count;
   int blocks = (int)((work + 255) / 256);
   if (blocks < 1) blocks = 1;
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(iter_init_kernel, dim3(blocks), dim3(256), 0, st, s, B, n_layers, conf_out, zero_buf, zero_count);
+  hipLaunchKernelGGL(iter_init_kernel, dim3(blocks), dim3(256), 0, st, s, B, n_layers, conf_out);
 }
 void launch_embed_bf16(const bf16_t* E, const int32_t* tokens, float* h, int B, int Mpad, int d, int vocab, hipStream_t st) {
   hipLaunchKernelGGL(embed_bf16_kernel, dim3(Mpad), dim3(256), 0, st, E, tokens, h, B, d, vocab);
