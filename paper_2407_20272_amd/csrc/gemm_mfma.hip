@@ -508,6 +508,18 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
               acc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wcur[t][u]),
                                                                    __builtin_bit_cast(bf16x8, bf[u & 1][mt]), acc[t][mt], 0, 0, 0);
         }
+        if constexpr (MT >= 4) {
+          // Order of the group, spelled out for the scheduler: the first step's fragments, then one fragment read
+          // of the next step behind every NTW multiplies, the last step's multiplies.  Left alone it issues each
+          // read right in front of the multiplies that use it and the matrix cores wait out every LDS round trip.
+          __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);
+#pragma unroll
+          for (int i = 0; i < (UT - 1) * MT; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, NTW, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+          }
+          __builtin_amdgcn_sched_group_barrier(0x008, MT * NTW, 0);
+        }
       }
     };
 
