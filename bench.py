@@ -119,6 +119,10 @@ def measure_peaks(torch, B):
         wgs = 256 * per_simd
         t = timed(lambda i=0: B.ee_calibration_mfma(wgs, iters, sink), 3)
         out[f"mfma_bf16_TFLOPs_{per_simd}_wavefront_per_simd"] = wgs * 4 * iters * 4 * 2.0 * 32 * 32 * 16 / t / 1e12
+    steps = 8000
+    for reads in (0, 8):   # the inner loop of a 128 x 128 wavefront tile alone, one workgroup per compute unit
+        t = timed(lambda i=0: B.ee_calibration_mfma_tile(256, steps, reads, sink), 3)
+        out[f"mfma_bf16_TFLOPs_4x4_tile_loop_{reads}_lds_fragment_reads_per_step"] = 256 * 4 * steps * 16 * 2.0 * 32 * 32 * 16 / t / 1e12
     out["note"] = "library calibration kernels, HIP events; published peaks: HBM 8000 GB/s, bf16 MFMA 2500 TFLOP/s"
     return out
 

@@ -247,9 +247,15 @@ int ee_calibration_copy(const float* src, float* dst, size_t n_floats, void* str
  *   wavefronts, each wavefront walking one contiguous piece with 16 KiB in flight; `sink` (dev, 16 bytes) is written only
  *   if the exclusive-or of a wavefront's words equals one fixed pattern.  Traffic: `bytes` read, nothing written.
  * ee_calibration_mfma: `workgroups` x 4 wavefronts each issue 4 * iterations 32x32x16 bf16 matrix instructions on
- *   registers (2 * 32 * 32 * 16 flop each), no memory traffic; `sink` (dev, 1 KiB) is never written. */
+ *   registers (2 * 32 * 32 * 16 flop each), no memory traffic; `sink` (dev, 1 KiB) is never written.
+ * ee_calibration_mfma_tile: the inner loop of a 128 x 128 wavefront tile alone: `workgroups` x 4 wavefronts (96 KiB of LDS
+ *   each: one workgroup per compute unit) run `steps` (even, >= 2) contraction steps of 16 such instructions on 4 x 4
+ *   accumulators; with `lds_fragment_reads` = 8 every step also reads the next step's 4 + 4 operand fragments (1 KiB
+ *   each) from LDS, with 0 it reads none.  No global memory traffic in the loop; `sink` (dev, 1 KiB) is never written.
+ *   Errors: EE_ERR_INVALID_ARG for a NULL sink, an odd or too small step count, another number of reads. */
 int ee_calibration_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream);
 int ee_calibration_mfma(int32_t workgroups, int32_t iterations, float* sink, void* stream);
+int ee_calibration_mfma_tile(int32_t workgroups, int32_t steps, int32_t lds_fragment_reads, float* sink, void* stream);
 int ee_profile_enable(int32_t on);
 int ee_profile_read(int32_t* kernel_class /*host*/, int32_t* layer /*host*/, float* ms /*host*/, int32_t max_records);
 

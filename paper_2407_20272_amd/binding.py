@@ -20,7 +20,8 @@ EE_FP32, EE_BF16 = 0, 1
 EE_PACK_PLAIN, EE_PACK_QKV, EE_PACK_GATE_UP = 0, 1, 2
 EXPORTS = ["ee_last_error", "ee_packed_weight_bytes", "ee_pack_weight", "ee_workspace_bytes", "ee_decode_iteration",
            "ee_exit_check", "ee_kv_fill", "ee_paged_attention_decode", "ee_profile_enable", "ee_profile_read", "ee_calibration_copy",
-           "ee_noalloc_init", "ee_exit_check_noalloc_bytes", "ee_exit_check_noalloc", "ee_calibration_read", "ee_calibration_mfma"]
+           "ee_noalloc_init", "ee_exit_check_noalloc_bytes", "ee_exit_check_noalloc", "ee_calibration_read", "ee_calibration_mfma",
+           "ee_calibration_mfma_tile"]
 EE_NOALLOC_SCRATCH_BYTES = 8 << 20
 KERNEL_CLASSES = ["norm", "qkv", "attention", "o_proj", "gate_up", "down", "head", "combine", "kv_fill", "other"]
 
@@ -93,6 +94,8 @@ def lib() -> C.CDLL:
         L.ee_calibration_read.restype = C.c_int
         L.ee_calibration_mfma.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.ee_calibration_mfma.restype = C.c_int
+        L.ee_calibration_mfma_tile.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+        L.ee_calibration_mfma_tile.restype = C.c_int
         L.ee_profile_enable.argtypes = [C.c_int32]
         L.ee_profile_read.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int32]
         L.ee_profile_enable.restype = C.c_int
@@ -313,3 +316,8 @@ def ee_calibration_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int):
 def ee_calibration_mfma(workgroups: int, iterations: int, sink: torch.Tensor):
     assert sink.dtype == torch.float32 and sink.numel() >= 256
     _check(lib().ee_calibration_mfma(workgroups, iterations, _ptr(sink), _stream()))
+
+
+def ee_calibration_mfma_tile(workgroups: int, steps: int, lds_fragment_reads: int, sink: torch.Tensor):
+    assert sink.dtype == torch.float32 and sink.numel() >= 256
+    _check(lib().ee_calibration_mfma_tile(workgroups, steps, lds_fragment_reads, _ptr(sink), _stream()))

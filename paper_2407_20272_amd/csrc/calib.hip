@@ -52,6 +52,56 @@ __global__ __launch_bounds__(256) void mfma_kernel(float* sink, int iters) {
   if (s == 1.2345f) sink[threadIdx.x] = s;   // never true for these operands; keeps the loop alive
 }
 
+// The inner loop of a 128 x 128 wavefront tile with nothing around it: per contraction step 16 MFMAs on 4 x 4
+// accumulators and, if READS, the 4 + 4 operand fragments of the next step read from LDS (1 KiB each, the
+// fragment order of the projection kernels) while the current step is multiplied.  Four wavefronts per
+// workgroup, 96 KiB of LDS so that one workgroup runs per compute unit.  No global memory traffic in the loop.
+template <bool READS>
+__global__ __launch_bounds__(256) void mfma_tile_kernel(float* sink, int iters) {
+  extern __shared__ u32x4 frag_lds[];   // 64 KiB are read: four stages of 16 fragments
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  for (int i = threadIdx.x; i < 64 * 1024 / 16; i += blockDim.x)
+    frag_lds[i] = u32x4{0x3c003c00u + (unsigned)i, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+  __syncthreads();
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+  u32x4 fa[2][4], fb[2][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    fa[0][a] = fa[1][a] = frag_lds[a * 64 + lane];
+    fb[0][a] = fb[1][a] = frag_lds[(8 + a) * 64 + lane];
+  }
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      if (READS) {
+        const u32x4* st = frag_lds + (size_t)(((it * 2 + u) & 3) * 16) * 64 + lane;
+#pragma unroll
+        for (int a = 0; a < 4; ++a) fa[(u + 1) & 1][a] = st[((wave & 1) * 4 + a) * 64];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) fb[(u + 1) & 1][b] = st[(8 + (wave >> 1) * 4 + b) * 64];
+      }
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[u & 1][a]),
+                                                              __builtin_bit_cast(bf16x8, fb[u & 1][b]), acc[a][b], 0, 0, 0);
+    }
+  }
+  float r = 0.0f;
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) r += acc[a][b][0] + acc[a][b][15];
+  if (r == 1.2345f) sink[threadIdx.x] = r;   // practically never true; keeps the loop alive
+}
+
 }  // namespace
 }  // namespace ee
 
@@ -72,6 +122,22 @@ int ee_calibration_read(const void* src, size_t bytes, void* sink, int32_t workg
 int ee_calibration_mfma(int32_t workgroups, int32_t iterations, float* sink, void* stream) {
   if (!sink || workgroups < 1 || iterations < 1) EE_FAIL(EE_ERR_INVALID_ARG, "ee_calibration_mfma: bad argument");
   hipLaunchKernelGGL(mfma_kernel, dim3(workgroups), dim3(256), 0, reinterpret_cast<hipStream_t>(stream), sink, iterations);
+  EE_HIP(hipGetLastError());
+  return EE_OK;
+}
+
+int ee_calibration_mfma_tile(int32_t workgroups, int32_t steps, int32_t lds_fragment_reads, float* sink, void* stream) {
+  if (!sink || workgroups < 1 || steps < 2 || (steps & 1) || (lds_fragment_reads != 0 && lds_fragment_reads != 8))
+    EE_FAIL(EE_ERR_INVALID_ARG, "ee_calibration_mfma_tile: steps must be even and >= 2, lds_fragment_reads 0 or 8");
+  const size_t lds = 96 * 1024;
+  auto st = reinterpret_cast<hipStream_t>(stream);
+  if (lds_fragment_reads) {
+    EE_HIP(hipFuncSetAttribute((const void*)mfma_tile_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(mfma_tile_kernel<true>, dim3(workgroups), dim3(256), lds, st, sink, steps / 2);
+  } else {
+    EE_HIP(hipFuncSetAttribute((const void*)mfma_tile_kernel<false>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(mfma_tile_kernel<false>, dim3(workgroups), dim3(256), lds, st, sink, steps / 2);
+  }
   EE_HIP(hipGetLastError());
   return EE_OK;
 }

@@ -131,6 +131,9 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert L.ee_calibration_read(None, 1 << 20, 1, 4, None) == B.EE_ERR_INVALID_ARG
     assert L.ee_calibration_read(16, 1024, 1, 4, None) == B.EE_ERR_INVALID_ARG          # too few bytes per workgroup
     assert L.ee_calibration_mfma(0, 10, 1, None) == B.EE_ERR_INVALID_ARG
+    assert L.ee_calibration_mfma_tile(4, 3, 8, 1, None) == B.EE_ERR_INVALID_ARG       # odd step count
+    assert L.ee_calibration_mfma_tile(4, 4, 5, 1, None) == B.EE_ERR_INVALID_ARG       # 0 or 8 fragment reads only
+    assert L.ee_calibration_mfma_tile(4, 4, 8, None, None) == B.EE_ERR_INVALID_ARG
     assert L.ee_calibration_copy(None, 1, 4, None) == B.EE_ERR_INVALID_ARG
     assert L.ee_pack_weight(1, 33, 16, 0, 0, 1, None) == B.EE_ERR_SHAPE
     assert L.ee_pack_weight(1, 64, 16, 1, 24, 1, None) == B.EE_ERR_SHAPE
