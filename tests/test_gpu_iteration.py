@@ -30,6 +30,21 @@ def test_tiny_fp32_full_trajectory_matches_oracle_and_stored_values():
     assert stats["L"] == want["batch_exit_layer"]
 
 
+def test_tiny_fp32_untied_head_trajectory_with_varying_tokens():
+    """The tiny shape with an untied head and wider weights (the stored second trajectory): every step emits a
+    different token per sequence, the batch leaves at layers 2, 3 and 4; all 16 steps, zero tolerated divergences."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(HERE, "golden", "make_golden.py"))
+    gen = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(gen)
+    cfg, seed = gen.case("tiny_fp32_untied_seed4")
+    stats = lockstep(cfg, seed=seed, steps=cfg.decode_steps, gain_jitter=0.0)
+    assert stats["near_threshold"] == 0 and stats["near_tie"] == 0
+    with open(os.path.join(HERE, "golden", "tiny_fp32_untied_seed4.json")) as f:
+        want = json.load(f)
+    assert stats["L"] == want["batch_exit_layer"]
+
+
 @pytest.mark.parametrize("seed", [1, 2])
 def test_tiny_fp32_other_seeds_with_gain_jitter(seed):
     stats = lockstep(TINY.with_(decode_steps=6, weight_std=0.05, logit_scale=1.0, threshold=0.3), seed=seed, steps=6)
