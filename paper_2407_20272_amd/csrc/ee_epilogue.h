@@ -144,6 +144,9 @@ struct HeadStat {
   float zmax, sum, z2;
   int idx;
 };
+// exp of a non-positive argument for the softmax sums: the hardware's base-2 exponential (relative error about 1e-7;
+// the library routine costs several times the instructions, and an exit head evaluates one per logit and row)
+__device__ inline float stat_exp(float x) { return __expf(x); }
 __device__ inline HeadStat stat_empty() { return {-INFINITY, 0.0f, -INFINITY, 0x7fffffff}; }
 __device__ inline HeadStat stat_merge(const HeadStat& a, const HeadStat& b, float scale) {
   HeadStat o;
@@ -156,8 +159,8 @@ __device__ inline HeadStat stat_merge(const HeadStat& a, const HeadStat& b, floa
     o.idx = b.idx;
     o.z2 = fmaxf(b.z2, a.zmax);
   }
-  const float wa = a.sum > 0.0f ? a.sum * expf(scale * (a.zmax - o.zmax)) : 0.0f;
-  const float wb = b.sum > 0.0f ? b.sum * expf(scale * (b.zmax - o.zmax)) : 0.0f;
+  const float wa = a.sum > 0.0f ? a.sum * stat_exp(scale * (a.zmax - o.zmax)) : 0.0f;
+  const float wb = b.sum > 0.0f ? b.sum * stat_exp(scale * (b.zmax - o.zmax)) : 0.0f;
   o.sum = wa + wb;
   return o;
 }
@@ -189,7 +192,7 @@ __device__ inline HeadStat stat_of_8x4(const float (&z)[4], int idx0, float scal
   float sum = 0.0f, z2 = -INFINITY;
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    sum += expf(scale * (z[i] - best));
+    sum += stat_exp(scale * (z[i] - best));
     if (idx0 + i != bi) z2 = fmaxf(z2, z[i]);
   }
 #pragma unroll
@@ -215,7 +218,7 @@ __device__ inline HeadStat stat_of(const float (&z)[N], const int (&idx)[N], flo
   float sum = 0.0f, z2 = -INFINITY;
 #pragma unroll
   for (int i = 0; i < N; ++i) {
-    sum += expf(scale * (z[i] - best));
+    sum += stat_exp(scale * (z[i] - best));
     if (idx[i] != bi) z2 = fmaxf(z2, z[i]);
   }
   return {best, sum, z2, bi};

@@ -362,6 +362,73 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmShape g, Epi e, Pred
 constexpr int UT = 4;
 __device__ u32x4 k_zero_tile[64];   // one operand tile of zeros, never written (activation rows past the contraction range; not const: it must live in the same address space as the operands)
 
+// Epilogue of one finished 32 x 32 result tile held in a wavefront's registers (tiled and ring kernels): accumulator a
+// (< 8) of a lane is result row r16 = (a/4)*8 + (lane/32)*4 + a%4 of column lane%32, accumulator a+8 is row r16+16 (its
+// partner row in the packed order).  nt: packed weight tile, mtile: 32-row batch tile, M_eff: valid rows, ksl: the
+// contraction slice this workgroup summed (accumulate projections).
+template <class Epi>
+__device__ inline void finish_from_registers(const f32x16& acc, int nt, int mtile, int M_eff, int ksl, const GemmShape& g,
+                                             const Epi& e, int lane) {
+  const int half = lane >> 5, ml = lane & 31;
+  const int m = mtile * 32 + ml;
+  if constexpr (std::is_same<Epi, LmEpi>::value) {
+    // this lane's 16 logits of the row in ascending vocabulary order: rows r16(a), a = 0..7, then r16(a)+16
+    float z[16];
+    int zi[16];
+    const float rs = m < M_eff ? row_rinv(e.rowsq, e.perm ? e.perm[m] : m, e.d_model, e.eps) : 0.0f;
+#pragma unroll
+    for (int a = 0; a < 8; ++a) {
+      const int r16 = (a >> 2) * 8 + half * 4 + (a & 3);
+      z[a] = acc[a] * rs;
+      zi[a] = nt * 32 + r16;
+      z[a + 8] = acc[a + 8] * rs;
+      zi[a + 8] = nt * 32 + r16 + 16;
+    }
+    HeadStat st = stat_of<16>(z, zi, e.scale);
+    HeadStat o;
+    o.zmax = __shfl_xor(st.zmax, 32);
+    o.sum = __shfl_xor(st.sum, 32);
+    o.z2 = __shfl_xor(st.z2, 32);
+    o.idx = __shfl_xor(st.idx, 32);
+    st = stat_merge(st, o, e.scale);
+    if (half == 0 && m < M_eff) {
+      const int row = e.perm ? e.perm[m] : m;
+      e.partials[(size_t)row * e.n_parts + (nt - g.tile_begin)] = stat_pack(st);
+    }
+  } else if constexpr (std::is_same<Epi, AccEpi>::value) {
+    // this workgroup's contraction slice (ksl) of the partial results, plain 16-byte stores: a lane holds, for its
+    // batch row, two runs of four consecutive channels and the two runs 16 channels further on
+    if (m < M_eff) {
+      float* row = e.h + ((size_t)ksl * e.Mpad + m) * e.n_out + nt * 32 + half * 4;
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        *reinterpret_cast<float4*>(row + q * 8) = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+        *reinterpret_cast<float4*>(row + q * 8 + 16) =
+            make_float4(acc[4 * q + 8], acc[4 * q + 9], acc[4 * q + 10], acc[4 * q + 11]);
+      }
+    }
+  } else {
+    if (m < M_eff) {
+      // this lane holds two runs of four consecutive output rows (and their partners 16 rows on) of its batch row
+#pragma unroll
+      for (int run = 0; run < 2; ++run) {
+        const int f_lo0 = packed_row_lo(nt, run * 8 + half * 4, g.pair_stride);
+        float lo[4], hi[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          lo[i] = acc[run * 4 + i];
+          hi[i] = acc[run * 4 + i + 8];
+        }
+        if constexpr (std::is_same<Epi, QkvEpi>::value) {
+          epi_qkv4(e, m, f_lo0, lo, hi);
+        } else {
+          epi_gateup4(e, m, f_lo0, lo, hi);
+        }
+      }
+    }
+  }
+}
+
 template <int MT>
 struct TiledLds {
   u32x4 b[2][UT][MT][64];
@@ -540,86 +607,138 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(GemmShape g, Epi e, Pre
     return;       // nothing to finish; the epilogues below take no workgroup barrier
   }
 
-  // epilogue from registers: accumulator a (< 8) of a lane is result row r16 = (a/4)*8 + (lane/32)*4 + a%4 of
-  // column lane%32, accumulator a+8 is row r16+16 (its partner row in the packed order)
-  const int half = lane >> 5, ml = lane & 31;
-  if constexpr (std::is_same<Epi, LmEpi>::value) {
+  // every wavefront finishes its own tiles from registers
 #pragma unroll
-    for (int t = 0; t < NTW; ++t)
+  for (int t = 0; t < NTW; ++t)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int nt = nt0 + t;
-        // this lane's 16 logits of the row in ascending vocabulary order: rows r16(a), a = 0..7, then r16(a)+16
-        float z[16];
-        int zi[16];
-        const int mrow = (chunk * MT + mt) * 32 + ml;
-        const float rs = mrow < M_eff ? row_rinv(e.rowsq, e.perm ? e.perm[mrow] : mrow, e.d_model, e.eps) : 0.0f;
+    for (int mt = 0; mt < MT; ++mt) finish_from_registers(acc[t][mt], nt0 + t, chunk * MT + mt, M_eff, ksl, g, e, lane);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Main loop 3 (LM head and gate/up at 385 to 512 rows, where the matrix cores are what counts): one workgroup owns a
+// 256-row x 256-column block of the result (eight batch tiles x eight weight tiles).  Wavefront w owns two weight
+// tiles (64 columns) against all eight batch tiles, 16 accumulator tiles = all 256 accumulation registers:
+//   * its weight fragments come straight from HBM into registers, RING_D contraction steps ahead (nobody else in
+//     the workgroup needs them, so they never touch LDS);
+//   * the activation fragments of a step (8 KiB, needed by all four wavefronts) land in a ring of RING_D + 1 LDS
+//     slots through direct-to-LDS loads, two tiles per wavefront, just as far ahead: a wavefront's loads complete
+//     in order, so a fragment from L2 queued behind a weight tile from HBM is ready no sooner than that tile and must
+//     have been asked for as early;
+//   * one bare barrier per contraction step (a fence would wait for every load in flight): at step s every
+//     wavefront has waited for its own two tiles of step s+1, and the slot of step s-1, whose fragments everybody
+//     has multiplied, takes step s+RING_D.
+// Per compute unit and step: 16 KiB from memory, 8 KiB written to and 32 KiB read from LDS, 64 MFMAs.  Every weight
+// byte leaves HBM once: the two row blocks of a column block run on one XCD and meet in its L2.
+// ---------------------------------------------------------------------------------------------------------
+constexpr int RING_D = 15;
+constexpr int RING_LDS_BYTES = (RING_D + 1) * 8 * 1024;
+typedef __attribute__((address_space(3))) void* lds_void_ptr;
+typedef __attribute__((address_space(1))) const void* global_void_ptr;
+template <int N>
+__device__ inline void wait_loads_but() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+
+template <class Epi>
+__global__ __launch_bounds__(256) void gemm_ring_kernel(GemmShape g, Epi e, Pred pred) {
+  extern __shared__ u32x4 ring[];   // [RING_D + 1][8 batch tiles][64 lanes]
+  if (pred_skip(pred)) return;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m_tiles = (g.M + 31) >> 5;
+  const int row_blocks = (m_tiles + 7) >> 3, col_blocks = g.n_tiles >> 3;
+  // ids congruent modulo 8 share an XCD: the row blocks of one column block get consecutive ids of one class
+  const int xcd = (int)blockIdx.x & 7, j = (int)blockIdx.x >> 3;
+  const int bm = j % row_blocks, bn = (j / row_blocks) * 8 + xcd;
+  if (bn >= col_blocks) return;
+  const int M_eff = g.M;            // (compacted operands stay with the tiled kernel, which skips empty 128-row chunks)
+  const int k_steps = g.K >> 4;     // a multiple of RING_D + 1 (the host checks)
+  const int nt0 = g.tile_begin + bn * 8 + wave * 2;
+  const u32x4* wsrc[2];
+  const u32x4* xsrc[2];
 #pragma unroll
-        for (int a = 0; a < 8; ++a) {
-          const int r16 = (a >> 2) * 8 + half * 4 + (a & 3);
-          z[a] = acc[t][mt][a] * rs;
-          zi[a] = nt * 32 + r16;
-          z[a + 8] = acc[t][mt][a + 8] * rs;
-          zi[a + 8] = nt * 32 + r16 + 16;
-        }
-        HeadStat st = stat_of<16>(z, zi, e.scale);
-        HeadStat o;
-        o.zmax = __shfl_xor(st.zmax, 32);
-        o.sum = __shfl_xor(st.sum, 32);
-        o.z2 = __shfl_xor(st.z2, 32);
-        o.idx = __shfl_xor(st.idx, 32);
-        st = stat_merge(st, o, e.scale);
-        const int m = (chunk * MT + mt) * 32 + ml;
-        if (half == 0 && m < M_eff) {
-          const int row = e.perm ? e.perm[m] : m;
-          e.partials[(size_t)row * e.n_parts + (nt - g.tile_begin)] = stat_pack(st);
-        }
-      }
-  } else if constexpr (std::is_same<Epi, AccEpi>::value) {
-    // this workgroup's contraction slice (ksl) of the partial results, plain 16-byte stores: a lane holds, for its
-    // batch row, two runs of four consecutive channels and the two runs 16 channels further on
-#pragma unroll
-    for (int t = 0; t < NTW; ++t)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int m = (chunk * MT + mt) * 32 + ml;
-        if (m < M_eff) {
-          float* row = e.h + ((size_t)ksl * e.Mpad + m) * e.n_out + (nt0 + t) * 32 + half * 4;
-#pragma unroll
-          for (int q = 0; q < 2; ++q) {
-            *reinterpret_cast<float4*>(row + q * 8) =
-                make_float4(acc[t][mt][4 * q], acc[t][mt][4 * q + 1], acc[t][mt][4 * q + 2], acc[t][mt][4 * q + 3]);
-            *reinterpret_cast<float4*>(row + q * 8 + 16) =
-                make_float4(acc[t][mt][4 * q + 8], acc[t][mt][4 * q + 9], acc[t][mt][4 * q + 10], acc[t][mt][4 * q + 11]);
-          }
-        }
-      }
-  } else {
-#pragma unroll
-    for (int t = 0; t < NTW; ++t)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const int m = (chunk * MT + mt) * 32 + ml;
-        if (m < M_eff) {
-          // this lane holds two runs of four consecutive output rows (and their partners 16 rows on) of its batch row
-#pragma unroll
-          for (int run = 0; run < 2; ++run) {
-            const int f_lo0 = packed_row_lo(nt0 + t, run * 8 + half * 4, g.pair_stride);
-            float lo[4], hi[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              lo[i] = acc[t][mt][run * 4 + i];
-              hi[i] = acc[t][mt][run * 4 + i + 8];
-            }
-            if constexpr (std::is_same<Epi, QkvEpi>::value) {
-              epi_qkv4(e, m, f_lo0, lo, hi);
-            } else {
-              epi_gateup4(e, m, f_lo0, lo, hi);
-            }
-          }
-        }
-      }
+  for (int i = 0; i < 2; ++i) {
+    wsrc[i] = reinterpret_cast<const u32x4*>(g.w) + (size_t)(nt0 + i) * k_steps * 64 + lane;
+    xsrc[i] = reinterpret_cast<const u32x4*>(g.x) + (size_t)min(bm * 8 + wave * 2 + i, m_tiles - 1) * k_steps * 64 + lane;
   }
+  // Exactly four loads per wavefront and step, in this order; steps past the end repeat the last one (never used).
+  auto issue = [&](int s, u32x4 (&wr)[2], int slot) {
+    const int ss = s < k_steps ? s : k_steps - 1;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) wr[i] = __builtin_nontemporal_load(wsrc[i] + (size_t)ss * 64);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      __builtin_amdgcn_global_load_lds((global_void_ptr)(xsrc[i] + (size_t)ss * 64),
+                                       (lds_void_ptr)(ring + ((size_t)slot * 8 + wave * 2 + i) * 64), 16, 0, 0);
+  };
+  auto read_x = [&](u32x4 (&f)[8], int slot) {
+    const u32x4* sp = ring + (size_t)slot * 8 * 64 + lane;
+#pragma unroll
+    for (int b = 0; b < 8; ++b) f[b] = sp[b * 64];
+  };
+  f32x16 acc[2][8];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+
+  u32x4 wr[RING_D + 1][2];
+  u32x4 f[2][8];
+#pragma unroll
+  for (int q = 0; q < RING_D; ++q) issue(q, wr[q], q);
+  wait_loads_but<0>();
+  __builtin_amdgcn_s_barrier();
+  read_x(f[0], 0);
+  // q = s % (RING_D + 1): step s lives in register set / ring slot q
+  auto step = [&](int s, const u32x4 (&wcur)[2], u32x4 (&wnew)[2], const u32x4 (&fcur)[8], u32x4 (&fnext)[8], int q) {
+    // loads issued after this wavefront's activation tiles of step s+1: the RING_D - 2 steps s-13 .. s-1
+    wait_loads_but<(RING_D - 2) * 4>();
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+    issue(s + RING_D, wnew, (q + RING_D) % (RING_D + 1));
+    read_x(fnext, (q + 1) % (RING_D + 1));
+#pragma unroll
+    for (int b = 0; b < 8; ++b)
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, wcur[a]),
+                                                            __builtin_bit_cast(bf16x8, fcur[b]), acc[a][b], 0, 0, 0);
+    // the multiplies start at once; one load, then one fragment read, goes out behind each of the first twelve
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x010, 1, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  static_assert(RING_D == 15, "the loop below is unrolled for sixteen register sets");
+  for (int s = 0; s < k_steps; s += 16) {
+#define EE_RING_STEP(i) step(s + i, wr[i], wr[(i + 15) % 16], f[i & 1], f[(i + 1) & 1], i)
+    EE_RING_STEP(0); EE_RING_STEP(1); EE_RING_STEP(2); EE_RING_STEP(3);
+    EE_RING_STEP(4); EE_RING_STEP(5); EE_RING_STEP(6); EE_RING_STEP(7);
+    EE_RING_STEP(8); EE_RING_STEP(9); EE_RING_STEP(10); EE_RING_STEP(11);
+    EE_RING_STEP(12); EE_RING_STEP(13); EE_RING_STEP(14); EE_RING_STEP(15);
+#undef EE_RING_STEP
+  }
+  wait_loads_but<0>();   // the repeated loads past the end still target LDS and registers
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 8; ++b)
+      if (bm * 8 + b < m_tiles) finish_from_registers(acc[a][b], nt0 + a, bm * 8 + b, M_eff, 0, g, e, lane);
+}
+
+// Which shapes the ring kernel serves: 385 to 512 rows (two row blocks, the second at least half full: below that the
+// tiled kernel's 128-row chunks waste less; above, the workgroups no longer fit the chip in one round), whole blocks
+// of eight weight tiles, a contraction of whole groups of sixteen steps.
+bool ring_serves(int M, int n_tiles, int K) {
+  return M > 384 && M <= 512 && n_tiles % 8 == 0 && (K >> 4) % (RING_D + 1) == 0 && (K & 15) == 0;
 }
 
 // Batch tiles per pass of the streaming kernel / per chunk of the tiled kernel.
@@ -688,6 +807,20 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
         g2.grid_y = chunks2;
         dim3 grid2((groups + 7) / 8 * 8 * chunks2, 1, nz);
         hipLaunchKernelGGL((gemm_tiled_kernel<2, 1, Epi, FILL>), grid2, block, 0, st, g2, e, pred, fc);
+        return;
+      }
+    }
+    if constexpr (!FILL && (std::is_same<Epi, LmEpi>::value || std::is_same<Epi, GateUpEpi>::value)) {
+      // the ring needs 128 KiB of dynamic LDS: asked for once (the attribute belongs to the function, not to a
+      // launch); if the runtime refuses, the tiled kernel below serves the shape
+      static int ring_ok = -1;
+      if (ring_ok < 0)
+        ring_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<Epi>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, RING_LDS_BYTES) == hipSuccess;
+      if (ring_ok && !g.n_rows_dev && ring_serves(g.M, g.n_tiles, g.K)) {
+        const int row_blocks = (m_tiles + 7) / 8, col_blocks = g.n_tiles / 8;
+        dim3 gridr((col_blocks + 7) / 8 * 8 * row_blocks, 1, 1);
+        hipLaunchKernelGGL((gemm_ring_kernel<Epi>), gridr, block, RING_LDS_BYTES, st, g, e, pred);
         return;
       }
     }

@@ -265,6 +265,17 @@ def test_bf16_per_sequence_exit_compacted_rows_lockstep(conf_mode, threshold, ba
     assert stats["near_threshold"] + stats["near_tie"] <= max(2, total // 20), stats
 
 
+@pytest.mark.parametrize("batch", [385, 400, 481, 512])
+@pytest.mark.parametrize("heads", [1, 2])
+def test_bf16_385_to_512_rows_lockstep(batch, heads):
+    """385 to 512 rows: LM head and gate/up run in the 256 x 256 ring kernel under Algorithm 1 (a second row block
+    from one row to full), and stay in the tiled kernel with compacted rows under the per-sequence rule."""
+    cfg = compactable_bf16(batch=batch)
+    stats = lockstep(cfg, seed=46, steps=2, heads=heads)
+    total = stats["decisions"] + stats["tokens"]
+    assert stats["near_threshold"] + stats["near_tie"] <= max(2, total // 20), stats
+
+
 @pytest.mark.parametrize("batch", [96, 150, 200])
 @pytest.mark.parametrize("heads", [1, 2])
 def test_bf16_row_counts_with_a_short_last_chunk(batch, heads):

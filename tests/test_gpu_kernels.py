@@ -258,6 +258,14 @@ def test_exit_check_sticky_forced_and_done_flag(dtype):
     run_exit_check(cfg, 34, layer=6 - 1, threshold=0.5, forced=torch.full((5,), 2, dtype=torch.int32), pre_status=pre)
 
 
+@pytest.mark.parametrize("batch,heads", [(385, 4), (481, 16), (512, 16)])
+def test_exit_check_385_to_512_rows(batch, heads):
+    """The row counts at which the LM head runs in the 256 x 256 ring kernel: contraction of one and of four groups
+    of sixteen steps (d_model 256 and 1024), a second row block of one row, of three tiles and a row, and full."""
+    cfg = cfg_of("bf16", 64, heads, n_layers=4, vocab=1280, logit_scale=2.0, batch=batch)
+    run_exit_check(cfg, seed=50 + heads, layer=2, threshold=0.3, hidden_scale=3.0)
+
+
 def test_exit_check_llama7b_width():
     """LM head of the 7B-shaped workload (vocab 32000 x d 4096, batch 32): every row's confidence and arg max."""
     cfg = W.reduced(L7B, n_layers=2, d_ffn=256)
