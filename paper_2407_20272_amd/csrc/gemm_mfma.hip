@@ -686,7 +686,7 @@ __global__ __launch_bounds__(256) void gemm_ring_kernel(GemmShape g, Epi e, Pred
   u32x4 f[2][8];
 #pragma unroll
   for (int q = 0; q < RING_D; ++q) issue(q, wr[q], q);
-  wait_loads_but<0>();
+  wait_loads_but<(RING_D - 1) * 4>();   // step 0 has landed; the loop's own waits take it from there
   __builtin_amdgcn_s_barrier();
   read_x(f[0], 0);
   // q = s % (RING_D + 1): step s lives in register set / ring slot q
