@@ -685,7 +685,10 @@ __global__ __launch_bounds__(256) void gemm_ring_kernel(GemmShape g, Epi e, Pred
   u32x4 wr[RING_D + 1][2];
   u32x4 f[2][8];
 #pragma unroll
-  for (int q = 0; q < RING_D; ++q) issue(q, wr[q], q);
+  for (int q = 0; q < RING_D; ++q) {
+    issue(q, wr[q], q);
+    asm volatile("" ::: "memory");      // the counted waits rely on the loads of a step staying together, in step order
+  }
   wait_loads_but<(RING_D - 1) * 4>();   // step 0 has landed; the loop's own waits take it from there
   __builtin_amdgcn_s_barrier();
   read_x(f[0], 0);
