@@ -198,8 +198,8 @@ int ee_exit_check(const ee_model* model, int32_t layer, const float* hidden, int
  * Every call on one GPU uses that GPU's one array: calls that overlap on a GPU (two streams, two threads) race;
  * calls on one stream are ordered and each clears what it needs to start at zero.
  * ee_noalloc_init resolves the array's device address for the current device (one host-side query, no
- * allocation); it is otherwise done by the first ee_exit_check_noalloc on that device, so call it beforehand
- * if that first call would fall inside a graph capture. */
+ * allocation) and sets the function attributes of the projection kernels; both are otherwise done by the first
+ * call that needs them, so call it beforehand if that first call would fall inside a graph capture. */
 #define EE_NOALLOC_SCRATCH_BYTES (8u << 20)
 int ee_noalloc_init(void);
 size_t ee_exit_check_noalloc_bytes(const ee_model_desc* desc, int32_t batch);

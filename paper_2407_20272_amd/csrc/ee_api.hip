@@ -795,6 +795,7 @@ size_t ee_exit_check_noalloc_bytes(const ee_model_desc* desc, int32_t batch) {
 
 int ee_noalloc_init(void) {
   void* p = nullptr;
+  gemm_bf16_prepare();
   return noalloc_scratch(&p);
 }
 

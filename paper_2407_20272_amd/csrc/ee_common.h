@@ -247,6 +247,8 @@ struct GemmShape {
 // Whether a projection of M rows onto n_tiles packed tiles runs in the tiled kernel (the one that takes
 // n_rows_dev and the epilogues' perm).
 bool gemm_bf16_is_tiled(int M, int n_tiles);
+// One-time host-side set-up of the projection kernels (function attributes) that the first launch would otherwise do.
+void gemm_bf16_prepare();
 // with_combine != nullptr (only where gemm_qkv_carries_combine(M) holds): the launch also takes the exit decision
 // of the previous layer.  The projection then runs SPECULATIVELY when that decision ends the iteration (its
 // predicate word may or may not show the new value yet): what it caches for its layer is what KV filling

@@ -785,6 +785,17 @@ AccPlan acc_plan(int M, int n_tiles, int K) {
   return p;
 }
 
+// The ring kernel needs 128 KiB of dynamic LDS: asked for once per process (the attribute belongs to the function,
+// not to a launch), at the first launch that wants it or by gemm_bf16_prepare().
+template <class Epi>
+bool ring_allowed() {
+  static int ok = -1;
+  if (ok < 0)
+    ok = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<Epi>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             RING_LDS_BYTES) == hipSuccess;
+  return ok > 0;
+}
+
 template <class Epi, bool FILL>
 void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int nz, hipStream_t st,
             const CombineJob& cj = CombineJob{}) {
@@ -814,13 +825,8 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
       }
     }
     if constexpr (!FILL && (std::is_same<Epi, LmEpi>::value || std::is_same<Epi, GateUpEpi>::value)) {
-      // the ring needs 128 KiB of dynamic LDS: asked for once (the attribute belongs to the function, not to a
-      // launch); if the runtime refuses, the tiled kernel below serves the shape
-      static int ring_ok = -1;
-      if (ring_ok < 0)
-        ring_ok = hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_ring_kernel<Epi>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, RING_LDS_BYTES) == hipSuccess;
-      if (ring_ok && !g.n_rows_dev && ring_serves(g.M, g.n_tiles, g.K)) {
+      // if the runtime refused the ring its 128 KiB of dynamic LDS, the tiled kernel below serves the shape
+      if (ring_allowed<Epi>() && !g.n_rows_dev && ring_serves(g.M, g.n_tiles, g.K)) {
         const int row_blocks = (m_tiles + 7) / 8, col_blocks = g.n_tiles / 8;
         dim3 gridr((col_blocks + 7) / 8 * 8 * row_blocks, 1, 1);
         hipLaunchKernelGGL((gemm_ring_kernel<Epi>), gridr, block, RING_LDS_BYTES, st, g, e, pred);
@@ -889,6 +895,11 @@ void launch(const GemmShape& g, const Epi& e, Pred pred, const FillCtl& fc, int 
 }  // namespace
 
 bool gemm_bf16_is_tiled(int M, int n_tiles) { return tiled(M, n_tiles); }
+
+void gemm_bf16_prepare() {
+  ring_allowed<LmEpi>();
+  ring_allowed<GateUpEpi>();
+}
 
 int gemm_acc_slices(int M, int n_tiles, int K) { return acc_plan(M, n_tiles, K).ksplit; }
 

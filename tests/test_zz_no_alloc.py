@@ -74,6 +74,47 @@ def test_noalloc_exit_check_equals_workspace_exit_check_twice_second_call_smalle
     assert_same(a, b, "third call, batch 5")
 
 
+def test_noalloc_exit_check_at_512_rows_inside_a_graph_capture():
+    """512 rows put the LM head into the 256 x 256 ring kernel, whose function attribute ee_noalloc_init sets ahead of
+    time: the allocation-free call is then captured into a HIP graph (nothing has run the kernel eagerly before in this
+    test's own calls), replayed twice with the program's own eager work in between, and compared with the eager
+    workspace call on the same inputs."""
+    cfg = W.reduced(W.CONFIGS[1], n_layers=4, d_model=256, n_heads=4, head_dim=64, d_ffn=512, vocab=1280, logit_scale=2.0,
+                    batch=512)
+    w = W.make_weights(cfg, seed=12, gain_jitter=0.2)
+    model = B.DeviceModel(cfg, w)
+    B.ee_noalloc_init()
+    batch, n = 512, cfg.n_layers
+    hidden = (torch.randn(batch, cfg.d_model, generator=torch.Generator().manual_seed(6)) * 3.0).cuda()
+
+    def fresh():
+        return (torch.zeros(batch, dtype=torch.int32, device="cuda"), torch.full((batch,), n, dtype=torch.int32, device="cuda"),
+                torch.zeros(1, dtype=torch.int32, device="cuda"), torch.zeros(1, dtype=torch.int32, device="cuda"),
+                torch.full((1,), n, dtype=torch.int32, device="cuda"), torch.full((batch,), -1, dtype=torch.int32, device="cuda"),
+                torch.zeros(batch, dtype=torch.float32, device="cuda"))
+
+    ref = fresh()
+    ws = B.Workspace(model.desc, batch, 16)
+    B.ee_exit_check(model, 3, hidden, 0.15, None, *ref, ws)
+    torch.cuda.synchronize()
+    got = fresh()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            B.ee_exit_check_noalloc(model, 3, hidden, 0.15, None, *got)
+    torch.cuda.synchronize()
+    for replay in range(2):
+        for t, z in zip(got, fresh()):
+            t.copy_(z)                       # the program's own eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for x, y, name in zip(got, ref, ("status", "exit_layer", "n_exited", "done", "batch_exit_layer", "argmax", "conf")):
+            assert torch.equal(x, y), f"replay {replay}: {name} differs from the eager workspace call"
+    assert 0 < int(ref[2].item()) < batch, "the threshold should split the batch"
+
+
 def test_noalloc_exit_check_at_llama7b_width_and_size_limit():
     """The LM head of the 7B-shaped workload at batch 32 fits the static array; a batch that does not is refused on the
     host with a message, before anything is enqueued."""
