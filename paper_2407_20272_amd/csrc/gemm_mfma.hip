@@ -1,16 +1,22 @@
-// bf16 projections of the decode step on the matrix cores (v_mfma_f32_32x32x16_bf16).
+// bf16 projections of the decode step on the matrix cores (v_mfma_f32_32x32x16_bf16).  Three kernels, by batch size:
 //
-// The decode step multiplies a handful of activation rows (the batch) by large weight matrices, so the
-// kernels are weight streamers: every weight byte is fetched from HBM exactly once, straight into registers
-// (1 KiB of consecutive bytes per wavefront load thanks to the packed tile order), and the small activation
-// operand comes out of L2.  A workgroup of four wavefronts owns 32-row output tiles and splits the contraction
-// four ways; the partial tiles meet in LDS and the epilogue (rotary + paged cache write, residual accumulation,
-// SwiGLU, or exit-head softmax statistics) runs on the finished sums.
+//   gemm_mfma_kernel   one or two 32-row batch tiles, few output tiles (QKV, output projection): a weight streamer.
+//                      Every weight byte is fetched from HBM exactly once, straight into registers (1 KiB of
+//                      consecutive bytes per wavefront load thanks to the packed tile order), the small activation
+//                      operand comes out of L2.  A workgroup of four wavefronts owns one 32-row output tile and splits
+//                      the contraction four ways; the partial tiles meet in LDS.
+//   gemm_tiled_kernel  everything else up to 384 rows, and the projections with few output tiles beyond: the four
+//                      wavefronts own different output tiles over the same contraction range and share the activation
+//                      operand through LDS; 128-row chunks.
+//   gemm_ring_kernel   LM head and gate/up at 385-512 rows, where the matrix cores are what counts: 256 x 256 blocks.
+//
+// The epilogues (rotary + paged cache write, partial results of the residual updates, SwiGLU, exit-head softmax
+// statistics) run on the finished sums, from LDS in the first kernel and from registers in the other two.
 //
 // The second operand is bf16 in operand-tile order: the attention output, the SwiGLU product, or the normalised
-// hidden state written by prep_x_kernel.  (Building the normalised operand on the fly from the float residual
-// stream inside this loop was tried and measured slower: twice the L2 traffic per weight byte plus the
-// conversion arithmetic cost more than the 4.7 us normalisation launch they replaced.)
+// hidden state written by finish_norm_kernel.  (Building the normalised operand on the fly from the float residual
+// stream inside the loop was tried and measured slower: twice the L2 traffic per weight byte plus the conversion
+// arithmetic cost more than the normalisation launch they replaced.)
 #include <type_traits>
 
 #include "ee_common.h"
