@@ -217,7 +217,12 @@ int ee_kv_fill(const ee_model* model, const ee_kv_cache* cache, const ee_batch* 
 /* Single-query attention over the paged cache of one layer (the attention inside Algorithm 1's M(i, ...)):
  * out[b][h] = softmax_j(q[b][h] . K[b][j][h] / sqrt(head_dim)) . V[b][j][h], j = 0..context_lens[b] INCLUSIVE: the new
  * token's K/V must already be in the cache.   q dev [B][H][dh] float, rotary embedding applied.
- * out dev [B][H][dh] float.  batch->tokens is not read. */
+ * out dev [B][H][dh] float.  batch->tokens is not read.
+ * workspace (dev, 16-byte aligned) may be NULL.  With B * H <= 64 and a block table at least 16 blocks wide, a
+ * workspace of at least B * H * 8 * (head_dim + 2) * 4 bytes lets up to eight workgroups share one (sequence, head)
+ * pair, each over a contiguous part of the context, merged in a fixed order by a second launch (single-stream decoding
+ * over a long context would otherwise keep only B * H compute units busy); a smaller or missing one is not an error,
+ * the call then runs one workgroup per pair.  ee_decode_iteration does the same out of its own workspace. */
 int ee_paged_attention_decode(const ee_model_desc* desc, const ee_kv_cache* cache, int32_t layer, const float* q,
                               const ee_batch* batch, float* out, void* workspace, size_t workspace_bytes,
                               void* stream);

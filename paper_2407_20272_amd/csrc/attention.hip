@@ -77,7 +77,7 @@ __device__ uint4 k_zero16;
 
 constexpr int TABLE_LDS_MAX = kAttnMaxBlocks;   // block-table entries staged in LDS
 
-template <class T, int DH, bool OUT_XT>
+template <class T, int DH, bool OUT_XT, bool SPLIT>
 __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred) {
   constexpr int EPL = Elems<T>::N;         // values per 16-byte lane load
   constexpr int LPT = DH / EPL;            // lanes per token
@@ -182,11 +182,19 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
   // Two blocks of this wavefront in flight at any time.  The steady loop has no conditional load: a load under
   // a condition makes the compiler wait for every outstanding load where the paths join, which would drain
   // the stream once per block; the scheduling fences keep each block's loads together ahead of the arithmetic.
+  // SPLIT: this workgroup is part blockIdx.z of gridDim.z and walks a contiguous range of the sequence's blocks
+  // (possibly empty: a short sequence in a wide table); otherwise all of them.
+  int lb_begin = 0, lb_end = n_blocks;
+  if constexpr (SPLIT) {
+    const int per = (n_blocks + (int)gridDim.z - 1) / (int)gridDim.z;
+    lb_begin = min(n_blocks, (int)blockIdx.z * per);
+    lb_end = min(n_blocks, lb_begin + per);
+  }
   Blk A, B;
-  int lb = wave;
-  if (lb < n_blocks) fetch(A, lb);
-  if (lb + NW < n_blocks) fetch(B, lb + NW);
-  for (; lb + 3 * NW < n_blocks; lb += 2 * NW) {
+  int lb = lb_begin + wave;
+  if (lb < lb_end) fetch(A, lb);
+  if (lb + NW < lb_end) fetch(B, lb + NW);
+  for (; lb + 3 * NW < lb_end; lb += 2 * NW) {
     consume(A, lb);
     __builtin_amdgcn_sched_barrier(0);
     fetch(A, lb + 2 * NW);
@@ -197,11 +205,11 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
     __builtin_amdgcn_sched_barrier(0);
   }
   // at most three blocks left: lb (in A), lb + NW (in B), lb + 2 NW (not fetched yet)
-  if (lb < n_blocks) {
+  if (lb < lb_end) {
     consume(A, lb);
-    const bool third = lb + 2 * NW < n_blocks;
+    const bool third = lb + 2 * NW < lb_end;
     if (third) fetch(A, lb + 2 * NW);
-    if (lb + NW < n_blocks) consume(B, lb + NW);
+    if (lb + NW < lb_end) consume(B, lb + NW);
     if (third) consume(A, lb + 2 * NW);
   }
 
@@ -243,13 +251,50 @@ __global__ __launch_bounds__(256) void attn_decode_kernel(AttnArgs a, Pred pred)
       L += sl[w] * wgt;
       acc += so[w][threadIdx.x] * wgt;
     }
-    const float r = acc / L;
-    const int col = head * DH + threadIdx.x;
-    if constexpr (OUT_XT) {
-      reinterpret_cast<bf16_t*>(a.out)[xt_index(out_row, col, a.n_heads * DH)] = (bf16_t)r;
+    if constexpr (SPLIT) {
+      // this part's running maximum, sum and unnormalised output; the merge launch takes it from here
+      float* ws = a.split_ws + (((size_t)b * a.n_heads + head) * gridDim.z + blockIdx.z) * (DH + 2);
+      if (threadIdx.x == 0) {
+        ws[0] = M;
+        ws[1] = L;
+      }
+      ws[2 + threadIdx.x] = acc;
     } else {
-      reinterpret_cast<float*>(a.out)[(size_t)out_row * a.n_heads * DH + col] = r;
+      const float r = acc / L;
+      const int col = head * DH + threadIdx.x;
+      if constexpr (OUT_XT) {
+        reinterpret_cast<bf16_t*>(a.out)[xt_index(out_row, col, a.n_heads * DH)] = (bf16_t)r;
+      } else {
+        reinterpret_cast<float*>(a.out)[(size_t)out_row * a.n_heads * DH + col] = r;
+      }
     }
+  }
+}
+
+// Second launch of the split form: one workgroup of DH threads per (sequence, head) adds the parts in part order.
+template <int DH, bool OUT_XT>
+__global__ __launch_bounds__(DH) void attn_merge_kernel(AttnArgs a, Pred pred) {
+  if (pred_skip(pred)) return;
+  const int head = blockIdx.x, b = blockIdx.y;
+  const int left = a.skip ? __hip_atomic_load(a.skip + b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0;
+  if (left != 0) return;
+  const int out_row = a.out_pos ? a.out_pos[b] : b;
+  const float* ws = a.split_ws + ((size_t)b * a.n_heads + head) * a.split_parts * (DH + 2);
+  float M = NEG_BIG;
+  for (int s = 0; s < a.split_parts; ++s) M = fmaxf(M, ws[(size_t)s * (DH + 2)]);
+  float L = 0.0f, acc = 0.0f;
+  for (int s = 0; s < a.split_parts; ++s) {
+    const float* p = ws + (size_t)s * (DH + 2);
+    const float wgt = __builtin_amdgcn_exp2f(p[0] - M);   // an empty part has the maximum -1e30: weight 0
+    L += p[1] * wgt;
+    acc += p[2 + threadIdx.x] * wgt;
+  }
+  const float r = acc / L;
+  const int col = head * DH + threadIdx.x;
+  if constexpr (OUT_XT) {
+    reinterpret_cast<bf16_t*>(a.out)[xt_index(out_row, col, a.n_heads * DH)] = (bf16_t)r;
+  } else {
+    reinterpret_cast<float*>(a.out)[(size_t)out_row * a.n_heads * DH + col] = r;
   }
 }
 
@@ -681,17 +726,44 @@ void launch_t(const AttnArgs& a, Pred pred, hipStream_t st) {
       hipLaunchKernelGGL((attn_rows_kernel<T, DH, ROWS_PER_GROUP, false>), grid, block, lds, st, a, pred);
     return;
   }
+  if (a.split_ws && a.split_parts > 1) {
+    // the output form only matters to the merge launch; the parts always leave as floats
+    dim3 grid(a.n_heads, a.B, a.split_parts);
+    hipLaunchKernelGGL((attn_decode_kernel<T, DH, false, true>), grid, block, lds, st, a, pred);
+    dim3 gridm(a.n_heads, a.B);
+    if (a.out_xt)
+      hipLaunchKernelGGL((attn_merge_kernel<DH, true>), gridm, dim3(DH), 0, st, a, pred);
+    else
+      hipLaunchKernelGGL((attn_merge_kernel<DH, false>), gridm, dim3(DH), 0, st, a, pred);
+    return;
+  }
   dim3 grid(a.n_heads, a.B);
   if (a.out_xt)
-    hipLaunchKernelGGL((attn_decode_kernel<T, DH, true>), grid, block, lds, st, a, pred);
+    hipLaunchKernelGGL((attn_decode_kernel<T, DH, true, false>), grid, block, lds, st, a, pred);
   else
-    hipLaunchKernelGGL((attn_decode_kernel<T, DH, false>), grid, block, lds, st, a, pred);
+    hipLaunchKernelGGL((attn_decode_kernel<T, DH, false, false>), grid, block, lds, st, a, pred);
 }
 
 }  // namespace
 
+// One workgroup per (sequence, head) keeps the chip busy from about 256 pairs on.  With at most 64, up to eight
+// workgroups share a pair so that about 256 run, as long as every part still has eight blocks (128 positions) of the
+// table's width to walk: below that, and at 128 pairs (measured: 28.6 against 29.0 us at 4 x 2048 positions), the second
+// launch costs what the idle compute units would have gained.  Measured at the 7B shape, one sequence: 16384
+// positions 147 -> 52 us per layer, 4096 positions 41 -> 21 us.
+int attn_split_parts(int B, int n_heads, int max_blocks) {
+  const long pairs = (long)B * n_heads;
+  if (pairs <= 0 || pairs > kAttnSplitMaxPairs) return 1;
+  int parts = (int)(256 / pairs);
+  if (parts > kAttnMaxSplit) parts = kAttnMaxSplit;
+  if (parts > max_blocks / 8) parts = max_blocks / 8;
+  return parts < 2 ? 1 : parts;
+}
+
 int launch_attention(const AttnArgs& a, int dtype, Pred pred, hipStream_t st) {
   if (a.B == 0) return EE_OK;
+  if (a.split_parts > 1 && a.row_table) EE_FAIL(EE_ERR_UNSUPPORTED, "attention: split_parts does not go with row_table");
+  if (a.split_parts > kAttnMaxSplit) EE_FAIL(EE_ERR_UNSUPPORTED, "attention: split_parts %d above %d", a.split_parts, kAttnMaxSplit);
   if (a.max_blocks < 1 || a.max_blocks > TABLE_LDS_MAX)
     EE_FAIL(EE_ERR_UNSUPPORTED, "attention: max_blocks %d outside 1..%d", a.max_blocks, TABLE_LDS_MAX);
   if (a.out_pos && a.row_table) EE_FAIL(EE_ERR_UNSUPPORTED, "attention: out_pos does not go with row_table");

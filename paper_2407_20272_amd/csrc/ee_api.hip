@@ -81,6 +81,7 @@ struct Workspace {
   // shared
   int32_t *status, *n_exited, *done, *scratch_exit_layer, *scratch_L;
   float* q;           // [B][d]
+  float* attn_split;  // [B][H][8][head_dim + 2] partial attention results, only for batches of at most 64 (sequence, head) pairs
   float2* rope;       // [B][head_dim/2] (cos, sin) of this iteration's rotary angles
   float4* partials;   // bf16: [Mpad][vocab/32]; fp32: [B]
   float* h;           // residual stream: bf16 [Mpad][d], fp32 [B][d]
@@ -119,6 +120,7 @@ Workspace carve(const ee_model_desc& D, int B, void* base) {
   w.scratch_exit_layer = c.take<int32_t>(Bp);
   w.scratch_L = c.take<int32_t>(1);
   w.q = c.take<float>(Bp * d);
+  w.attn_split = c.take<float>((long)Bp * D.n_heads <= kAttnSplitMaxPairs ? attn_split_floats(Bp, D.n_heads, D.head_dim, kAttnMaxSplit) : 0);
   w.rope = c.take<float2>((size_t)Bp * (D.head_dim / 2));
   if (D.dtype == EE_BF16) {
     w.partials = c.take<float4>((size_t)Mpad * (V / 32));
@@ -576,7 +578,11 @@ int ee_decode_iteration(const ee_model* model, const ee_kv_cache* cache, const e
     const size_t pool_off = pool_layer_elems(D, *cache) * elem_bytes(D) * (size_t)(i - 1);
     AttnArgs at{w.q, reinterpret_cast<char*>(cache->k_pool) + pool_off, reinterpret_cast<char*>(cache->v_pool) + pool_off,
                 batch->context_lens, batch->block_tables, batch->max_blocks, B, D.n_heads, D.head_dim, nullptr, 0, left,
-                batch->row_table, rmap.cpos, cache->num_blocks};
+                batch->row_table, rmap.cpos, cache->num_blocks, nullptr, 1};
+    if (!batch->row_table && (long)B * D.n_heads <= kAttnSplitMaxPairs) {   // few pairs, long contexts: several workgroups per pair
+      at.split_parts = attn_split_parts(B, D.n_heads, batch->max_blocks);
+      at.split_ws = at.split_parts > 1 ? w.attn_split : nullptr;
+    }
     const bool head_here = use_exit_heads && has_head(D, i);
     if (bf) {
       if (i == 1) {   // operand of the first layer from the embedding (also h_0, the "previous" hidden state of layer 1)
@@ -841,8 +847,6 @@ int ee_kv_fill(const ee_model* model, const ee_kv_cache* cache, const ee_batch* 
 
 int ee_paged_attention_decode(const ee_model_desc* desc, const ee_kv_cache* cache, int32_t layer, const float* q,
                               const ee_batch* batch, float* out, void* workspace, size_t workspace_bytes, void* stream) {
-  (void)workspace;
-  (void)workspace_bytes;
   int rc;
   if ((rc = check_desc(desc)) || (rc = check_cache(cache)) || (rc = check_batch(batch, false))) return rc;
   if (batch->batch == 0) return EE_OK;
@@ -851,7 +855,15 @@ int ee_paged_attention_decode(const ee_model_desc* desc, const ee_kv_cache* cach
   const size_t off = pool_layer_elems(*desc, *cache) * elem_bytes(*desc) * (size_t)(layer - 1);
   AttnArgs at{q, reinterpret_cast<char*>(cache->k_pool) + off, reinterpret_cast<char*>(cache->v_pool) + off,
               batch->context_lens, batch->block_tables, batch->max_blocks, batch->batch, desc->n_heads, desc->head_dim,
-              out, 0, nullptr, batch->row_table, nullptr, cache->num_blocks};
+              out, 0, nullptr, batch->row_table, nullptr, cache->num_blocks, nullptr, 1};
+  if (workspace && !batch->row_table) {   // a workspace lets few (sequence, head) pairs share their contexts among workgroups
+    const int parts = attn_split_parts(batch->batch, desc->n_heads, batch->max_blocks);
+    if (parts > 1 && (reinterpret_cast<uintptr_t>(workspace) & 15) == 0 &&
+        workspace_bytes >= attn_split_floats(batch->batch, desc->n_heads, desc->head_dim, parts) * sizeof(float)) {
+      at.split_parts = parts;
+      at.split_ws = reinterpret_cast<float*>(workspace);
+    }
+  }
   const Pred always{nullptr, 0};
   if ((rc = launch_attention(at, desc->dtype, always, reinterpret_cast<hipStream_t>(stream)))) return rc;
   EE_HIP(hipGetLastError());

@@ -305,7 +305,20 @@ struct AttnArgs {
   const int32_t* row_table;     // nullptr, or [B]: row b uses row row_table[b] of block_tables
   const int32_t* out_pos;       // nullptr, or [B]: the result of sequence b goes to row out_pos[b] of out (compacted operand)
   int num_blocks;               // blocks per layer of the pools: a block id outside 0..num_blocks-1 is read as block 0
+  // Few (sequence, head) pairs and long contexts: split_parts > 1 workgroups share one pair, each over a contiguous
+  // range of the sequence's blocks; their partial results (running maximum, sum and unnormalised output:
+  // head_dim + 2 floats each) meet in split_ws [B][H][split_parts][head_dim + 2] and a second launch merges them in
+  // part order.  1 (or split_ws == nullptr) = one workgroup per pair.  Not with row_table.
+  float* split_ws;
+  int split_parts;
 };
 int launch_attention(const AttnArgs& a, int dtype, Pred pred, hipStream_t st);
+// How many workgroups should share one (sequence, head) pair for this batch, and the floats of split_ws that takes.
+int attn_split_parts(int B, int n_heads, int max_blocks);
+inline size_t attn_split_floats(int B, int n_heads, int head_dim, int parts) {
+  return parts > 1 ? (size_t)B * n_heads * parts * (head_dim + 2) : 0;
+}
+constexpr int kAttnMaxSplit = 8;
+constexpr int kAttnSplitMaxPairs = 64;   // (sequence, head) pairs up to which the split form is used
 
 }  // namespace ee

@@ -51,6 +51,20 @@ def test_tiny_fp32_other_seeds_with_gain_jitter(seed):
     assert stats["near_threshold"] == 0 and stats["near_tie"] == 0
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_two_sequences_long_prompts_attention_split_among_workgroups(dtype):
+    """Two sequences with prompts of 140 to 300 tokens and two heads: the iteration's attention gives every
+    (sequence, head) pair to two workgroups (a part of the context each) and merges them in a second launch."""
+    if dtype == "fp32":
+        cfg = TINY.with_(batch=2, n_heads=2, head_dim=128, prompt_len=300, min_prompt_len=140, decode_steps=3, weight_std=0.05,
+                         logit_scale=1.0, threshold=0.3, shuffled_blocks=True)
+    else:
+        cfg = small_bf16(batch=2, prompt_len=300, min_prompt_len=140, shuffled_blocks=True)
+    stats = lockstep(cfg, seed=47, steps=3)
+    total = stats["decisions"] + stats["tokens"]
+    assert stats["near_threshold"] + stats["near_tie"] <= max(2, total // 20), stats
+
+
 def test_fp32_ragged_prompts_shuffled_blocks_conf_mode1():
     cfg = TINY.with_(batch=6, prompt_len=21, min_prompt_len=3, shuffled_blocks=True, conf_mode=1, weight_std=0.05,
                      logit_scale=2.0, threshold=0.2, n_layers=5, exit_every=2)

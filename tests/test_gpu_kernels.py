@@ -37,7 +37,15 @@ def poison_unwritten_slots(cache, bt, n_pos):
     cache.v[mask] = float("nan")
 
 
-def run_attention(cfg, lens, seed, shuffled=True, sample=None, poison=False):
+class RawWorkspace:
+    """A bare device buffer with the two attributes the binding reads from a workspace."""
+
+    def __init__(self, n_bytes):
+        self.buf = torch.empty(max(n_bytes, 16), dtype=torch.uint8, device="cuda")
+        self.bytes = n_bytes
+
+
+def run_attention(cfg, lens, seed, shuffled=True, sample=None, poison=False, ws_bytes=None):
     lens = torch.tensor(lens, dtype=torch.int32)
     cfg = cfg.with_(batch=len(lens), shuffled_blocks=shuffled)
     max_ctx = int(lens.max()) + 1
@@ -54,7 +62,10 @@ def run_attention(cfg, lens, seed, shuffled=True, sample=None, poison=False):
     out = torch.zeros(cfg.batch, cfg.n_heads, cfg.head_dim, device="cuda")
     batch = B.make_batch(None, lens.cuda(), bt.cuda(), max_ctx)
     layer = cfg.n_layers
-    B.ee_paged_attention_decode(B.make_desc(cfg), cache, layer, q.cuda(), batch, out)
+    ws = None if ws_bytes is None else RawWorkspace(ws_bytes)
+    if ws is not None:
+        ws.buf.fill_(0xFF)           # NaN patterns: a part that is not written would show
+    B.ee_paged_attention_decode(B.make_desc(cfg), cache, layer, q.cuda(), batch, out, ws)
     torch.cuda.synchronize()
     out = out.cpu()
     rows = range(cfg.batch) if sample is None else sample
@@ -76,6 +87,19 @@ def test_attention_ignores_what_unwritten_slots_hold(dtype, dh):
     """Slots after a sequence's last position (and blocks nobody owns) hold NaN: no result may change."""
     cfg = cfg_of(dtype, dh, 2)
     run_attention(cfg, [0, 1, 14, 15, 16, 17, 31, 32, 63, 64, 65, 100, 257, 5], seed=12, poison=True)
+
+
+@pytest.mark.parametrize("dtype,dh,heads", [("fp32", 64, 2), ("bf16", 64, 8), ("bf16", 128, 3)])
+def test_attention_context_split_among_workgroups(dtype, dh, heads):
+    """Few (sequence, head) pairs and a wide block table: with a workspace up to eight workgroups share a pair, each
+    over a contiguous part of the context (parts of a short sequence are empty), and a second launch merges them.
+    Unowned slots hold NaN.  A workspace that is too small is not an error: the call runs one workgroup per pair."""
+    cfg = cfg_of(dtype, dh, heads)
+    lens = [0, 5, 130, 700, 2049]
+    need = len(lens) * heads * 8 * (dh + 2) * 4
+    run_attention(cfg, lens, seed=15, poison=True, ws_bytes=need)
+    run_attention(cfg, lens, seed=16, poison=True, ws_bytes=need // 16)
+    run_attention(cfg, [4000], seed=17, ws_bytes=heads * 8 * (dh + 2) * 4)          # one sequence, every part full
 
 
 def test_attention_rows_sharing_one_block_table():
