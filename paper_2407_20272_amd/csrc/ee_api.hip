@@ -120,7 +120,10 @@ Workspace carve(const ee_model_desc& D, int B, void* base) {
   w.scratch_exit_layer = c.take<int32_t>(Bp);
   w.scratch_L = c.take<int32_t>(1);
   w.q = c.take<float>(Bp * d);
-  w.attn_split = c.take<float>((long)Bp * D.n_heads <= kAttnSplitMaxPairs ? attn_split_floats(Bp, D.n_heads, D.head_dim, kAttnMaxSplit) : 0);
+  {   // room for the largest batch that splits its attention, so that a workspace sized for B rows serves any fewer
+    const long pairs = (long)Bp * D.n_heads < kAttnSplitMaxPairs ? (long)Bp * D.n_heads : kAttnSplitMaxPairs;
+    w.attn_split = c.take<float>((size_t)pairs * kAttnMaxSplit * (D.head_dim + 2));
+  }
   w.rope = c.take<float2>((size_t)Bp * (D.head_dim / 2));
   if (D.dtype == EE_BF16) {
     w.partials = c.take<float4>((size_t)Mpad * (V / 32));

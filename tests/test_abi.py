@@ -44,6 +44,13 @@ def test_workspace_sizes():
     assert L.ee_workspace_bytes(C.byref(desc(d_model=255)), 4, 64) == 0
     assert L.ee_workspace_bytes(None, 4, 64) == 0
     assert B.ee_packed_weight_bytes(64, 32) == 64 * 32 * 2
+    # a workspace sized for B rows must serve every call with fewer rows (the serving harness sizes it once):
+    # the size never shrinks as the batch grows, whichever kernels and layouts a batch size selects
+    small_bf16 = desc(n_layers=3, d_model=256, n_heads=2, head_dim=128, d_ffn=384, vocab=1024, dtype=B.EE_BF16)
+    for dsc in (desc(), small_bf16, big):
+        sizes = [L.ee_workspace_bytes(C.byref(dsc), b, 64) for b in range(1, 600)]
+        assert all(x > 0 for x in sizes)
+        assert all(x <= y for x, y in zip(sizes, sizes[1:])), [i + 1 for i, (x, y) in enumerate(zip(sizes, sizes[1:])) if x > y]
     # bf16 path: the normalisation kernel holds a row of at most 8192 channels
     wide = desc(n_layers=2, d_model=16384, n_heads=128, head_dim=128, d_ffn=1024, vocab=512, dtype=B.EE_BF16)
     assert L.ee_workspace_bytes(C.byref(wide), 4, 64) == 0 and "8192" in B.ee_last_error()
