@@ -271,8 +271,8 @@ def main():
         how = B.EE_EXIT_NONE if mode == "full" else (
             B.EE_EXIT_PER_SEQUENCE if per_seq and mode != "never" else B.EE_EXIT_BATCH)
         B.ee_decode_iteration(variants.get(mode, model), cache, batch, thr, f, how, out_tok, out_exit, out_L, conf_buf, None, ws)
-        L_hist.scatter_add_(0, out_L.long(), one1)
-        E_hist.scatter_add_(0, out_exit.long(), oneB)
+        L_hist.index_add_(0, out_L, one1)          # histograms of the timed steps (int32 indices: no cast launches)
+        E_hist.index_add_(0, out_exit, oneB)
         torch.add(out_tok, 0, out=tokens)          # next iteration consumes the tokens just produced
         ctx.add_(1)
 
