@@ -114,6 +114,16 @@ def measure_peaks(torch, B):
         t = timed(lambda i=0: B.ee_calibration_read(bufs[i % 4], sink, wgs), 16)
         best = max(best, bufs[0].numel() * 4 / t / 1e9)
     out["read_GBps"] = best
+    # one workgroup per compute unit, half of the loads from a weight-like stream (HBM), half from 4 MiB that everybody
+    # walks (L2): what a compute unit takes in, by the loads it keeps in flight.  "own": every workgroup has its stream to
+    # itself; "pairs": two workgroups of one XCD share a stream (every byte leaves HBM once and L2 twice), as the two
+    # row blocks of a column block of the ring projection kernel do
+    common = torch.full((1 << 20,), 3.0, dtype=torch.float32, device="cuda")
+    for pairs in (False, True):
+        for depth in (8, 16, 32, 48):
+            t = timed(lambda i=0: B.ee_calibration_intake(bufs[i % 4], common, 256, depth, pairs, sink), 8)
+            per_wg = (2 if pairs else 1) * bufs[0].numel() * 4 / 256      # bytes of the stream one workgroup reads
+            out[f"intake_GBps_per_cu_{'pairs' if pairs else 'own'}_{depth * 4}_KiB_in_flight"] = 2 * per_wg / t / 1e9
     iters = 20000
     for per_simd in (1, 2):
         wgs = 256 * per_simd

@@ -257,10 +257,20 @@ int ee_calibration_copy(const float* src, float* dst, size_t n_floats, void* str
  *   each: one workgroup per compute unit) run `steps` (even, >= 2) contraction steps of 16 such instructions on 4 x 4
  *   accumulators; with `lds_fragment_reads` = 8 every step also reads the next step's 4 + 4 operand fragments (1 KiB
  *   each) from LDS, with 0 it reads none.  No global memory traffic in the loop; `sink` (dev, 1 KiB) is never written.
- *   Errors: EE_ERR_INVALID_ARG for a NULL sink, an odd or too small step count, another number of reads. */
+ *   Errors: EE_ERR_INVALID_ARG for a NULL sink, an odd or too small step count, another number of reads.
+ * ee_calibration_intake: what a compute unit takes in when half of its loads come from beyond its L2: `workgroups` x 4
+ *   wavefronts each read a piece of `own` (dev, own_bytes, read once: from HBM) in 1 KiB loads, alternating with 1 KiB
+ *   loads from `common` (dev, a power of two >= 64 KiB of bytes that every workgroup walks alike, so its lines are in
+ *   L2 after the first reader), `loads_in_flight` (8, 16, 32 or 48) per wavefront.  pairs = 0: every workgroup has a
+ *   piece of `own` to itself; each workgroup takes in own_bytes / workgroups from `own` and as much from `common`.
+ *   pairs = 1 (workgroups a multiple of 16): workgroups whose ids differ by 8 (one XCD, one L2) read the same piece, so
+ *   every byte of `own` leaves HBM once and L2 twice: each takes in 2 * own_bytes / workgroups from `own` and as much from
+ *   `common`.  `sink` (dev, 16 bytes) is practically never written. */
 int ee_calibration_read(const void* src, size_t bytes, void* sink, int32_t workgroups, void* stream);
 int ee_calibration_mfma(int32_t workgroups, int32_t iterations, float* sink, void* stream);
 int ee_calibration_mfma_tile(int32_t workgroups, int32_t steps, int32_t lds_fragment_reads, float* sink, void* stream);
+int ee_calibration_intake(const void* own, size_t own_bytes, const void* common, size_t common_bytes, int32_t workgroups,
+                          int32_t loads_in_flight, int32_t pairs, void* sink, void* stream);
 int ee_profile_enable(int32_t on);
 int ee_profile_read(int32_t* kernel_class /*host*/, int32_t* layer /*host*/, float* ms /*host*/, int32_t max_records);
 

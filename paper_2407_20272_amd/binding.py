@@ -21,7 +21,7 @@ EE_PACK_PLAIN, EE_PACK_QKV, EE_PACK_GATE_UP = 0, 1, 2
 EXPORTS = ["ee_last_error", "ee_packed_weight_bytes", "ee_pack_weight", "ee_workspace_bytes", "ee_decode_iteration",
            "ee_exit_check", "ee_kv_fill", "ee_paged_attention_decode", "ee_profile_enable", "ee_profile_read", "ee_calibration_copy",
            "ee_noalloc_init", "ee_exit_check_noalloc_bytes", "ee_exit_check_noalloc", "ee_calibration_read", "ee_calibration_mfma",
-           "ee_calibration_mfma_tile"]
+           "ee_calibration_mfma_tile", "ee_calibration_intake"]
 EE_NOALLOC_SCRATCH_BYTES = 8 << 20
 KERNEL_CLASSES = ["norm", "qkv", "attention", "o_proj", "gate_up", "down", "head", "combine", "kv_fill", "other"]
 
@@ -96,6 +96,9 @@ def lib() -> C.CDLL:
         L.ee_calibration_mfma.restype = C.c_int
         L.ee_calibration_mfma_tile.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
         L.ee_calibration_mfma_tile.restype = C.c_int
+        L.ee_calibration_intake.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_size_t, C.c_int32, C.c_int32, C.c_int32,
+                                            C.c_void_p, C.c_void_p]
+        L.ee_calibration_intake.restype = C.c_int
         L.ee_profile_enable.argtypes = [C.c_int32]
         L.ee_profile_read.argtypes = [C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_float), C.c_int32]
         L.ee_profile_enable.restype = C.c_int
@@ -316,6 +319,13 @@ def ee_calibration_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int):
 def ee_calibration_mfma(workgroups: int, iterations: int, sink: torch.Tensor):
     assert sink.dtype == torch.float32 and sink.numel() >= 256
     _check(lib().ee_calibration_mfma(workgroups, iterations, _ptr(sink), _stream()))
+
+
+def ee_calibration_intake(own: torch.Tensor, common: torch.Tensor, workgroups: int, loads_in_flight: int, pairs: bool,
+                          sink: torch.Tensor):
+    _check(lib().ee_calibration_intake(_ptr(own), own.numel() * own.element_size(), _ptr(common),
+                                       common.numel() * common.element_size(), workgroups, loads_in_flight, int(pairs),
+                                       _ptr(sink), _stream()))
 
 
 def ee_calibration_mfma_tile(workgroups: int, steps: int, lds_fragment_reads: int, sink: torch.Tensor):

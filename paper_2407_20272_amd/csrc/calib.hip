@@ -52,6 +52,51 @@ __global__ __launch_bounds__(256) void mfma_kernel(float* sink, int iters) {
   if (s == 1.2345f) sink[threadIdx.x] = s;   // never true for these operands; keeps the loop alive
 }
 
+// What one compute unit takes in when half of what it asks for comes from beyond its L2: every wavefront alternates
+// 1 KiB loads from a stream of its own (read once, from HBM) with 1 KiB loads from a small buffer that every workgroup
+// walks alike (its lines are in L2 after the first reader: the activation operand of a projection), D loads in flight
+// per wavefront, two register sets so that the next D / 2 are requested before the current ones are consumed.
+template <int D>
+__global__ __launch_bounds__(256) void intake_kernel(const u32x4* own, size_t words_per_wave, const u32x4* common,
+                                                     size_t common_mask, u32x4* sink, int pairs) {
+  constexpr int H = D / 2;            // loads per register set: H / 2 from each source
+  const int lane = threadIdx.x & 63, wave_in_wg = threadIdx.x >> 6;
+  // pairs: workgroups whose ids differ by 8 (same XCD, same L2) read the same stream, as the two row blocks of a
+  // column block of the ring projection kernel do: every byte of it then leaves HBM once and L2 twice
+  const size_t piece = pairs ? (size_t)(blockIdx.x >> 4) * 8 + (blockIdx.x & 7) : blockIdx.x;
+  const size_t wave = piece * 4 + wave_in_wg;
+  const u32x4* q = own + wave * words_per_wave + lane;
+  u32x4 a[H], b[H], acc = {0, 0, 0, 0};
+  size_t c = (size_t)wave_in_wg * 64;   // the four wavefronts of a workgroup walk consecutive KiB of the common buffer
+  auto issue = [&](u32x4 (&v)[H], size_t i) {
+#pragma unroll
+    for (int u = 0; u < H / 2; ++u) v[u] = __builtin_nontemporal_load(q + i + (size_t)u * 64);
+#pragma unroll
+    for (int u = 0; u < H / 2; ++u) {
+      v[H / 2 + u] = common[((c + (size_t)u * 256) & common_mask) + lane];
+    }
+    c += (size_t)(H / 2) * 256;
+  };
+  auto eat = [&](const u32x4 (&v)[H]) {
+#pragma unroll
+    for (int u = 0; u < H; ++u) acc ^= v[u];
+  };
+  const size_t step = (size_t)(H / 2) * 64;
+  const size_t n = words_per_wave / step;      // whole steps only
+  if (n >= 2) {
+    issue(a, 0);
+    size_t i = 1;
+    for (; i + 1 < n; i += 2) {
+      issue(b, i * step);
+      eat(a);
+      issue(a, (i + 1) * step);
+      eat(b);
+    }
+    eat(a);
+  }
+  if (acc.x == 0x12345678u && acc.y == 0x9abcdef0u && acc.z == 1u) sink[0] = acc;
+}
+
 // The inner loop of a 128 x 128 wavefront tile with nothing around it: per contraction step 16 MFMAs on 4 x 4
 // accumulators and, if READS, the 4 + 4 operand fragments of the next step read from LDS (1 KiB each, the
 // fragment order of the projection kernels) while the current step is multiplied.  Four wavefronts per
@@ -122,6 +167,33 @@ int ee_calibration_read(const void* src, size_t bytes, void* sink, int32_t workg
 int ee_calibration_mfma(int32_t workgroups, int32_t iterations, float* sink, void* stream) {
   if (!sink || workgroups < 1 || iterations < 1) EE_FAIL(EE_ERR_INVALID_ARG, "ee_calibration_mfma: bad argument");
   hipLaunchKernelGGL(mfma_kernel, dim3(workgroups), dim3(256), 0, reinterpret_cast<hipStream_t>(stream), sink, iterations);
+  EE_HIP(hipGetLastError());
+  return EE_OK;
+}
+
+int ee_calibration_intake(const void* own, size_t own_bytes, const void* common, size_t common_bytes, int32_t workgroups,
+                          int32_t loads_in_flight, int32_t pairs, void* sink, void* stream) {
+  if (!own || !common || !sink) EE_FAIL(EE_ERR_INVALID_ARG, "ee_calibration_intake: NULL pointer");
+  if (((reinterpret_cast<uintptr_t>(own) | reinterpret_cast<uintptr_t>(common)) & 15) || workgroups < 1 ||
+      common_bytes < (64u << 10) || (common_bytes & (common_bytes - 1)) || own_bytes < (size_t)workgroups * 4 * (128u << 10) ||
+      (pairs && (workgroups & 15)))
+    EE_FAIL(EE_ERR_INVALID_ARG,
+            "ee_calibration_intake: 16-byte aligned buffers, a power of two >= 64 KiB of common bytes, >= 128 KiB of own bytes per "
+            "wavefront, a multiple of 16 workgroups with pairs");
+  const size_t pieces = pairs ? (size_t)workgroups / 2 : (size_t)workgroups;
+  const size_t words_per_wave = own_bytes / 16 / (pieces * 4) / 64 * 64;
+  const size_t mask = common_bytes / 16 - 1 - 63;   // index of a 1 KiB row start: the low six bits come from the lane
+  auto st = reinterpret_cast<hipStream_t>(stream);
+  auto o = reinterpret_cast<const u32x4*>(own);
+  auto cm = reinterpret_cast<const u32x4*>(common);
+  auto sk = reinterpret_cast<u32x4*>(sink);
+  switch (loads_in_flight) {
+    case 8: hipLaunchKernelGGL(intake_kernel<8>, dim3(workgroups), dim3(256), 0, st, o, words_per_wave, cm, mask, sk, pairs); break;
+    case 16: hipLaunchKernelGGL(intake_kernel<16>, dim3(workgroups), dim3(256), 0, st, o, words_per_wave, cm, mask, sk, pairs); break;
+    case 32: hipLaunchKernelGGL(intake_kernel<32>, dim3(workgroups), dim3(256), 0, st, o, words_per_wave, cm, mask, sk, pairs); break;
+    case 48: hipLaunchKernelGGL(intake_kernel<48>, dim3(workgroups), dim3(256), 0, st, o, words_per_wave, cm, mask, sk, pairs); break;
+    default: EE_FAIL(EE_ERR_INVALID_ARG, "ee_calibration_intake: loads_in_flight must be 8, 16, 32 or 48");
+  }
   EE_HIP(hipGetLastError());
   return EE_OK;
 }

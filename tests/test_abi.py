@@ -138,6 +138,10 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert L.ee_calibration_read(None, 1 << 20, 1, 4, None) == B.EE_ERR_INVALID_ARG
     assert L.ee_calibration_read(16, 1024, 1, 4, None) == B.EE_ERR_INVALID_ARG          # too few bytes per workgroup
     assert L.ee_calibration_mfma(0, 10, 1, None) == B.EE_ERR_INVALID_ARG
+    assert L.ee_calibration_intake(16, 1 << 30, 16, 1 << 20, 4, 7, 0, 1, None) == B.EE_ERR_INVALID_ARG    # 8, 16, 32 or 48 loads
+    assert L.ee_calibration_intake(16, 1 << 30, 16, 3 << 20, 4, 8, 0, 1, None) == B.EE_ERR_INVALID_ARG    # common: a power of two
+    assert L.ee_calibration_intake(16, 1 << 20, 16, 1 << 20, 256, 8, 0, 1, None) == B.EE_ERR_INVALID_ARG  # too little per wavefront
+    assert L.ee_calibration_intake(16, 1 << 30, 16, 1 << 20, 24, 8, 1, 1, None) == B.EE_ERR_INVALID_ARG     # pairs: 16 | workgroups
     assert L.ee_calibration_mfma_tile(4, 3, 8, 1, None) == B.EE_ERR_INVALID_ARG       # odd step count
     assert L.ee_calibration_mfma_tile(4, 4, 5, 1, None) == B.EE_ERR_INVALID_ARG       # 0 or 8 fragment reads only
     assert L.ee_calibration_mfma_tile(4, 4, 8, None, None) == B.EE_ERR_INVALID_ARG
